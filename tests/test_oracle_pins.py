@@ -1,0 +1,307 @@
+"""Pins for the CPU fp64 checker: each test ties it to something other than itself
+(hand-worked numbers, closed forms, pure-Python brute force, algebraic invariants,
+numpy/scipy routines), chosen so that a dropped term, a wrong sign or index, or a
+transposed operand fails at least one of them.  CPU only."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from paper_2605_10453_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bits(x):
+    return synth.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def rand_bits(rng, shape, scale=1.0):
+    return synth.f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+# ------------------------------------------------------------------ hand-worked example
+
+def test_worked_example_low_rank(oracle_mod):
+    g = json.load(open(os.path.join(GOLDEN, "worked_example.json")))
+    h, A, B = bits(g["h"]), bits(g["A"]), bits(g["B"])
+    # the fixture's numbers are exact in bf16
+    assert np.array_equal(synth.bf16_bits_to_f64(A), np.array(g["A"]))
+    t = oracle_mod.down_projection(h, A)
+    assert np.array_equal(t, np.array(g["t"]))
+    res = oracle_mod.slimspec_head_topk(h, A, B, 2, return_logits=True)
+    assert np.array_equal(res.z, np.array(g["z"]))
+    assert res.ids.tolist() == g["top2_ids"]
+    for i, zrow in enumerate(g["z"]):
+        lse = math.log(sum(math.exp(v) for v in zrow))
+        assert abs(res.lse[i] - lse) < 1e-12
+        for p in range(2):
+            assert abs(res.logprobs[i, p] - (zrow[g["top2_ids"][i][p]] - lse)) < 1e-6
+    res4 = oracle_mod.slimspec_head_topk(h, A, B, 4)
+    assert res4.ids.tolist() == g["top4_ids"]
+    # gaps between consecutive sorted logits, last one is +inf at k == V
+    assert np.allclose(res4.gap[0, :3], [1.0, 5.5, 4.625]) and np.isinf(res4.gap[0, 3])
+
+
+def test_worked_example_full_head(oracle_mod):
+    # W = A B of the same fixture, worked by hand:
+    # row c of W = sum_j A[c][j] B[j][:]
+    W = [[1.25, -1.5, 0.0, 1.0],        # 1*[1,-2,.5,0] + .5*[.5,1,-1,2]
+         [0.0, 4.0, -2.5, 4.0],         # -1*[1,-2,.5,0] + 2*[.5,1,-1,2]
+         [0.75, 0.5, -0.875, 2.0]]      # .25*[1,-2,.5,0] + 1*[.5,1,-1,2]
+    g = json.load(open(os.path.join(GOLDEN, "worked_example.json")))
+    h = bits(g["h"])
+    for Wm in (bits(W), np.asarray(W, dtype=np.float32)):
+        res = oracle_mod.full_head_topk(h, Wm, 2, return_logits=True)
+        assert np.array_equal(res.z, np.array(g["z"]))
+        assert res.ids.tolist() == g["top2_ids"]
+
+
+# ------------------------------------------------------------------ closed forms
+
+@pytest.mark.parametrize("V", [8192, 128256])
+def test_zero_hidden_state_gives_uniform(oracle_mod, V):
+    rng = np.random.default_rng(1)
+    d, r, k = 16, 8, 5
+    h = np.zeros((2, d), dtype=np.uint16)
+    A, B = rand_bits(rng, (d, r)), rand_bits(rng, (r, V))
+    res = oracle_mod.slimspec_head_topk(h, A, B, k)
+    assert res.ids.tolist() == [list(range(k))] * 2          # all tied: smaller id first
+    assert np.allclose(res.logprobs, -math.log(V), atol=1e-6)  # natural log
+    assert np.allclose(res.lse, math.log(V), atol=1e-12)
+    if V == 128256:
+        assert abs(res.logprobs[0, 0] - (-11.761785)) < 2e-6
+    else:
+        assert abs(res.logprobs[0, 0] - (-9.010913)) < 2e-6
+
+
+def test_one_hot_column_lse(oracle_mod):
+    d, V, a = 4, 1000, 3.0
+    h = bits([[1.0, 2.0, 0.0, -1.0]])
+    W = np.zeros((d, V), dtype=np.float32)
+    W[:, 7] = [1.0, 0.5, 9.0, -1.0]      # z_7 = 1 + 1 + 0 + 1 = 3
+    res = oracle_mod.full_head_topk(h, W, 3)
+    lse = math.log(math.exp(a) + V - 1)
+    assert abs(res.lse[0] - lse) < 1e-12
+    assert res.ids[0].tolist() == [7, 0, 1]
+    assert abs(res.logprobs[0, 0] - (a - lse)) < 1e-6
+    assert abs(res.logprobs[0, 1] - (0.0 - lse)) < 1e-6
+
+
+# ------------------------------------------------------------------ brute force, tiny
+
+def _py_head(hf, Af, Bf):
+    rows, d = len(hf), len(hf[0])
+    r, V = len(Bf), len(Bf[0])
+    out = []
+    for i in range(rows):
+        t = [sum(hf[i][c] * Af[c][j] for c in range(d)) for j in range(r)]
+        out.append([sum(t[j] * Bf[j][v] for j in range(r)) for v in range(V)])
+    return out
+
+
+def test_brute_force_tiny(oracle_mod):
+    rng = np.random.default_rng(2)
+    rows, d, r, V, k = 3, 5, 4, 7, 3
+    h, A, B = rand_bits(rng, (rows, d)), rand_bits(rng, (d, r)), rand_bits(rng, (r, V))
+    z_py = _py_head(synth.bf16_bits_to_f64(h).tolist(), synth.bf16_bits_to_f64(A).tolist(),
+                    synth.bf16_bits_to_f64(B).tolist())
+    res = oracle_mod.slimspec_head_topk(h, A, B, k, return_logits=True)
+    assert np.allclose(res.z, np.array(z_py), rtol=0, atol=1e-13)
+    for i in range(rows):
+        order = sorted(range(V), key=lambda v: (-z_py[i][v], v))
+        assert res.ids[i].tolist() == order[:k]
+        lse = math.log(sum(math.exp(x) for x in z_py[i]))
+        assert np.allclose(res.logprobs[i], [z_py[i][v] - lse for v in order[:k]], atol=1e-6)
+
+
+def test_reassociation_hA_B_equals_h_AB(oracle_mod):
+    """(h A) B = h (A B): the low-rank head equals a full head with W = A B (tiny, brute force)."""
+    rng = np.random.default_rng(3)
+    rows, d, r, V = 4, 24, 6, 40
+    h, A, B = rand_bits(rng, (rows, d)), rand_bits(rng, (d, r), d ** -0.5), rand_bits(rng, (r, V), r ** -0.5)
+    A64, B64, h64 = (synth.bf16_bits_to_f64(x) for x in (A, B, h))
+    W64 = [[sum(A64[c, j] * B64[j, v] for j in range(r)) for v in range(V)] for c in range(d)]
+    z_full = np.array([[sum(h64[i, c] * W64[c][v] for c in range(d)) for v in range(V)] for i in range(rows)])
+    res = oracle_mod.slimspec_head_topk(h, A, B, 5, return_logits=True)
+    assert np.max(np.abs(res.z - z_full)) <= 1e-12 * max(1.0, np.max(np.abs(z_full)))
+
+
+def test_identity_down_projection_reduces_to_full_head(oracle_mod):
+    """r = d and A = I: the low-rank head is the plain dense head with W = B."""
+    rng = np.random.default_rng(4)
+    rows, d, V, k = 3, 16, 300, 6
+    h, B = rand_bits(rng, (rows, d)), rand_bits(rng, (d, V), 0.25)
+    A = bits(np.eye(d))
+    lo = oracle_mod.slimspec_head_topk(h, A, B, k, return_logits=True)
+    fu = oracle_mod.full_head_topk(h, B, k, return_logits=True)
+    assert np.array_equal(lo.z, fu.z)
+    assert np.array_equal(lo.ids, fu.ids) and np.array_equal(lo.logprobs, fu.logprobs)
+
+
+def test_rank_of_low_rank_logits(oracle_mod):
+    """Feeding the d unit vectors as hidden states returns the matrix A B; its rank is at most r."""
+    rng = np.random.default_rng(5)
+    d, r, V = 12, 3, 20
+    A, B = rand_bits(rng, (d, r)), rand_bits(rng, (r, V))
+    res = oracle_mod.slimspec_head_topk(bits(np.eye(d)), A, B, 1, return_logits=True)
+    s = np.linalg.svd(res.z, compute_uv=False)
+    assert np.sum(s > 1e-10 * s[0]) == r            # generic A, B: exactly r
+    full = oracle_mod.full_head_topk(bits(np.eye(d)), rand_bits(rng, (d, V)), 1, return_logits=True)
+    assert np.linalg.matrix_rank(full.z) == d       # the full head is not rank-limited
+
+
+# ------------------------------------------------------------------ softmax / top-k invariants
+
+def test_probabilities_sum_to_one(oracle_mod):
+    cfg = synth.CONFIGS["C1"]
+    x = synth.make_inputs(cfg, 0)
+    res = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, cfg.V)       # k = V
+    p = np.exp(res.logprobs.astype(np.float64))
+    assert abs(p.sum() - 1.0) < 1e-5                                 # float32 outputs
+    ids, lp, lse, _ = oracle_mod.log_softmax_topk(np.linspace(-3, 9, 5000), 5000)
+    assert abs(np.exp(np.linspace(-3, 9, 5000) - lse).sum() - 1.0) < 1e-12
+
+
+def test_shift_invariance(oracle_mod):
+    rng = np.random.default_rng(6)
+    z = rng.standard_normal(4096) * 3
+    ids0, lp0, lse0, _ = oracle_mod.log_softmax_topk(z, 10)
+    for c in (-50.0, 7.25, 1000.0):
+        ids1, lp1, lse1, _ = oracle_mod.log_softmax_topk(z + c, 10)
+        assert np.array_equal(ids0, ids1)
+        assert np.allclose(lp0, lp1, atol=1e-5)
+        assert abs((lse1 - c) - lse0) < 1e-9
+
+
+def test_large_logits_do_not_overflow(oracle_mod):
+    z = np.array([1000.0, 999.0, -1000.0, 998.0])
+    ids, lp, lse, _ = oracle_mod.log_softmax_topk(z, 2)
+    ref = 1000.0 + math.log(1 + math.exp(-1) + math.exp(-2) + math.exp(-2000))
+    assert ids.tolist() == [0, 1] and abs(lse - ref) < 1e-12
+
+
+def test_permutation_equivariance(oracle_mod):
+    rng = np.random.default_rng(7)
+    rows, d, r, V, k = 2, 32, 8, 500, 7
+    h, A, B = rand_bits(rng, (rows, d)), rand_bits(rng, (d, r), d ** -0.5), rand_bits(rng, (r, V), r ** -0.5)
+    base = oracle_mod.slimspec_head_topk(h, A, B, k)
+    perm = rng.permutation(V)                      # new column v holds old column perm[v]
+    res = oracle_mod.slimspec_head_topk(h, A, np.ascontiguousarray(B[:, perm]), k)
+    assert np.array_equal(perm[res.ids], base.ids)
+    assert np.array_equal(res.logprobs, base.logprobs)
+
+
+def test_k1_is_argmax_and_kV_is_sorted_log_softmax(oracle_mod):
+    rng = np.random.default_rng(8)
+    z = rng.standard_normal(3000)
+    ids, lp, lse, _ = oracle_mod.log_softmax_topk(z, 1)
+    assert ids[0] == int(np.argmax(z))
+    ids, lp, lse, _ = oracle_mod.log_softmax_topk(z, 3000)
+    order = np.argsort(-z, kind="stable")
+    assert np.array_equal(ids, order)
+    assert np.allclose(lp, scipy.special.log_softmax(z)[order], atol=1e-6)
+    assert abs(lse - scipy.special.logsumexp(z)) < 1e-12
+
+
+def test_tie_rule_smaller_id_first(oracle_mod):
+    z = np.array([1.0, 5.0, 5.0, 0.0, 5.0, 2.0, 2.0])
+    ids, lp, _, gap = oracle_mod.log_softmax_topk(z, 5)
+    assert ids.tolist() == [1, 2, 4, 5, 6]
+    assert lp[0] == lp[1] == lp[2]
+    assert gap.tolist() == [0.0, 0.0, 3.0, 0.0, 1.0]
+
+
+def test_planted_identical_columns_tie_exactly(oracle_mod):
+    cfg = synth.small_config(rows=3, d=64, r=16, V=1024, k=4)
+    x = synth.make_inputs(cfg, 11)
+    t = oracle_mod.down_projection(x.h, x.A)
+    V = cfg.V
+    synth.plant_identical_columns(x.B, 0.35 * t[0] / math.sqrt(cfg.r) * 4, [0, V // 2, V - 1])
+    res = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, cfg.k, return_logits=True)
+    assert res.ids[0, :3].tolist() == [0, V // 2, V - 1]
+    assert res.z[0, 0] == res.z[0, V // 2] == res.z[0, V - 1]
+    assert res.logprobs[0, 0] == res.logprobs[0, 1] == res.logprobs[0, 2]
+    for k in (1, 2, 3):                               # tie straddling the k boundary
+        assert oracle_mod.slimspec_head_topk(x.h, x.A, x.B, k).ids[0].tolist() == [0, V // 2, V - 1][:k]
+
+
+# ------------------------------------------------------------------ library cross-checks
+
+@pytest.mark.parametrize("name,seed", [("C1", 0), ("C2", 0), ("C2", 3)])
+def test_against_numpy_float64(oracle_mod, name, seed):
+    cfg = synth.CONFIGS[name]
+    x = synth.make_inputs(cfg, seed)
+    res = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, cfg.k, return_logits=True)
+    h64, A64, B64 = (synth.bf16_bits_to_f64(a) for a in (x.h, x.A, x.B))
+    z = (h64 @ A64) @ B64
+    assert np.max(np.abs(res.z - z)) < 1e-10
+    order = np.argsort(-z[0], kind="stable")[: cfg.k]
+    assert np.array_equal(res.ids[0], order)
+    lse = scipy.special.logsumexp(z[0])
+    assert abs(res.lse[0] - lse) < 1e-10
+    assert np.allclose(res.logprobs[0], z[0][order] - lse, atol=2e-6)
+    assert np.allclose(res.gap[0, :-1], -np.diff(z[0][order]), atol=1e-10)
+
+
+def test_multi_row_matches_single_row_and_numpy(oracle_mod):
+    cfg = synth.small_config(rows=9, d=96, r=24, V=3001, k=6, peaked_every=4)
+    x = synth.make_inputs(cfg, 5, with_full_head=True)
+    res = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, cfg.k, return_logits=True)
+    h64, A64, B64, W64 = (synth.bf16_bits_to_f64(a) for a in (x.h, x.A, x.B, x.W))
+    assert np.max(np.abs(res.z - (h64 @ A64) @ B64)) < 1e-11
+    for i in range(cfg.rows):
+        one = oracle_mod.slimspec_head_topk(x.h[i:i + 1], x.A, x.B, cfg.k)
+        assert np.array_equal(one.ids[0], res.ids[i]) and np.array_equal(one.logprobs[0], res.logprobs[i])
+    full = oracle_mod.full_head_topk(x.h, x.W, cfg.k, return_logits=True)
+    assert np.max(np.abs(full.z - h64 @ W64)) < 1e-11
+    Wf = synth.bf16_bits_to_f32(x.W)
+    full32 = oracle_mod.full_head_topk(x.h, Wf, cfg.k, return_logits=True)
+    assert np.array_equal(full32.z, full.z)
+
+
+def test_logits_at_matches_full_rows(oracle_mod):
+    cfg = synth.small_config(rows=5, d=40, r=8, V=777, k=3)
+    x = synth.make_inputs(cfg, 2, with_full_head=True)
+    res = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, cfg.k, return_logits=True)
+    ri = np.array([0, 4, 2, 2, 1]); ci = np.array([0, 776, 5, 400, 13])
+    assert np.array_equal(oracle_mod.slimspec_logits_at(x.h, x.A, x.B, ri, ci), res.z[ri, ci])
+    full = oracle_mod.full_head_topk(x.h, x.W, cfg.k, return_logits=True)
+    assert np.allclose(oracle_mod.full_logits_at(x.h, x.W, ri, ci), full.z[ri, ci], atol=1e-13)
+
+
+def test_config1_full_head_with_materialised_W_agrees(oracle_mod):
+    """Config 1's comparator: W = A B rounded once to fp32; both heads must pick the same tokens."""
+    cfg = synth.CONFIGS["C1"]
+    x = synth.make_inputs(cfg, 0)
+    W = (synth.bf16_bits_to_f64(x.A) @ synth.bf16_bits_to_f64(x.B)).astype(np.float32)
+    lo = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, cfg.k)
+    fu = oracle_mod.full_head_topk(x.h, W, cfg.k)
+    assert np.array_equal(lo.ids, fu.ids)
+    assert np.allclose(lo.logprobs, fu.logprobs, atol=1e-5)
+
+
+def test_bad_arguments_are_rejected(oracle_mod):
+    x = synth.make_inputs(synth.small_config(1, 8, 4, 16, 2), 0)
+    with pytest.raises(RuntimeError):
+        oracle_mod.slimspec_head_topk(x.h, x.A, x.B, 17)     # k > V
+    with pytest.raises(RuntimeError):
+        oracle_mod.slimspec_head_topk(x.h, x.A, x.B, 0)
+
+
+# ------------------------------------------------------------------ cost identity of section 4.1
+
+def test_cost_ratio_identity():
+    g = json.load(open(os.path.join(GOLDEN, "cost_ratio.json")))
+    for c in g["identity_cases"]:
+        d, r, V = c["d"], c["r"], c["V"]
+        lhs = (r * d + V * r) / (V * d)
+        rhs = (r / d) * (1 + d / V)
+        assert abs(lhs - rhs) < 1e-15 and abs(lhs - c["ratio"]) < 1e-9
+        assert abs(lhs - r / d) / (r / d) < 0.07          # "approximately r/d" since V >> d
+    e = g["paper_eq4_case"]
+    gain = e["rho_tau"] * (1 + e["kappa"]) / (1 + e["nu"] * e["kappa"])
+    assert abs(gain - e["printed_gain"]) < 0.02
