@@ -1,0 +1,109 @@
+/*
+ * slimspec.h - C ABI of the MI355X (gfx950) drafter LM-head library.
+ *
+ * The operation (paper section 4.1, "LM-head architecture"): a speculative-decoding
+ * drafter maps a hidden state h in R^d to logits over the whole target vocabulary,
+ * either with the standard full head  z = W_full h  (W_full in R^{V x d}) or with the
+ * low-rank head  z = W_up (W_down h)  (W_down in R^{r x d}, W_up in R^{V x r}, r < d,
+ * typically d/8), which cuts the cost from O(Vd) to O(rd + Vr) while keeping all V
+ * logits.  This library evaluates either head for a batch of rows and reduces every
+ * logit row, in the same pass and without ever writing a rows x V tensor to memory, to
+ * the k most likely token ids and their natural-log probabilities
+ *     logprob_v = z_v - log sum_u exp(z_u)          (softmax over the full vocabulary,
+ *                                                    section 3.2; temperature 1, no bias)
+ *
+ * Matrix layout (row-vector form; all row-major, all DEVICE memory):
+ *     h [rows, d]  bf16     hidden states, one row per drafted position
+ *     A [d, r]     bf16     A = W_down^T        t = h A
+ *     B [r, V]     bf16     B = W_up^T          z = t B
+ *     W [d, V]     bf16|f32 W = W_full^T        z = h W
+ * bf16 values are raw 16-bit patterns (upper half of an IEEE fp32).
+ *
+ * Outputs (DEVICE memory, caller-owned):
+ *     out_ids      [rows, k] int32   vocabulary index (column of B / W) of the p-th
+ *                                    largest logit of the row, p = 0..k-1
+ *     out_logprobs [rows, k] float   its log-probability
+ * Order: descending logit; equal logits: smaller id first.  Logits are accumulated in
+ * fp32 from exact bf16 products; t is carried with at least 16 significant bits.
+ *
+ * Ownership / asynchrony: every pointer is caller-owned; the library allocates and
+ * frees nothing, keeps nothing between calls, and never synchronises.  All work is
+ * enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ * the call returns immediately; outputs are valid once the stream has been
+ * synchronised.  `workspace` is device scratch of at least
+ * slimspec_workspace_bytes(...) bytes, 256-byte aligned; its contents are undefined
+ * after the call and two calls that overlap in time must not share it.  `shape` is read
+ * on the host during the call only.
+ *
+ * Errors: 0 on success, a negative slimspec_status otherwise.  Arguments are validated
+ * on the host before any HIP call, and nothing is enqueued or written when validation
+ * fails.  NaN/Inf inputs are not checked; results are then unspecified.
+ */
+#ifndef SLIMSPEC_H
+#define SLIMSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct slimspec_shape {
+    int32_t rows;   /* number of hidden-state rows in the call, >= 1            */
+    int32_t d;      /* drafter hidden size, multiple of 8                        */
+    int32_t r;      /* rank of the low-rank head, multiple of 8 (ignored by full_head_topk) */
+    int32_t V;      /* vocabulary size, multiple of 8                            */
+} slimspec_shape;
+
+typedef enum slimspec_dtype {
+    SLIMSPEC_BF16 = 0,
+    SLIMSPEC_F32 = 1
+} slimspec_dtype;
+
+typedef enum slimspec_status {
+    SLIMSPEC_OK = 0,
+    SLIMSPEC_INVALID_ARGUMENT = -1,    /* null pointer, non-positive size, k < 1, k > V, bad dtype   */
+    SLIMSPEC_UNSUPPORTED = -2,         /* k > SLIMSPEC_KMAX, d/r/V not a multiple of 8, misaligned   */
+    SLIMSPEC_WORKSPACE_TOO_SMALL = -3,
+    SLIMSPEC_HIP_ERROR = -4            /* a launch failed; text via slimspec_last_hip_error()        */
+} slimspec_status;
+
+#define SLIMSPEC_KMAX 64
+#define SLIMSPEC_VERSION 1
+
+/* Library version (SLIMSPEC_VERSION it was built with).  Host only, no HIP call. */
+int slimspec_version(void);
+
+/* Device scratch needed by slimspec_head_topk / full_head_topk for this shape and k
+ * (the larger of the two).  Pure host function, no HIP call.  Returns 0 when the
+ * shape or k is invalid or unsupported. */
+size_t slimspec_workspace_bytes(const slimspec_shape *shape, int32_t k);
+
+/* Low-rank head (second display of section 4.1): z = (h A) B, then per-row top-k ids
+ * and log-probabilities.  h, A, B: device, bf16.  All device pointers 16-byte aligned. */
+int slimspec_head_topk(const void *h, const void *A, const void *B,
+                       const slimspec_shape *shape, int32_t k,
+                       int32_t *out_ids, float *out_logprobs,
+                       void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/* Full head (first display of section 4.1): z = h W, same reduction.  W is bf16 or
+ * fp32 as named by w_dtype; shape->r is ignored. */
+int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
+                   const slimspec_shape *shape, int32_t k,
+                   int32_t *out_ids, float *out_logprobs,
+                   void *workspace, size_t workspace_bytes,
+                   void *stream);
+
+/* Human-readable name of a status code (static storage). */
+const char *slimspec_status_string(int status);
+
+/* Text of the HIP error behind the calling thread's most recent SLIMSPEC_HIP_ERROR
+ * ("" if none).  Static/thread-local storage. */
+const char *slimspec_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIMSPEC_H */

@@ -1,0 +1,187 @@
+"""Thin ctypes binding over libslimspec.so: argument marshalling only.
+
+Every step of the head (down-projection, vocabulary projection, online
+log-sum-exp, top-k, merge) runs in the library's HIP kernels; torch is used here
+for device memory and the current stream, nothing else.  There is no CPU or
+PyTorch fallback: if the library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch  # must be imported before the library so that both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libslimspec.so")
+
+SLIMSPEC_BF16 = 0
+SLIMSPEC_F32 = 1
+SLIMSPEC_KMAX = 64
+
+STATUS_OK = 0
+STATUS_INVALID_ARGUMENT = -1
+STATUS_UNSUPPORTED = -2
+STATUS_WORKSPACE_TOO_SMALL = -3
+STATUS_HIP_ERROR = -4
+
+EXPORTED_SYMBOLS = (
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "full_head_topk",
+    "slimspec_status_string", "slimspec_last_hip_error",
+)
+
+
+class SlimspecShape(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int32), ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("V", ctypes.c_int32)]
+
+
+class SlimspecError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"slimspec status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libslimspec.so (built in-tree by build.py); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2605_10453_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    shp = ctypes.POINTER(SlimspecShape)
+    lib.slimspec_version.restype = ctypes.c_int
+    lib.slimspec_version.argtypes = []
+    lib.slimspec_workspace_bytes.restype = sz
+    lib.slimspec_workspace_bytes.argtypes = [shp, i32]
+    lib.slimspec_head_topk.restype = ctypes.c_int
+    lib.slimspec_head_topk.argtypes = [vp, vp, vp, shp, i32, vp, vp, vp, sz, vp]
+    lib.full_head_topk.restype = ctypes.c_int
+    lib.full_head_topk.argtypes = [vp, vp, ctypes.c_int, shp, i32, vp, vp, vp, sz, vp]
+    lib.slimspec_status_string.restype = ctypes.c_char_p
+    lib.slimspec_status_string.argtypes = [ctypes.c_int]
+    lib.slimspec_last_hip_error.restype = ctypes.c_char_p
+    lib.slimspec_last_hip_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().slimspec_status_string(status).decode()
+
+
+def _raise(status: int):
+    lib = load_library()
+    text = lib.slimspec_status_string(status).decode()
+    if status == STATUS_HIP_ERROR:
+        text += ": " + lib.slimspec_last_hip_error().decode()
+    raise SlimspecError(status, text)
+
+
+def slimspec_version() -> int:
+    return int(load_library().slimspec_version())
+
+
+def slimspec_workspace_bytes(rows: int, d: int, r: int, V: int, k: int) -> int:
+    shape = SlimspecShape(rows, d, r, V)
+    return int(load_library().slimspec_workspace_bytes(ctypes.byref(shape), k))
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _dev_ptr(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _outputs(rows, k, device, out_ids, out_logprobs):
+    if out_ids is None:
+        out_ids = torch.empty((rows, k), dtype=torch.int32, device=device)
+    if out_logprobs is None:
+        out_logprobs = torch.empty((rows, k), dtype=torch.float32, device=device)
+    if out_ids.dtype != torch.int32 or out_logprobs.dtype != torch.float32:
+        raise ValueError("out_ids must be int32 and out_logprobs float32")
+    if tuple(out_ids.shape) != (rows, k) or tuple(out_logprobs.shape) != (rows, k):
+        raise ValueError("outputs must be [rows, k]")
+    return out_ids, out_logprobs
+
+
+def _workspace(nbytes: int, device, workspace):
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def slimspec_head_topk(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, k: int,
+                       out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Low-rank head z = (h A) B -> per-row top-k ids and log-probabilities (device tensors).
+
+    h [rows, d], A [d, r], B [r, V]: bf16 device tensors (torch.bfloat16, or int16/uint16 bit patterns).
+    Work is enqueued on `stream` (default: torch's current stream); nothing is synchronised.
+    """
+    rows, d = h.shape
+    d2, r = A.shape
+    r2, V = B.shape
+    if d != d2 or r != r2:
+        raise ValueError("shape mismatch between h, A and B")
+    for t, n in ((h, "h"), (A, "A"), (B, "B")):
+        if t.element_size() != 2:
+            raise ValueError(f"{n} must hold bf16 (2-byte) elements")
+    out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, r, V)
+    need = int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k))
+    workspace = _workspace(need, h.device, workspace)
+    st = lib.slimspec_head_topk(_dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"), ctypes.byref(shape), k,
+                                _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+                                _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs
+
+
+def full_head_topk(h: torch.Tensor, W: torch.Tensor, k: int,
+                   out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                   workspace: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Full head z = h W -> per-row top-k ids and log-probabilities.  W [d, V] is bf16 or float32."""
+    rows, d = h.shape
+    d2, V = W.shape
+    if d != d2:
+        raise ValueError("shape mismatch between h and W")
+    if h.element_size() != 2:
+        raise ValueError("h must hold bf16 (2-byte) elements")
+    if W.dtype == torch.float32:
+        w_dtype = SLIMSPEC_F32
+    elif W.element_size() == 2:
+        w_dtype = SLIMSPEC_BF16
+    else:
+        raise ValueError("W must be bf16 or float32")
+    out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, 0, V)
+    need = int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k))
+    workspace = _workspace(need, h.device, workspace)
+    st = lib.full_head_topk(_dev_ptr(h, "h"), _dev_ptr(W, "W"), w_dtype, ctypes.byref(shape), k,
+                            _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+                            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                            _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs

@@ -1,0 +1,137 @@
+// C ABI of the library (see include/slimspec.h): argument checks, workspace
+// layout, and the launch sequence for each head.  Everything before the first
+// launch is plain host arithmetic, so validation works without a GPU.
+#include "../../include/slimspec.h"
+#include "launch.hpp"
+#include <string.h>
+
+using namespace slimspec;
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int fail_hip(hipError_t e)
+{
+    const char *s = hipGetErrorString(e);
+    strncpy(g_hip_error, s ? s : "unknown HIP error", sizeof(g_hip_error) - 1);
+    g_hip_error[sizeof(g_hip_error) - 1] = 0;
+    return SLIMSPEC_HIP_ERROR;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape / k checks common to both heads.  Returns SLIMSPEC_OK or the error.
+int check_shape(HeadKind kind, const slimspec_shape *s, int32_t k)
+{
+    if (!s) return SLIMSPEC_INVALID_ARGUMENT;
+    if (s->rows <= 0 || s->d <= 0 || s->V <= 0) return SLIMSPEC_INVALID_ARGUMENT;
+    if (kind == HeadKind::LowRank && s->r <= 0) return SLIMSPEC_INVALID_ARGUMENT;
+    if (k < 1 || k > s->V) return SLIMSPEC_INVALID_ARGUMENT;
+    if (k > SLIMSPEC_KMAX) return SLIMSPEC_UNSUPPORTED;
+    if ((s->d & 7) || (s->V & 7)) return SLIMSPEC_UNSUPPORTED;
+    if (kind == HeadKind::LowRank && (s->r & 7)) return SLIMSPEC_UNSUPPORTED;
+    // index arithmetic inside the kernels is 32-bit for ids and 64-bit for offsets
+    if ((int64_t)s->V > (int64_t)1 << 30) return SLIMSPEC_UNSUPPORTED;
+    int chunks = (s->V + kChunkCols - 1) / kChunkCols;
+    if (merge_lds_bytes(chunks, k) > kMergeLdsLimit) return SLIMSPEC_UNSUPPORTED;
+    return SLIMSPEC_OK;
+}
+
+int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_is_f32,
+             const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
+             void *workspace, size_t workspace_bytes, void *stream)
+{
+    int st = check_shape(kind, shape, k);
+    if (st != SLIMSPEC_OK) return st;
+    if (!h || !M || !out_ids || !out_logprobs || !workspace) return SLIMSPEC_INVALID_ARGUMENT;
+    if (kind == HeadKind::LowRank && !A) return SLIMSPEC_INVALID_ARGUMENT;
+    if (!aligned16(h) || !aligned16(M) || (A && !aligned16(A)) || !aligned16(workspace))
+        return SLIMSPEC_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(out_ids) & 3u) || (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
+        return SLIMSPEC_UNSUPPORTED;
+    const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
+    if (workspace_bytes < p.bytes) return SLIMSPEC_WORKSPACE_TOO_SMALL;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    float *x = reinterpret_cast<float *>(ws + p.off_x);
+    float *down_part = reinterpret_cast<float *>(ws + p.off_down_part);
+    float2 *part_ms = reinterpret_cast<float2 *>(ws + p.off_part_ms);
+    float *part_val = reinterpret_cast<float *>(ws + p.off_part_val);
+    int *part_id = reinterpret_cast<int *>(ws + p.off_part_id);
+    const uint16_t *hb = static_cast<const uint16_t *>(h);
+
+    // Rows are processed in groups of kGemvMaxRows by the streaming kernels; the
+    // groups reuse the small x / down-projection scratch in stream order.
+    for (int row0 = 0; row0 < p.rows; row0 += kGemvMaxRows) {
+        const int rows_here = (p.rows - row0 < kGemvMaxRows) ? p.rows - row0 : kGemvMaxRows;
+        hipError_t e;
+        if (kind == HeadKind::LowRank)
+            e = launch_down_projection(hb + (size_t)row0 * p.d, static_cast<const uint16_t *>(A),
+                                       down_part, x, rows_here, p.d, p.r, p.down_splits, s);
+        else
+            e = launch_widen_rows(hb + (size_t)row0 * p.d, x, rows_here * p.d, s);
+        if (e != hipSuccess) return fail_hip(e);
+        e = launch_stream_topk(x, M, m_is_f32, part_ms, part_val, part_id,
+                               rows_here, row0, p.K, p.V, p.chunks, k, s);
+        if (e != hipSuccess) return fail_hip(e);
+    }
+    hipError_t e = launch_merge(part_ms, part_val, part_id, p.rows, p.chunks, k, out_ids, out_logprobs, s);
+    if (e != hipSuccess) return fail_hip(e);
+    return SLIMSPEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int slimspec_version(void) { return SLIMSPEC_VERSION; }
+
+size_t slimspec_workspace_bytes(const slimspec_shape *shape, int32_t k)
+{
+    if (!shape) return 0;
+    size_t need = 0;
+    if (check_shape(HeadKind::Full, shape, k) == SLIMSPEC_OK)
+        need = make_plan(HeadKind::Full, shape->rows, shape->d, shape->r, shape->V, k).bytes;
+    if (check_shape(HeadKind::LowRank, shape, k) == SLIMSPEC_OK) {
+        size_t lo = make_plan(HeadKind::LowRank, shape->rows, shape->d, shape->r, shape->V, k).bytes;
+        if (lo > need) need = lo;
+    }
+    return need;
+}
+
+int slimspec_head_topk(const void *h, const void *A, const void *B,
+                       const slimspec_shape *shape, int32_t k,
+                       int32_t *out_ids, float *out_logprobs,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_head(HeadKind::LowRank, h, A, B, false, shape, k, out_ids, out_logprobs,
+                    workspace, workspace_bytes, stream);
+}
+
+int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
+                   const slimspec_shape *shape, int32_t k,
+                   int32_t *out_ids, float *out_logprobs,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
+    return run_head(HeadKind::Full, h, nullptr, W, w_dtype == SLIMSPEC_F32, shape, k, out_ids, out_logprobs,
+                    workspace, workspace_bytes, stream);
+}
+
+const char *slimspec_status_string(int status)
+{
+    switch (status) {
+    case SLIMSPEC_OK: return "ok";
+    case SLIMSPEC_INVALID_ARGUMENT: return "invalid argument";
+    case SLIMSPEC_UNSUPPORTED: return "unsupported shape, k or alignment";
+    case SLIMSPEC_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case SLIMSPEC_HIP_ERROR: return "HIP error";
+    default: return "unknown status";
+    }
+}
+
+const char *slimspec_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+"""The C-ABI library without a GPU: it loads, exports every symbol the header declares,
+sizes workspaces, and rejects bad arguments before any HIP call.  CPU only."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2605_10453_amd import binding
+    return binding.load_library(), binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "slimspec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+
+
+def test_header_symbols_are_exported(lib):
+    l, binding = lib
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTED_SYMBOLS), names
+    for n in names:
+        assert getattr(l, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    l, binding = lib
+    assert binding.slimspec_version() == 1
+    assert binding.status_string(0) == "ok"
+    for s in (-1, -2, -3, -4):
+        assert binding.status_string(s) not in ("ok", "unknown status")
+    assert binding.status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes(lib):
+    _, b = lib
+    w1 = b.slimspec_workspace_bytes(1, 4096, 512, 128256, 10)
+    w512 = b.slimspec_workspace_bytes(512, 4096, 512, 128256, 10)
+    assert 0 < w1 < w512 and w1 % 256 == 0
+    assert b.slimspec_workspace_bytes(1, 4096, 512, 128256, 64) > w1
+    # invalid or unsupported shapes -> 0
+    assert b.slimspec_workspace_bytes(0, 4096, 512, 128256, 10) == 0
+    assert b.slimspec_workspace_bytes(1, 4096, 512, 128256, 0) == 0
+    assert b.slimspec_workspace_bytes(1, 4096, 512, 128256, 65) == 0
+    assert b.slimspec_workspace_bytes(1, 4096, 512, 128257, 10) == 0
+    assert b.slimspec_workspace_bytes(1, 4100, 512, 128256, 10) == 0
+    # r is ignored by the full head: a bad r still leaves the full-head size
+    assert b.slimspec_workspace_bytes(1, 4096, 0, 128256, 10) > 0
+
+
+def test_argument_validation_without_gpu(lib):
+    l, b = lib
+    fake = ctypes.c_void_p(0x1000)     # never dereferenced: validation fails first
+    null = ctypes.c_void_p(0)
+
+    def low(shape, k, h=fake, A=fake, B=fake, ids=fake, lp=fake, ws=fake, wsb=1 << 40):
+        return l.slimspec_head_topk(h, A, B, ctypes.byref(shape) if shape else None, k, ids, lp, ws, wsb, None)
+
+    def full(shape, k, dtype=0, h=fake, W=fake, ids=fake, lp=fake, ws=fake, wsb=1 << 40):
+        return l.full_head_topk(h, W, dtype, ctypes.byref(shape) if shape else None, k, ids, lp, ws, wsb, None)
+
+    S = b.SlimspecShape
+    good = S(1, 4096, 512, 128256)
+    assert low(None, 10) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 10, h=null) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 10, A=null) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 10, B=null) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 10, ids=null) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 10, lp=null) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 10, ws=null) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 0) == b.STATUS_INVALID_ARGUMENT
+    assert low(S(1, 64, 8, 16), 17) == b.STATUS_INVALID_ARGUMENT            # k > V
+    assert low(S(0, 4096, 512, 128256), 10) == b.STATUS_INVALID_ARGUMENT
+    assert low(S(1, -8, 512, 128256), 10) == b.STATUS_INVALID_ARGUMENT
+    assert low(S(1, 4096, 0, 128256), 10) == b.STATUS_INVALID_ARGUMENT
+    assert low(good, 65) == b.STATUS_UNSUPPORTED                            # k > KMAX
+    assert low(S(1, 4096, 512, 128260), 10) == b.STATUS_UNSUPPORTED         # V % 8
+    assert low(S(1, 4100, 512, 128256), 10) == b.STATUS_UNSUPPORTED         # d % 8
+    assert low(S(1, 4096, 516, 128256), 10) == b.STATUS_UNSUPPORTED         # r % 8
+    assert low(good, 10, h=ctypes.c_void_p(0x1004)) == b.STATUS_UNSUPPORTED  # misaligned
+    assert low(good, 10, wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
+    assert full(good, 10, dtype=7) == b.STATUS_INVALID_ARGUMENT
+    assert full(good, 10, W=null) == b.STATUS_INVALID_ARGUMENT
+    assert full(S(1, 4096, 0, 128256), 10, wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL   # r ignored
+    assert full(S(1, 4096, 0, 128256), 0) == b.STATUS_INVALID_ARGUMENT
+
+
+def test_product_path_does_not_touch_the_checker():
+    """Neither the package nor the C/HIP sources may import, include or call anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2605_10453_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f), errors="ignore").read()
+                assert "oracle" not in text.lower(), f"{f} mentions the checker"
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2605_10453_amd" not in text and "libslimspec" not in text

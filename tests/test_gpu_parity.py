@@ -1,0 +1,219 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 checker on the
+same seeded inputs.  Bar: ids identical except where the checker's logits are within 1e-3;
+log-probabilities within 2e-2 absolute."""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2605_10453_amd import synth
+from parity_util import compare_with_oracle, to_dev_bf16, to_dev_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2605_10453_amd import binding
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    binding.load_library()
+    return torch, binding
+
+
+def run_low_rank(gpu, x, k):
+    torch, b = gpu
+    ids, lp = b.slimspec_head_topk(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), k)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), lp.cpu().numpy()
+
+
+def run_full(gpu, h_bits, W, k):
+    torch, b = gpu
+    Wd = to_dev_f32(W) if W.dtype == np.float32 else to_dev_bf16(W)
+    ids, lp = b.full_head_topk(to_dev_bf16(h_bits), Wd, k)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), lp.cpu().numpy()
+
+
+def check_low_rank(gpu, oracle_mod, x, k, exact_rows=()):
+    print(f"low-rank case rows={x.cfg.rows} d={x.cfg.d} r={x.cfg.r} V={x.cfg.V} k={k} seed={x.seed}", flush=True)
+    g_ids, g_lp = run_low_rank(gpu, x, k)
+    ora = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, k)
+    z_at = lambda ri, ci: oracle_mod.slimspec_logits_at(x.h, x.A, x.B, ri, ci)
+    n_exempt, err = compare_with_oracle(g_ids, g_lp, ora.ids, ora.lse, z_at, x.cfg.V)
+    for i in exact_rows:
+        assert np.array_equal(g_ids[i], ora.ids[i]), (i, g_ids[i], ora.ids[i])
+    return g_ids, g_lp, ora, n_exempt
+
+
+def check_full(gpu, oracle_mod, h, W, k, rows_subset=None):
+    print(f"full-head case rows={h.shape[0]} d={h.shape[1]} V={W.shape[1]} k={k} W={W.dtype}", flush=True)
+    g_ids, g_lp = run_full(gpu, h, W, k)
+    if rows_subset is not None:
+        hs = np.ascontiguousarray(h[rows_subset])
+        g_ids, g_lp = g_ids[rows_subset], g_lp[rows_subset]
+    else:
+        hs = h
+    ora = oracle_mod.full_head_topk(hs, W, k)
+    z_at = lambda ri, ci: oracle_mod.full_logits_at(hs, W, ri, ci)
+    compare_with_oracle(g_ids, g_lp, ora.ids, ora.lse, z_at, W.shape[1])
+    return g_ids, g_lp, ora
+
+
+# ------------------------------------------------------------------ small shapes, several tiles + ragged tails
+
+SMALL = [
+    # rows, d,   r,   V,     k
+    (1, 256, 32, 8192, 8),          # config 1
+    (1, 40, 24, 520, 5),            # one full chunk + 8 columns; d, r not multiples of 32
+    (1, 64, 8, 8, 8),               # k == V, a single lane of a single chunk
+    (1, 64, 16, 72, 64),            # k = KMAX with fewer valid columns per lane group than k
+    (2, 128, 16, 5000, 1),          # k = 1 is the argmax
+    (3, 200, 40, 3072, 16),
+    (4, 512, 64, 10248, 10),
+    (7, 264, 72, 1544, 33),
+    (8, 1024, 128, 20000, 10),
+    (9, 96, 24, 2056, 7),           # one row more than a row group
+    (17, 128, 32, 4104, 12),        # three row groups
+    (40, 256, 32, 1032, 3),
+]
+
+
+@pytest.mark.parametrize("rows,d,r,V,k", SMALL)
+def test_low_rank_small(gpu, oracle_mod, rows, d, r, V, k):
+    x = synth.make_inputs(synth.small_config(rows, d, r, V, k, peaked_every=5), seed=rows * 1000 + k)
+    check_low_rank(gpu, oracle_mod, x, k)
+
+
+@pytest.mark.parametrize("rows,d,r,V,k", SMALL[:8])
+@pytest.mark.parametrize("w_f32", [False, True])
+def test_full_head_small(gpu, oracle_mod, rows, d, r, V, k, w_f32):
+    x = synth.make_inputs(synth.small_config(rows, d, r, V, k), seed=77 + rows, with_full_head=True)
+    W = synth.bf16_bits_to_f32(x.W) if w_f32 else x.W
+    check_full(gpu, oracle_mod, x.h, W, k)
+
+
+def test_config1_both_heads_agree(gpu, oracle_mod):
+    """Config 1: the full-head comparator uses W = A B materialised in fp32."""
+    cfg = synth.CONFIGS["C1"]
+    x = synth.make_inputs(cfg, 0)
+    g_ids, g_lp, ora, _ = check_low_rank(gpu, oracle_mod, x, cfg.k)
+    W = (synth.bf16_bits_to_f64(x.A) @ synth.bf16_bits_to_f64(x.B)).astype(np.float32)
+    f_ids, f_lp, _ = check_full(gpu, oracle_mod, x.h, W, cfg.k)
+    assert np.array_equal(f_ids, g_ids)
+    assert np.allclose(f_lp, g_lp, atol=1e-3)
+
+
+# ------------------------------------------------------------------ degenerate cases
+
+def test_zero_hidden_state_all_tied(gpu, oracle_mod):
+    """h = 0: every logit is exactly 0, so ids must be 0..k-1 and every logprob -ln V."""
+    cfg = synth.small_config(rows=3, d=64, r=16, V=4104, k=9)
+    x = synth.make_inputs(cfg, 1)
+    x.h[:] = 0
+    g_ids, g_lp = run_low_rank(gpu, x, cfg.k)
+    assert g_ids.tolist() == [list(range(cfg.k))] * 3
+    assert np.allclose(g_lp, -math.log(cfg.V), atol=1e-4)
+
+
+@pytest.mark.parametrize("rows", [1, 6])
+def test_planted_exact_ties(gpu, oracle_mod, rows):
+    cfg = synth.small_config(rows=rows, d=256, r=64, V=6152, k=5)
+    x = synth.make_inputs(cfg, 21)
+    V = cfg.V
+    t = oracle_mod.down_projection(x.h, x.A)
+    synth.plant_identical_columns(x.B, 0.35 * t[0] / math.sqrt(cfg.r) * 2, [0, V // 2, V - 1])
+    g_ids, g_lp, ora, _ = check_low_rank(gpu, oracle_mod, x, cfg.k, exact_rows=[0])
+    assert g_ids[0, :3].tolist() == [0, V // 2, V - 1]
+    assert g_lp[0, 0] == g_lp[0, 1] == g_lp[0, 2]
+    for k in (1, 2, 3):
+        ids, _ = run_low_rank(gpu, x, k)
+        assert ids[0].tolist() == [0, V // 2, V - 1][:k]
+
+
+def test_run_to_run_determinism(gpu):
+    cfg = synth.small_config(rows=5, d=512, r=64, V=20000, k=10)
+    x = synth.make_inputs(cfg, 3)
+    a = run_low_rank(gpu, x, cfg.k)
+    b = run_low_rank(gpu, x, cfg.k)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+
+
+def test_side_stream_and_caller_buffers(gpu, oracle_mod):
+    torch, b = gpu
+    cfg = synth.small_config(rows=2, d=256, r=32, V=9000, k=6)
+    x = synth.make_inputs(cfg, 4)
+    h, A, B = to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B)
+    need = b.slimspec_workspace_bytes(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k)
+    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda")      # poisoned scratch
+    ids = torch.full((cfg.rows, cfg.k), -7, dtype=torch.int32, device="cuda")
+    lp = torch.full((cfg.rows, cfg.k), float("nan"), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    b.slimspec_head_topk(h, A, B, cfg.k, out_ids=ids, out_logprobs=lp, workspace=ws, stream=s)
+    s.synchronize()
+    ora = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, cfg.k)
+    z_at = lambda ri, ci: oracle_mod.slimspec_logits_at(x.h, x.A, x.B, ri, ci)
+    compare_with_oracle(ids.cpu().numpy(), lp.cpu().numpy(), ora.ids, ora.lse, z_at, cfg.V)
+    # too small a workspace is refused and nothing is written
+    ids.fill_(-7)
+    with pytest.raises(b.SlimspecError) as e:
+        b.slimspec_head_topk(h, A, B, cfg.k, out_ids=ids, out_logprobs=lp, workspace=ws[:1024])
+    assert e.value.status == b.STATUS_WORKSPACE_TOO_SMALL
+    torch.cuda.synchronize()
+    assert int((ids == -7).sum()) == ids.numel()
+
+
+# ------------------------------------------------------------------ the five workloads at full size
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_config2_low_rank(gpu, oracle_mod, seed):
+    cfg = synth.CONFIGS["C2"]
+    check_low_rank(gpu, oracle_mod, synth.make_inputs(cfg, seed), cfg.k)
+
+
+def test_config2_full_head(gpu, oracle_mod):
+    cfg = synth.CONFIGS["C2"]
+    x = synth.make_inputs(cfg, 0, with_full_head=True)
+    check_full(gpu, oracle_mod, x.h, x.W, cfg.k)
+
+
+def test_config3_both_heads(gpu, oracle_mod):
+    cfg = synth.CONFIGS["C3"]
+    x = synth.make_inputs(cfg, 0, with_full_head=True)
+    check_low_rank(gpu, oracle_mod, x, cfg.k)
+    check_full(gpu, oracle_mod, x.h, x.W, cfg.k)
+
+
+@pytest.mark.parametrize("name", ["C4", "C4_r256", "C4_r1024"])
+def test_config4_low_rank(gpu, oracle_mod, name):
+    cfg = synth.CONFIGS[name]
+    _, _, _, n_exempt = check_low_rank(gpu, oracle_mod, synth.make_inputs(cfg, 0), cfg.k)
+    print(f"{name}: {n_exempt} positions used the tie exemption", flush=True)
+
+
+def test_config4_full_head_row_subset(gpu, oracle_mod):
+    """The full-head checker costs 0.5 G fp64 MACs per row: all 512 rows run on the GPU,
+    a fixed subset (first 16 rows and every peaked row) is checked."""
+    cfg = synth.CONFIGS["C4"]
+    x = synth.make_inputs(cfg, 0, with_full_head=True)
+    subset = sorted(set(range(16)) | set(range(0, cfg.rows, cfg.peaked_every)))
+    check_full(gpu, oracle_mod, x.h, x.W, cfg.k, rows_subset=np.array(subset))
+
+
+def test_config5_with_planted_ties(gpu, oracle_mod):
+    cfg = synth.CONFIGS["C5"]
+    x = synth.make_inputs(cfg, 0, with_full_head=True)
+    V = cfg.V
+    t = oracle_mod.down_projection(x.h[:1], x.A)
+    synth.plant_identical_columns(x.B, 0.35 * t[0] / math.sqrt(cfg.r), [0, V // 2, V - 1])
+    g_ids, g_lp, ora, _ = check_low_rank(gpu, oracle_mod, x, cfg.k, exact_rows=[0])
+    assert g_ids[0, :3].tolist() == [0, V // 2, V - 1]
+    assert g_lp[0, 0] == g_lp[0, 1] == g_lp[0, 2]
+    # full head of the same workload, ties planted through h[0] itself
+    h0 = synth.bf16_bits_to_f64(x.h[0])
+    synth.plant_identical_columns(x.W, 0.35 * h0 / math.sqrt(cfg.d), [0, V // 2, V - 1])
+    subset = np.arange(0, cfg.rows, 8)
+    f_ids, f_lp, _ = check_full(gpu, oracle_mod, x.h, x.W, cfg.k, rows_subset=subset)
+    assert f_ids[0, :3].tolist() == [0, V // 2, V - 1]
