@@ -103,6 +103,15 @@ const char *slimspec_status_string(int status);
  * ("" if none).  Static/thread-local storage. */
 const char *slimspec_last_hip_error(void);
 
+/* Measurement aid (not part of the method): when both are non-NULL, every later call
+ * made by this host thread records `start_event` just before and `stop_event` just
+ * after its vocabulary-projection kernel (the kernel that streams B or W; for calls
+ * that run it several times, the first run) on the call's stream, so a harness can
+ * read that kernel's duration with hipEventElapsedTime.  Both are hipEvent_t handles
+ * owned by the caller and must outlive the calls.  NULL, NULL switches it off.
+ * Returns SLIMSPEC_OK, or SLIMSPEC_INVALID_ARGUMENT if exactly one is NULL. */
+int slimspec_set_timing_events(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ STATUS_HIP_ERROR = -4
 
 EXPORTED_SYMBOLS = (
     "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "full_head_topk",
-    "slimspec_status_string", "slimspec_last_hip_error",
+    "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
 
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.slimspec_status_string.argtypes = [ctypes.c_int]
     lib.slimspec_last_hip_error.restype = ctypes.c_char_p
     lib.slimspec_last_hip_error.argtypes = []
+    lib.slimspec_set_timing_events.restype = ctypes.c_int
+    lib.slimspec_set_timing_events.argtypes = [vp, vp]
     _lib = lib
     return lib
 
@@ -92,6 +94,19 @@ def slimspec_version() -> int:
 def slimspec_workspace_bytes(rows: int, d: int, r: int, V: int, k: int) -> int:
     shape = SlimspecShape(rows, d, r, V)
     return int(load_library().slimspec_workspace_bytes(ctypes.byref(shape), k))
+
+
+def slimspec_set_timing_events(start_event: Optional[torch.cuda.Event],
+                               stop_event: Optional[torch.cuda.Event]) -> None:
+    """Have later calls record the two events around their vocabulary-projection kernel (None, None: off).
+
+    The events must have been recorded once already so that their HIP handles exist.
+    """
+    a = None if start_event is None else int(start_event.cuda_event)
+    b = None if stop_event is None else int(stop_event.cuda_event)
+    st = load_library().slimspec_set_timing_events(a, b)
+    if st != STATUS_OK:
+        _raise(st)
 
 
 def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:

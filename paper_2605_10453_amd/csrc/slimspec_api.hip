@@ -10,6 +10,7 @@ using namespace slimspec;
 namespace {
 
 thread_local char g_hip_error[256] = "";
+thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 int fail_hip(hipError_t e)
 {
@@ -73,9 +74,12 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         else
             e = launch_widen_rows(hb + (size_t)row0 * p.d, x, rows_here * p.d, s);
         if (e != hipSuccess) return fail_hip(e);
+        const bool timed = g_ev_start && row0 == 0;
+        if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
         e = launch_stream_topk(x, M, m_is_f32, part_ms, part_val, part_id,
                                rows_here, row0, p.K, p.V, p.chunks, k, s);
         if (e != hipSuccess) return fail_hip(e);
+        if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
     }
     hipError_t e = launch_merge(part_ms, part_val, part_id, p.rows, p.chunks, k, out_ids, out_logprobs, s);
     if (e != hipSuccess) return fail_hip(e);
@@ -133,5 +137,13 @@ const char *slimspec_status_string(int status)
 }
 
 const char *slimspec_last_hip_error(void) { return g_hip_error; }
+
+int slimspec_set_timing_events(void *start_event, void *stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return SLIMSPEC_INVALID_ARGUMENT;
+    g_ev_start = static_cast<hipEvent_t>(start_event);
+    g_ev_stop = static_cast<hipEvent_t>(stop_event);
+    return SLIMSPEC_OK;
+}
 
 }  // extern "C"
