@@ -1,5 +1,6 @@
 // Small device helpers shared by the gfx950 kernels: bf16 unpacking, the
-// (logit desc, id asc) order, and wavefront-wide (64-lane) reductions.
+// (logit desc, id asc) order as a 64-bit key, and wavefront-wide (64-lane)
+// reductions built on DPP lane permutes (no LDS traffic, no bpermute latency).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -17,13 +18,6 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs).
-__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
 // exp(x) and ln(x) through the hardware base-2 units.
 __device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
 __device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
@@ -33,28 +27,89 @@ __device__ __forceinline__ bool ranks_before(float va, int ia, float vb, int ib)
     return (va > vb) || (va == vb && ia < ib);
 }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+// ---------------------------------------------------------------------------
+// 64-bit sort key: high word = logit mapped to an unsigned integer with the same
+// order (-0 is first turned into +0 so that equal logits give equal words), low
+// word = ~tiebreak, so that a larger key ranks first and, among equal logits,
+// the smaller tiebreak (vocabulary id or list position) ranks first.
+__device__ __forceinline__ uint32_t float_order_bits(float v) {
+    uint32_t u = __float_as_uint(v + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
-
-// Butterfly sum: the same pairing for every lane, so all lanes end with the
-// same bits and the result does not depend on timing.
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+__device__ __forceinline__ float float_from_order_bits(uint32_t o) {
+    return __uint_as_float((o & 0x80000000u) ? (o & 0x7fffffffu) : ~o);
 }
+__device__ __forceinline__ uint64_t make_key(float v, uint32_t tiebreak) {
+    return ((uint64_t)float_order_bits(v) << 32) | (uint32_t)~tiebreak;
+}
+__device__ __forceinline__ float key_value(uint64_t k) { return float_from_order_bits((uint32_t)(k >> 32)); }
+__device__ __forceinline__ uint32_t key_tiebreak(uint64_t k) { return ~(uint32_t)k; }
+constexpr uint64_t kNoKey = 0;      // ranks after every real key (a real key has a non-zero high word)
 
-// All lanes receive the (value, id) pair that ranks first among the 64 lanes.
-__device__ __forceinline__ void wave_first(float &v, int &i) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        float ov = __shfl_xor(v, off, kWave);
-        int oi = __shfl_xor(i, off, kWave);
-        if (ranks_before(ov, oi, v, i)) { v = ov; i = oi; }
+// ---------------------------------------------------------------------------
+// Lane permutes.  DPP controls: quad_perm [1,0,3,2] = 0xB1 (lane ^ 1), quad_perm
+// [2,3,0,1] = 0x4E (lane ^ 2), row_half_mirror = 0x141 (7 - lane within 8),
+// row_mirror = 0x140 (15 - lane within 16).  After the first two steps all lanes
+// of a quad agree, after the mirrors all lanes of a row of 16 agree; the two
+// gfx950 permlane swaps then exchange rows of 16 and halves of 32.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) { return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(x))); }
+
+// value held by the lane 16 (STEP == 16) or 32 (STEP == 32) positions away, xor-wise
+template <int STEP>
+__device__ __forceinline__ void swap_pair(uint32_t x, uint32_t &a, uint32_t &b) {
+    if constexpr (STEP == 16) {
+        auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        a = r[0]; b = r[1];
+    } else {
+        auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        a = r[0]; b = r[1];
     }
+}
+
+#define SLIMSPEC_WAVE_REDUCE_F32(NAME, OP)                                            \
+    __device__ __forceinline__ float NAME(float v) {                                  \
+        v = OP(v, dpp_f32<0xB1>(v));                                                  \
+        v = OP(v, dpp_f32<0x4E>(v));                                                  \
+        v = OP(v, dpp_f32<0x141>(v));                                                 \
+        v = OP(v, dpp_f32<0x140>(v));                                                 \
+        uint32_t a, b;                                                                \
+        swap_pair<16>(__float_as_uint(v), a, b);                                      \
+        v = OP(__uint_as_float(a), __uint_as_float(b));                               \
+        swap_pair<32>(__float_as_uint(v), a, b);                                      \
+        v = OP(__uint_as_float(a), __uint_as_float(b));                               \
+        return v;                                                                     \
+    }
+__device__ __forceinline__ float op_max(float a, float b) { return fmaxf(a, b); }
+__device__ __forceinline__ float op_add(float a, float b) { return a + b; }
+// Every lane ends with the same bits: each step combines two values that all
+// lanes of the group already share, and max / + are commutative bit for bit.
+SLIMSPEC_WAVE_REDUCE_F32(wave_max, op_max)
+SLIMSPEC_WAVE_REDUCE_F32(wave_sum, op_add)
+#undef SLIMSPEC_WAVE_REDUCE_F32
+
+__device__ __forceinline__ uint64_t u64_from(uint32_t hi, uint32_t lo) { return ((uint64_t)hi << 32) | lo; }
+__device__ __forceinline__ uint64_t u64_max(uint64_t a, uint64_t b) { return a > b ? a : b; }
+
+// Largest 64-bit key of the wavefront, in every lane.
+__device__ __forceinline__ uint64_t wave_max_key(uint64_t k) {
+    uint32_t hi = (uint32_t)(k >> 32), lo = (uint32_t)k;
+#define SLIMSPEC_STEP(CTRL)                                                           \
+    {                                                                                 \
+        uint64_t o = u64_from(dpp_u32<CTRL>(hi), dpp_u32<CTRL>(lo));                  \
+        k = u64_max(k, o); hi = (uint32_t)(k >> 32); lo = (uint32_t)k;                \
+    }
+    SLIMSPEC_STEP(0xB1) SLIMSPEC_STEP(0x4E) SLIMSPEC_STEP(0x141) SLIMSPEC_STEP(0x140)
+#undef SLIMSPEC_STEP
+    uint32_t ha, hb, la, lb;
+    swap_pair<16>(hi, ha, hb); swap_pair<16>(lo, la, lb);
+    k = u64_max(u64_from(ha, la), u64_from(hb, lb)); hi = (uint32_t)(k >> 32); lo = (uint32_t)k;
+    swap_pair<32>(hi, ha, hb); swap_pair<32>(lo, la, lb);
+    return u64_max(u64_from(ha, la), u64_from(hb, lb));
 }
 
 }  // namespace slimspec

@@ -2,8 +2,7 @@
 // is bound by reading the weight matrix once from HBM (paper section 4.1: the
 // O(rd + Vr) low-rank head and the O(Vd) full head).
 //
-//   down_partial_kernel   t = h A, split over d into partial sums
-//   down_reduce_kernel    fixed-order sum of the partials -> fp32 t
+//   down_strip_kernel     t = h A, one block per strip of 8 columns of A over all of d
 //   widen_rows_kernel     bf16 h -> fp32 (contraction input of the full head)
 //   stream_topk_kernel    z[:, chunk] = x M[:, chunk] for a 512-column chunk, then the
 //                         chunk's running max, sum of exp and top-k, one partial per
@@ -14,29 +13,21 @@
 namespace slimspec {
 
 // ---------------------------------------------------------------------------
-// t = h A, partial over a slice of d.  A is [d, r] row-major bf16; a lane owns 8
-// adjacent columns of A (one 128-bit load per row), a wavefront covers 512
-// columns, the four wavefronts of a block take interleaved rows of the slice.
-// part is [splits, kGemvMaxRows, r] fp32.
+// t = h A for up to R rows.  A is [d, r] row-major bf16.  Block b owns columns
+// [8b, 8b + 8) (one 128-bit load per row of A); its 1024 threads take the rows of A
+// c = tid, tid + 1024, ... and the partial sums are combined in a fixed order: lanes
+// of a wavefront by the DPP butterfly, wavefronts in index order.  t is fp32 [R, r].
+constexpr int kDownThreads = 1024;
+
 template <int R>
-__global__ __launch_bounds__(256) void down_partial_kernel(
-    const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ part,
+__global__ __launch_bounds__(kDownThreads) void down_strip_kernel(
+    const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ t,
     int rows_here, int d, int r)
 {
-    __shared__ float hs[R][kDownSplitRows];
-    __shared__ float red[4][kChunkCols];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int c0 = blockIdx.x * kDownSplitRows;
-    const int nc = min(kDownSplitRows, d - c0);
-    const int col = (blockIdx.y * kWave + lane) * 8;
-    const bool active = col < r;
-
-    for (int e = threadIdx.x; e < R * kDownSplitRows; e += 256) {
-        int i = e / kDownSplitRows, c = e % kDownSplitRows;
-        hs[i][c] = (i < rows_here && c < nc) ? bf16_to_float(h[(size_t)i * d + c0 + c]) : 0.f;
-    }
-    __syncthreads();
+    __shared__ float red[kDownThreads / 64][R * 8];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int col = blockIdx.x * 8;
 
     float acc[R][8];
 #pragma unroll
@@ -44,55 +35,42 @@ __global__ __launch_bounds__(256) void down_partial_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
 
-    if (active) {
-        constexpr int PER_WAVE = kDownSplitRows / 4;
-        uint4 w[PER_WAVE];
+    constexpr int U = 4;
+    for (int c0 = tid; c0 < d; c0 += kDownThreads * U) {
+        uint4 w[U];
 #pragma unroll
-        for (int u = 0; u < PER_WAVE; ++u) {
-            int c = wave + 4 * u;
-            w[u] = (c < nc) ? *reinterpret_cast<const uint4 *>(A + (size_t)(c0 + c) * r + col)
-                            : make_uint4(0, 0, 0, 0);
+        for (int u = 0; u < U; ++u) {
+            int c = c0 + u * kDownThreads;
+            w[u] = (c < d) ? *reinterpret_cast<const uint4 *>(A + (size_t)c * r + col) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int u = 0; u < PER_WAVE; ++u) {
-            int c = wave + 4 * u;
+        for (int u = 0; u < U; ++u) {
+            int c = c0 + u * kDownThreads;
             float f[8] = {bf16_lo(w[u].x), bf16_hi(w[u].x), bf16_lo(w[u].y), bf16_hi(w[u].y),
                           bf16_lo(w[u].z), bf16_hi(w[u].z), bf16_lo(w[u].w), bf16_hi(w[u].w)};
 #pragma unroll
             for (int i = 0; i < R; ++i) {
-                float hv = hs[i][c];
+                float hv = (c < d && i < rows_here) ? bf16_to_float(h[(size_t)i * d + c]) : 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(hv, f[e], acc[i][e]);
             }
         }
     }
-    // fixed-order sum over the four wavefronts, one row of t at a time
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
+    for (int i = 0; i < R; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = acc[i][e];
-        __syncthreads();
-        for (int cc = threadIdx.x; cc < kChunkCols; cc += 256) {
-            int j = blockIdx.y * kChunkCols + cc;
-            if (j < r) {
-                float s = ((red[0][cc] + red[1][cc]) + red[2][cc]) + red[3][cc];
-                part[((size_t)blockIdx.x * kGemvMaxRows + i) * r + j] = s;
-            }
+        for (int e = 0; e < 8; ++e) {
+            float s = wave_sum(acc[i][e]);
+            if (lane == 0) red[wave][i * 8 + e] = s;
         }
-        __syncthreads();
+    __syncthreads();
+    if (tid < R * 8) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDownThreads / 64; ++w) s += red[w][tid];
+        int i = tid >> 3, e = tid & 7;
+        if (i < rows_here) t[(size_t)i * r + col + e] = s;
     }
-}
-
-// t[i][j] = sum over splits, in split order.  t is fp32 [kGemvMaxRows, r].
-__global__ __launch_bounds__(256) void down_reduce_kernel(
-    const float *__restrict__ part, float *__restrict__ t, int splits, int r, int rows_here)
-{
-    int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= rows_here * r) return;
-    int i = e / r, j = e % r;
-    float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) s += part[((size_t)sp * kGemvMaxRows + i) * r + j];
-    t[(size_t)i * r + j] = s;
 }
 
 __global__ __launch_bounds__(256) void widen_rows_kernel(
@@ -103,16 +81,20 @@ __global__ __launch_bounds__(256) void widen_rows_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Load 8 adjacent columns of one matrix row as floats.
-__device__ __forceinline__ void load8(const uint16_t *p, float (&f)[8]) {
-    uint4 w = *reinterpret_cast<const uint4 *>(p);
-    f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x); f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
-    f[4] = bf16_lo(w.z); f[5] = bf16_hi(w.z); f[6] = bf16_lo(w.w); f[7] = bf16_hi(w.w);
+// 8 adjacent columns of one matrix row: kept as loaded (raw) while in flight, widened
+// to fp32 only when consumed, so that many loads can be outstanding per lane.
+struct Raw8Bf16 { uint4 w; };
+struct Raw8F32 { float4 a, b; };
+__device__ __forceinline__ Raw8Bf16 load_raw8(const uint16_t *p) { return {*reinterpret_cast<const uint4 *>(p)}; }
+__device__ __forceinline__ Raw8F32 load_raw8(const float *p) {
+    return {*reinterpret_cast<const float4 *>(p), *reinterpret_cast<const float4 *>(p + 4)};
 }
-__device__ __forceinline__ void load8(const float *p, float (&f)[8]) {
-    float4 a = *reinterpret_cast<const float4 *>(p);
-    float4 b = *reinterpret_cast<const float4 *>(p + 4);
-    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+__device__ __forceinline__ void widen8(const Raw8Bf16 &q, float (&f)[8]) {
+    f[0] = bf16_lo(q.w.x); f[1] = bf16_hi(q.w.x); f[2] = bf16_lo(q.w.y); f[3] = bf16_hi(q.w.y);
+    f[4] = bf16_lo(q.w.z); f[5] = bf16_hi(q.w.z); f[6] = bf16_lo(q.w.w); f[7] = bf16_hi(q.w.w);
+}
+__device__ __forceinline__ void widen8(const Raw8F32 &q, float (&f)[8]) {
+    f[0] = q.a.x; f[1] = q.a.y; f[2] = q.a.z; f[3] = q.a.w; f[4] = q.b.x; f[5] = q.b.y; f[6] = q.b.z; f[7] = q.b.w;
 }
 
 // One block per 512-column chunk of the vocabulary.  x is the fp32 contraction
@@ -120,6 +102,11 @@ __device__ __forceinline__ void load8(const float *p, float (&f)[8]) {
 // wavefronts split K; every lane owns 8 adjacent columns and keeps R x 8 fp32
 // accumulators.  After a fixed-order sum over the wavefronts, wavefront i % NW
 // reduces row i of the chunk to (max, sum of exp, top-k) and writes the partial.
+//
+// Top-k of a chunk: k rounds; in each the wavefront's largest remaining logit is
+// found with a DPP max, the first lane holding it (lanes own increasing columns, so
+// the first lane has the smallest id among equal logits) gives up its first such
+// element and recomputes its own maximum.
 template <int R, int NW, typename WT>
 __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     const float *__restrict__ x, const WT *__restrict__ M,
@@ -143,25 +130,28 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     const int per = (K + NW - 1) / NW;
     const int j0 = min(K, wave * per), j1 = min(K, j0 + per);
     if (active) {
-        constexpr int U = 8;
+        constexpr int U = (sizeof(WT) == 2 && R <= 2) ? 16 : 8;
         const WT *base = M + col;
         int j = j0;
         for (; j + U <= j1; j += U) {
-            float f[U][8];
+            decltype(load_raw8(base)) q[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) load8(base + (size_t)(j + u) * V, f[u]);
+            for (int u = 0; u < U; ++u) q[u] = load_raw8(base + (size_t)(j + u) * V);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u) {
+                float f[8];
+                widen8(q[u], f);
 #pragma unroll
                 for (int i = 0; i < R; ++i) {
                     float xv = x[(size_t)i * K + j + u];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(xv, f[u][e], acc[i][e]);
+                    for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(xv, f[e], acc[i][e]);
                 }
+            }
         }
         for (; j < j1; ++j) {
             float f[8];
-            load8(base + (size_t)j * V, f);
+            widen8(load_raw8(base + (size_t)j * V), f);
 #pragma unroll
             for (int i = 0; i < R; ++i) {
                 float xv = x[(size_t)i * K + j];
@@ -171,45 +161,59 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
         }
     }
 #pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) red[wave][i][lane * 8 + e] = acc[i][e];
+    for (int i = 0; i < R; ++i) {
+        float4 *dst = reinterpret_cast<float4 *>(&red[wave][i][lane * 8]);
+        dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+        dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+    }
     __syncthreads();
 
     for (int i = wave; i < rows_here; i += NW) {
         float z[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float s = red[0][i][lane * 8 + e];
+        for (int e = 0; e < 8; ++e) z[e] = 0.f;
 #pragma unroll
-            for (int w = 1; w < NW; ++w) s += red[w][i][lane * 8 + e];
-            z[e] = active ? s : kNegInf;
+        for (int w = 0; w < NW; ++w) {          // fixed order: wavefront 0 first
+            const float4 *src = reinterpret_cast<const float4 *>(&red[w][i][lane * 8]);
+            float4 a = src[0], b = src[1];
+            z[0] += a.x; z[1] += a.y; z[2] += a.z; z[3] += a.w;
+            z[4] += b.x; z[5] += b.y; z[6] += b.z; z[7] += b.w;
         }
-        // running max and sum of exp of the chunk
-        float m = z[0];
 #pragma unroll
-        for (int e = 1; e < 8; ++e) m = fmaxf(m, z[e]);
-        m = wave_max(m);
+        for (int e = 0; e < 8; ++e) z[e] = active ? z[e] : kNegInf;
+
+        // running max and sum of exp of the chunk
+        float lm = z[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) lm = fmaxf(lm, z[e]);
+        const float m = wave_max(lm);
         float s = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) s += fast_exp(z[e] - m);     // exp(-inf) = 0 for padding lanes
         s = wave_sum(s);
 
-        // top-k of the chunk: k rounds of "first in order among what is left"
         unsigned alive = active ? 0xffu : 0u;
         float keep_v = kNegInf;
         int keep_i = kNoId;
+        float wm = m;
         for (int p = 0; p < k; ++p) {
-            float bv = kNegInf;
-            int bi = kNoId;
+            const unsigned long long holders = __ballot(alive != 0u && lm == wm);
+            if (holders == 0ull) break;                        // fewer than k columns in this chunk
+            const int first = __builtin_ctzll(holders);
+            int e_sel = 0;
+            if (lane == first) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                bool ok = (alive >> e) & 1u;
-                if (ok && ranks_before(z[e], col + e, bv, bi)) { bv = z[e]; bi = col + e; }
+                for (int e = 7; e >= 0; --e)
+                    if (((alive >> e) & 1u) && z[e] == wm) e_sel = e;
+                alive &= ~(1u << e_sel);
+                lm = kNegInf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if ((alive >> e) & 1u) lm = fmaxf(lm, z[e]);
             }
-            wave_first(bv, bi);
-            if (lane == p) { keep_v = bv; keep_i = bi; }
-            if (bi != kNoId && (bi >> 3) == (col >> 3)) alive &= ~(1u << (bi & 7));
+            e_sel = __builtin_amdgcn_readlane(e_sel, first);
+            if (lane == p) { keep_v = wm; keep_i = chunk * kChunkCols + first * 8 + e_sel; }
+            if (p + 1 < k) wm = wave_max(lm);
         }
         const size_t slot = (size_t)(row0 + i) * chunks + chunk;
         if (lane < k) {
@@ -224,25 +228,20 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
 // launchers
 
 template <int R>
-static hipError_t launch_down(const uint16_t *h, const uint16_t *A, float *part, float *t,
-                              int rows_here, int d, int r, int splits, hipStream_t st)
+static hipError_t launch_down(const uint16_t *h, const uint16_t *A, float *t,
+                              int rows_here, int d, int r, hipStream_t st)
 {
-    dim3 grid(splits, (r / 8 + kWave - 1) / kWave);
-    down_partial_kernel<R><<<grid, 256, 0, st>>>(h, A, part, rows_here, d, r);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    int n = rows_here * r;
-    down_reduce_kernel<<<(n + 255) / 256, 256, 0, st>>>(part, t, splits, r, rows_here);
+    down_strip_kernel<R><<<r / 8, kDownThreads, 0, st>>>(h, A, t, rows_here, d, r);
     return hipGetLastError();
 }
 
-hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *part, float *t,
-                                  int rows_here, int d, int r, int splits, hipStream_t st)
+hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *t,
+                                  int rows_here, int d, int r, hipStream_t st)
 {
-    if (rows_here <= 1) return launch_down<1>(h, A, part, t, rows_here, d, r, splits, st);
-    if (rows_here <= 2) return launch_down<2>(h, A, part, t, rows_here, d, r, splits, st);
-    if (rows_here <= 4) return launch_down<4>(h, A, part, t, rows_here, d, r, splits, st);
-    return launch_down<8>(h, A, part, t, rows_here, d, r, splits, st);
+    if (rows_here <= 1) return launch_down<1>(h, A, t, rows_here, d, r, st);
+    if (rows_here <= 2) return launch_down<2>(h, A, t, rows_here, d, r, st);
+    if (rows_here <= 4) return launch_down<4>(h, A, t, rows_here, d, r, st);
+    return launch_down<8>(h, A, t, rows_here, d, r, st);
 }
 
 hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)

@@ -6,9 +6,9 @@
 
 namespace slimspec {
 
-// t = h A for up to kGemvMaxRows rows: partial sums over slices of d, then a fixed-order reduce.
-hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *part, float *t,
-                                  int rows_here, int d, int r, int splits, hipStream_t st);
+// t = h A (fp32) for up to kGemvMaxRows rows.
+hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *t,
+                                  int rows_here, int d, int r, hipStream_t st);
 
 // x = float(h) for the full head.
 hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st);

@@ -9,7 +9,8 @@ namespace slimspec {
 
 constexpr int kChunkCols = 512;      // vocabulary columns per partial: one wavefront x 8 columns per lane
 constexpr int kGemvMaxRows = 8;      // rows handled by one pass of the streaming (lane-owns-columns) path
-constexpr int kDownSplitRows = 32;   // rows of A (entries of d) per down-projection partial
+constexpr int kMergeThreads = 256;    // threads of the merge block of one row
+constexpr int SLIMSPEC_KMAX_INTERNAL = 64;
 constexpr size_t kAlign = 256;
 
 enum class HeadKind { LowRank, Full };
@@ -19,10 +20,8 @@ struct Plan {
     int rows = 0, d = 0, r = 0, V = 0, k = 0;
     int K = 0;                 // contraction length of the vocabulary projection (r or d)
     int chunks = 0;            // partials per row
-    int down_splits = 0;       // partial sums of the down-projection
     // byte offsets into the workspace
     size_t off_x = 0;          // fp32 [kGemvMaxRows, K]: t (low-rank) or widened h (full)
-    size_t off_down_part = 0;  // fp32 [down_splits, kGemvMaxRows, r]
     size_t off_part_ms = 0;    // float2 [rows, chunks]      running max, sum of exp
     size_t off_part_val = 0;   // float  [rows, chunks, k]   per-chunk top-k logits
     size_t off_part_id = 0;    // int32  [rows, chunks, k]   per-chunk top-k ids
@@ -36,10 +35,8 @@ inline Plan make_plan(HeadKind kind, int rows, int d, int r, int V, int k) {
     p.rows = rows; p.d = d; p.r = r; p.V = V; p.k = k;
     p.K = (kind == HeadKind::LowRank) ? r : d;
     p.chunks = (V + kChunkCols - 1) / kChunkCols;
-    p.down_splits = (kind == HeadKind::LowRank) ? (d + kDownSplitRows - 1) / kDownSplitRows : 0;
     size_t off = 0;
     p.off_x = off;          off = align_up(off + sizeof(float) * kGemvMaxRows * (size_t)p.K);
-    p.off_down_part = off;  off = align_up(off + sizeof(float) * (size_t)p.down_splits * kGemvMaxRows * (size_t)r);
     p.off_part_ms = off;    off = align_up(off + 2 * sizeof(float) * (size_t)rows * p.chunks);
     p.off_part_val = off;   off = align_up(off + sizeof(float) * (size_t)rows * p.chunks * k);
     p.off_part_id = off;    off = align_up(off + sizeof(int32_t) * (size_t)rows * p.chunks * k);

@@ -57,7 +57,6 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     float *x = reinterpret_cast<float *>(ws + p.off_x);
-    float *down_part = reinterpret_cast<float *>(ws + p.off_down_part);
     float2 *part_ms = reinterpret_cast<float2 *>(ws + p.off_part_ms);
     float *part_val = reinterpret_cast<float *>(ws + p.off_part_val);
     int *part_id = reinterpret_cast<int *>(ws + p.off_part_id);
@@ -70,7 +69,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         hipError_t e;
         if (kind == HeadKind::LowRank)
             e = launch_down_projection(hb + (size_t)row0 * p.d, static_cast<const uint16_t *>(A),
-                                       down_part, x, rows_here, p.d, p.r, p.down_splits, s);
+                                       x, rows_here, p.d, p.r, s);
         else
             e = launch_widen_rows(hb + (size_t)row0 * p.d, x, rows_here * p.d, s);
         if (e != hipSuccess) return fail_hip(e);
