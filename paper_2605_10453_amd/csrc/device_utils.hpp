@@ -112,4 +112,13 @@ __device__ __forceinline__ uint64_t wave_max_key(uint64_t k) {
     return u64_max(u64_from(ha, la), u64_from(hb, lb));
 }
 
+// Orders the shared-memory accesses of one wavefront: writes before it are visible to
+// the reads of the other lanes after it (the LDS serves a wavefront's requests in
+// order; this keeps the compiler from reordering across the point).
+__device__ __forceinline__ void lds_wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 }  // namespace slimspec

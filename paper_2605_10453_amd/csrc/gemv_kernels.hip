@@ -27,7 +27,13 @@ __global__ __launch_bounds__(kDownThreads) void down_strip_kernel(
     __shared__ float red[kDownThreads / 64][R * 8];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int col = blockIdx.x * 8;
+    // blocks are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of strips
+    // so that the 128-byte lines of A it touches are used in full inside its own L2
+    const int nstrips = r / 8;
+    const int per_xcd = gridDim.x / 8;              // the grid is 8 * ceil(nstrips / 8) blocks
+    const int strip = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (strip >= nstrips) return;
+    const int col = strip * 8;
 
     float acc[R][8];
 #pragma unroll
@@ -103,10 +109,12 @@ __device__ __forceinline__ void widen8(const Raw8F32 &q, float (&f)[8]) {
 // accumulators.  After a fixed-order sum over the wavefronts, wavefront i % NW
 // reduces row i of the chunk to (max, sum of exp, top-k) and writes the partial.
 //
-// Top-k of a chunk: k rounds; in each the wavefront's largest remaining logit is
-// found with a DPP max, the first lane holding it (lanes own increasing columns, so
-// the first lane has the smallest id among equal logits) gives up its first such
-// element and recomputes its own maximum.
+// Top-k of a chunk in three steps whose cost does not grow with k: the k-th largest
+// of the 64 lane maxima (by all-pairs counting) bounds the answer from below; the
+// few elements that reach the bound are gathered in shared memory; they are ranked
+// among themselves by (logit desc, id asc), again by counting.  Lanes own increasing
+// columns, so ordering lane maxima by (value, lane) is consistent with ordering
+// elements by (value, id): an element below the bound is preceded by k lane maxima.
 template <int R, int NW, typename WT>
 __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     const float *__restrict__ x, const WT *__restrict__ M,
@@ -114,6 +122,11 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     int rows_here, int row0, int K, int V, int chunks, int k)
 {
     __shared__ float red[NW][R][kChunkCols];
+    constexpr int EW = (R < NW) ? R : NW;           // wavefronts that run the per-row epilogue
+    __shared__ uint64_t sel_keys[EW][64];
+    __shared__ uint64_t sel_cand[EW][kChunkCols];
+    __shared__ uint64_t sel_bound[EW];
+    __shared__ uint32_t sel_cnt[EW];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int chunk = blockIdx.x;
@@ -192,35 +205,48 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
         for (int e = 0; e < 8; ++e) s += fast_exp(z[e] - m);     // exp(-inf) = 0 for padding lanes
         s = wave_sum(s);
 
-        unsigned alive = active ? 0xffu : 0u;
-        float keep_v = kNegInf;
-        int keep_i = kNoId;
-        float wm = m;
-        for (int p = 0; p < k; ++p) {
-            const unsigned long long holders = __ballot(alive != 0u && lm == wm);
-            if (holders == 0ull) break;                        // fewer than k columns in this chunk
-            const int first = __builtin_ctzll(holders);
-            int e_sel = 0;
-            if (lane == first) {
+        // top-k of the chunk, without k serial rounds
+        // (1) bound: the k-th largest of the 64 lane maxima, as keys (value, lane)
+        uint64_t *lane_keys = sel_keys[wave];
+        uint64_t *cand = sel_cand[wave];
+        const uint64_t my_lane_key = active ? make_key(lm, (uint32_t)lane) : kNoKey;
+        lane_keys[lane] = my_lane_key;
+        if (lane == 0) { sel_cnt[wave] = 0u; sel_bound[wave] = kNoKey; }
+        lds_wave_sync();
+        int rank = 0;
+#pragma unroll 8
+        for (int q = 0; q < 64; ++q) rank += (lane_keys[q] > my_lane_key) ? 1 : 0;
+        if (rank == k - 1 && my_lane_key != kNoKey) sel_bound[wave] = my_lane_key;   // keys are unique: one lane at most
+        lds_wave_sync();
+        const uint64_t bound = sel_bound[wave];          // kNoKey when fewer than k lanes hold columns: keep everything
+        // (2) every element whose (value, lane) key reaches the bound is a candidate
 #pragma unroll
-                for (int e = 7; e >= 0; --e)
-                    if (((alive >> e) & 1u) && z[e] == wm) e_sel = e;
-                alive &= ~(1u << e_sel);
-                lm = kNegInf;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if ((alive >> e) & 1u) lm = fmaxf(lm, z[e]);
+        for (int e = 0; e < 8; ++e) {
+            if (active && make_key(z[e], (uint32_t)lane) >= bound) {
+                uint32_t pos = atomicAdd(&sel_cnt[wave], 1u);
+                cand[pos] = make_key(z[e], (uint32_t)(col + e));
             }
-            e_sel = __builtin_amdgcn_readlane(e_sel, first);
-            if (lane == p) { keep_v = wm; keep_i = chunk * kChunkCols + first * 8 + e_sel; }
-            if (p + 1 < k) wm = wave_max(lm);
         }
+        lds_wave_sync();
+        const int n_cand = (int)sel_cnt[wave];
+        // (3) rank the candidates among themselves by (value desc, id asc); ranks below k are the answer
         const size_t slot = (size_t)(row0 + i) * chunks + chunk;
-        if (lane < k) {
-            part_val[slot * k + lane] = keep_v;
-            part_id[slot * k + lane] = keep_i;
+        for (int c0 = 0; c0 < n_cand; c0 += 64) {
+            const int c = c0 + lane;
+            const uint64_t mine = (c < n_cand) ? cand[c] : kNoKey;
+            int rk = 0;
+            for (int q = 0; q < n_cand; ++q) rk += (cand[q] > mine) ? 1 : 0;
+            if (c < n_cand && rk < k) {
+                part_val[slot * k + rk] = key_value(mine);
+                part_id[slot * k + rk] = (int)key_tiebreak(mine);
+            }
+        }
+        if (lane >= n_cand && lane < k) {                  // fewer than k columns in this chunk
+            part_val[slot * k + lane] = kNegInf;
+            part_id[slot * k + lane] = kNoId;
         }
         if (lane == 0) part_ms[slot] = make_float2(m, s);
+        lds_wave_sync();                                   // the buffers are reused by this wavefront's next row
     }
 }
 
@@ -231,7 +257,7 @@ template <int R>
 static hipError_t launch_down(const uint16_t *h, const uint16_t *A, float *t,
                               int rows_here, int d, int r, hipStream_t st)
 {
-    down_strip_kernel<R><<<r / 8, kDownThreads, 0, st>>>(h, A, t, rows_here, d, r);
+    down_strip_kernel<R><<<8 * ((r / 8 + 7) / 8), kDownThreads, 0, st>>>(h, A, t, rows_here, d, r);
     return hipGetLastError();
 }
 

@@ -2,13 +2,15 @@
 // partials (running max m_c, sum of exp s_c, sorted top-k list per vocabulary chunk) into
 //     lse = M + ln sum_c s_c exp(m_c - M),   M = max_c m_c
 // and the k globally first (logit desc, id asc) candidates, and writes
-// out_ids / out_logprobs = logit - lse.  The order of every reduction is fixed, so
-// the output does not depend on scheduling.
+// out_ids / out_logprobs = logit - lse.  The order of every reduction is fixed and the
+// selection works on unique keys, so the output does not depend on scheduling.
 //
-// Partials of one row cover increasing, disjoint id ranges and each list is
-// already in output order, so "smaller list position c * k + p" breaks ties exactly
-// like "smaller id".  Thread t owns the lists c = t, t + 256, ...; it offers the head
-// of its best list, the block takes the best offer k times (one barrier per round).
+// Partials of one row cover increasing, disjoint id ranges and each list is already in
+// output order, so "smaller list position e = c * k + p" breaks ties exactly like
+// "smaller id".  Selection, in steps whose cost does not grow with k:
+//   (1) the k-th largest list head (by all-pairs counting) bounds the answer from below;
+//   (2) the entries that reach the bound (at most k lists, k entries each) are gathered;
+//   (3) they are ranked among themselves by counting; ranks below k are the output.
 #include "device_utils.hpp"
 #include "launch.hpp"
 
@@ -20,11 +22,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(
     const float2 *__restrict__ part_ms, const float *__restrict__ part_val, const int *__restrict__ part_id,
     int chunks, int k, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
-    extern __shared__ unsigned char lds_raw[];
-    float *vals = reinterpret_cast<float *>(lds_raw);                       // [chunks * k]
-    int *cursor = reinterpret_cast<int *>(vals + (size_t)chunks * k);       // [chunks]
-    __shared__ float red_f[kMergeWaves];
-    __shared__ uint64_t offer[2][kMergeWaves];
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    uint64_t *heads = reinterpret_cast<uint64_t *>(lds_raw);                 // [chunks]
+    uint64_t *cand = heads + chunks;                                          // [k * k]
+    float *vals = reinterpret_cast<float *>(cand + (size_t)k * k);           // [chunks * k]
+    __shared__ float red_m[kMergeWaves], red_s[kMergeWaves];
+    __shared__ uint64_t bound_sh;
+    __shared__ uint32_t cnt_sh;
     __shared__ uint32_t winners[SLIMSPEC_KMAX_INTERNAL];
 
     const int row = blockIdx.x;
@@ -35,62 +39,61 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(
 
     const int n = chunks * k;
     for (int e = tid; e < n; e += kMergeThreads) vals[e] = pv[e];
-    for (int c = tid; c < chunks; c += kMergeThreads) cursor[c] = 0;
+    if (tid == 0) { bound_sh = kNoKey; cnt_sh = 0u; }
 
-    // log-sum-exp over the chunks
-    float M = kNegInf;
-    for (int c = tid; c < chunks; c += kMergeThreads) M = fmaxf(M, ms[c].x);
-    M = wave_max(M);
-    if (lane == 0) red_f[wave] = M;
-    __syncthreads();
-    M = red_f[0];
-#pragma unroll
-    for (int w = 1; w < kMergeWaves; ++w) M = fmaxf(M, red_f[w]);
-    __syncthreads();
-    float S = 0.f;
+    // log-sum-exp: every thread folds its chunks in increasing order, then the block combines
+    float m_t = kNegInf, s_t = 0.f;
     for (int c = tid; c < chunks; c += kMergeThreads) {
+        heads[c] = make_key(pv[(size_t)c * k], (uint32_t)(c * k));
         float2 p = ms[c];
-        S += p.y * fast_exp(p.x - M);
+        float m_new = fmaxf(m_t, p.x);
+        s_t = s_t * fast_exp(m_t - m_new) + p.y * fast_exp(p.x - m_new);
+        m_t = m_new;
     }
-    S = wave_sum(S);
-    if (lane == 0) red_f[wave] = S;
+    const float m_w = wave_max(m_t);
+    float s_w = (m_t == kNegInf) ? 0.f : s_t * fast_exp(m_t - m_w);
+    s_w = wave_sum(s_w);
+    if (lane == 0) { red_m[wave] = m_w; red_s[wave] = s_w; }
     __syncthreads();
-    S = red_f[0];
+    float M = red_m[0];
 #pragma unroll
-    for (int w = 1; w < kMergeWaves; ++w) S += red_f[w];
+    for (int w = 1; w < kMergeWaves; ++w) M = fmaxf(M, red_m[w]);
+    float S = 0.f;
+#pragma unroll
+    for (int w = 0; w < kMergeWaves; ++w) S += (red_m[w] == kNegInf) ? 0.f : red_s[w] * fast_exp(red_m[w] - M);
     const float lse = M + fast_log(S);
 
-    // this thread's best head
-    auto best_of_mine = [&]() {
-        uint64_t b = kNoKey;
-        for (int c = tid; c < chunks; c += kMergeThreads) {
-            int cur = cursor[c];
-            if (cur < k) {
-                float v = vals[c * k + cur];
-                if (v != kNegInf) b = u64_max(b, make_key(v, (uint32_t)(c * k + cur)));
-            }
-        }
-        return b;
-    };
-    uint64_t mine = best_of_mine();
-    for (int p = 0; p < k; ++p) {
-        uint64_t w = wave_max_key(mine);
-        if (lane == 0) offer[p & 1][wave] = w;
-        __syncthreads();
-        uint64_t best = offer[p & 1][0];
-#pragma unroll
-        for (int q = 1; q < kMergeWaves; ++q) best = u64_max(best, offer[p & 1][q]);
-        if (best == kNoKey) break;                  // cannot happen when k <= V
-        if (mine == best) {                         // keys are unique: exactly one thread
-            uint32_t e = key_tiebreak(best);
-            winners[p] = e;
-            cursor[e / (uint32_t)k] += 1;
-            mine = best_of_mine();
+    // (1) the k-th largest head
+    for (int c = tid; c < chunks; c += kMergeThreads) {
+        const uint64_t mine = heads[c];
+        int rank = 0;
+        for (int q = 0; q < chunks; ++q) rank += (heads[q] > mine) ? 1 : 0;
+        if (rank == k - 1) bound_sh = mine;             // keys are unique: one writer at most
+    }
+    __syncthreads();
+    const uint64_t bound = bound_sh;                    // kNoKey when there are fewer than k lists: keep everything
+    // (2) gather what reaches the bound
+    for (int c = tid; c < chunks; c += kMergeThreads) {
+        if (heads[c] < bound) continue;
+        for (int p = 0; p < k; ++p) {
+            const float v = vals[c * k + p];
+            const uint64_t key = make_key(v, (uint32_t)(c * k + p));
+            if (v == kNegInf || key < bound) break;     // lists are sorted
+            cand[atomicAdd(&cnt_sh, 1u)] = key;
         }
     }
     __syncthreads();
-    if (tid < k) {
-        uint32_t e = winners[tid];
+    // (3) rank the gathered entries
+    const int n_cand = (int)cnt_sh;
+    for (int c = tid; c < n_cand; c += kMergeThreads) {
+        const uint64_t mine = cand[c];
+        int rank = 0;
+        for (int q = 0; q < n_cand; ++q) rank += (cand[q] > mine) ? 1 : 0;
+        if (rank < k) winners[rank] = key_tiebreak(mine);
+    }
+    __syncthreads();
+    if (tid < k) {                                      // n_cand >= k whenever k <= V
+        const uint32_t e = winners[tid];
         out_ids[(size_t)row * k + tid] = pi[e];
         out_logprobs[(size_t)row * k + tid] = vals[e] - lse;
     }

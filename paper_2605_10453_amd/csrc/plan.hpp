@@ -45,9 +45,10 @@ inline Plan make_plan(HeadKind kind, int rows, int d, int r, int V, int k) {
     return p;
 }
 
-// Shared memory the merge kernel needs: every partial's k logits plus a cursor per partial.
+// Dynamic shared memory of the merge kernel: the head key of every list, the gathered
+// candidates (at most k lists of k entries) and every list's k logits.
 inline size_t merge_lds_bytes(int chunks, int k) {
-    return sizeof(float) * (size_t)chunks * k + sizeof(int) * (size_t)chunks + 2 * sizeof(int) * 64;
+    return sizeof(uint64_t) * ((size_t)chunks + (size_t)k * k) + sizeof(float) * (size_t)chunks * k;
 }
 constexpr size_t kMergeLdsLimit = 160 * 1024 - 1024;
 
