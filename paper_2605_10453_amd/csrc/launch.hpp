@@ -22,4 +22,28 @@ hipError_t launch_stream_topk(const float *x, const void *M, bool m_is_f32,
 hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int *part_id,
                         int rows, int chunks, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st);
 
+// ---- matrix-core path (rows > kGemvMaxRows, bf16 weights) ----
+constexpr int kStreamList = 3;          // groups kept per lane stream
+constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial
+
+int mfma_cols_per_wave(int rows);       // MFMA tiles (of the 8 in a 256-wide tile) owned by one wavefront
+
+// partial sums of t = h A over `slices` slices of d (kslice entries each, a multiple of 64)
+hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int d, int r,
+                            int slices, int kslice, hipStream_t st);
+// slices -> fp32 t, f16 t (k-grouped), per-row rounding statistics, rms estimate of B
+hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_pad, int r,
+                              float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
+                              hipStream_t st);
+// vocabulary projection with the fused epilogue; X is f16 k-grouped (x_row_major = false, M converted to
+// f16 on the fly) or bf16 row-major [rows, K] (x_row_major = true, bf16 MFMA)
+hipError_t launch_head_mfma(const uint16_t *X, bool x_row_major, const uint16_t *M, float *part,
+                            int rows, int rows_pad, int K, int V, int n_rb, int gw, hipStream_t st);
+
+// stream partials -> final ids / log-probabilities, with exact fp32 re-evaluation of uncertain ranks
+hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
+                                const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
+                                const float2 *stat, const float *brms, int k,
+                                int32_t *out_ids, float *out_logprobs, hipStream_t st);
+
 }  // namespace slimspec

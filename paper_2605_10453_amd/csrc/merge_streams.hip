@@ -1,0 +1,318 @@
+// Merge for the matrix-core path: one block per row turns the row's lane-stream partials
+// (see mfma_kernels.hip) into the final top-k ids and log-probabilities.
+//
+// What a stream tells about its share of the row's logits (all values as computed by the
+// matrix cores, i.e. with a 16-bit contraction input in the low-rank head):
+//   * L listed groups of 16 logits: the group maximum x (its low 4 bits name its position in the
+//     group), the second largest value y of the group, a tag naming the group;
+//   * U: an upper bound of every logit in its unlisted groups.
+// Let tau be the k-th largest listed maximum and eps a bound of |computed - exact|.  Every logit
+// that can be among the exact top-k is computed >= tau - 2 eps =: theta.  The block therefore
+// collects (a) listed maxima >= theta, (b) the other 15 members of listed groups whose second
+// largest value reaches theta, (c) all members of unlisted groups of streams with U >= theta
+// (b and c are rare), evaluates exactly, in fp32 from the fp32 contraction input, every
+// collected logit whose rank is not already certain (members under b and c, and listed maxima
+// within 2 eps of another collected value), and ranks the collected set by (value desc, id asc).
+// If the collected set outgrows its buffer (possible only with thousands of near-ties at the
+// k-th place) the block falls back to an exhaustive exact pass over the row's whole vocabulary.
+//
+// log-sum-exp: streams carry (max * log2 e, sum of 2^(z log2 e - max)); combined in a fixed order.
+#include "device_utils.hpp"
+#include "launch.hpp"
+
+namespace slimspec {
+
+namespace {
+
+constexpr int kWorkCap = 2048;          // collected logits per row before the exhaustive fallback
+constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
+constexpr float kEpsSigmas = 8.0f;      // eps = this many standard deviations of the rounding error of t
+
+__device__ __forceinline__ float mask4(float v) { return __uint_as_float(__float_as_uint(v) & 0xfffffff0u); }
+
+struct RowCtx {
+    const void *x; int x_is_bf16;       // exact contraction input of this row: fp32 t or bf16 h
+    const uint16_t *M; int K, V;
+};
+
+__device__ __forceinline__ float x_at(const RowCtx &c, int j) {
+    return c.x_is_bf16 ? bf16_to_float(static_cast<const uint16_t *>(c.x)[j]) : static_cast<const float *>(c.x)[j];
+}
+
+// exact fp32 logit of one vocabulary id, computed by one wavefront (all 64 lanes must call)
+__device__ __forceinline__ float exact_logit_wave(const RowCtx &c, int id, int lane) {
+    float acc = 0.f;
+    for (int j = lane; j < c.K; j += 64) acc = fmaf(x_at(c, j), bf16_to_float(c.M[(size_t)j * c.V + id]), acc);
+    return wave_sum(acc);
+}
+
+// rank of every key among keys[0, n) by counting; calls f(index, key, rank) for this thread's keys
+template <class F>
+__device__ __forceinline__ void rank_all_pairs(const uint64_t *keys, int n, int tid, int nthreads, F f) {
+    for (int c = tid; c < n; c += nthreads) {
+        const uint64_t mine = keys[c];
+        int rank = 0;
+        for (int q = 0; q < n; ++q) rank += (keys[q] > mine) ? 1 : 0;
+        f(c, mine, rank);
+    }
+}
+
+}  // namespace
+
+__global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
+    const float *__restrict__ part, int nsr, int gw, int n_wv, int tv, int n_vt,
+    const void *__restrict__ xexact, int x_is_bf16, int ldx,
+    const uint16_t *__restrict__ M, int K, int V,
+    const float2 *__restrict__ stat, const float *__restrict__ brms,
+    int k, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+{
+    constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int n = nsr * L;
+    const int ngroups = (n + 63) / 64;
+    uint64_t *keys = reinterpret_cast<uint64_t *>(lds_raw);            // [n]            listed maxima
+    uint64_t *surv = keys + n;                                          // [ngroups * k]  best k of every 64
+    uint64_t *work = surv + (size_t)ngroups * k;                        // [kWorkCap]     final keys / fallback buffer
+    int *w_id = reinterpret_cast<int *>(work + kWorkCap);               // [kWorkCap]
+    float *w_val = reinterpret_cast<float *>(w_id + kWorkCap);          // [kWorkCap]
+    int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]
+    __shared__ float red_m[NWAVES], red_s[NWAVES];
+    __shared__ uint64_t tau_key;
+    __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden;
+    __shared__ uint32_t winners[SLIMSPEC_KMAX_INTERNAL];
+
+    const int row = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *rec = part + (size_t)row * nsr * REC;
+    RowCtx ctx;
+    ctx.x = x_is_bf16 ? static_cast<const void *>(static_cast<const uint16_t *>(xexact) + (size_t)row * ldx)
+                      : static_cast<const void *>(static_cast<const float *>(xexact) + (size_t)row * ldx);
+    ctx.x_is_bf16 = x_is_bf16; ctx.M = M; ctx.K = K; ctx.V = V;
+
+    if (tid == 0) { tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; }
+
+    // ---- log-sum-exp of the streams, and the squared norm of the row's contraction input
+    float m_t = kNegInf, s_t = 0.f, x2 = 0.f;
+    for (int sidx = tid; sidx < nsr; sidx += NT) {
+        const float mc = rec[(size_t)sidx * REC], s = rec[(size_t)sidx * REC + 1];
+        if (s > 0.f) {
+            const float m_new = fmaxf(m_t, mc);
+            s_t = s_t * __builtin_amdgcn_exp2f(m_t - m_new) + s * __builtin_amdgcn_exp2f(mc - m_new);
+            m_t = m_new;
+        }
+    }
+    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); x2 += v * v; }
+    const float m_w = wave_max(m_t);
+    float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
+    s_w = wave_sum(s_w);
+    x2 = wave_sum(x2);
+    if (lane == 0) { red_m[wave] = m_w; red_s[wave] = s_w; }
+    __shared__ float red_x[NWAVES];
+    if (lane == 0) red_x[wave] = x2;
+
+    // ---- keys of the listed maxima
+    for (int e = tid; e < n; e += NT) {
+        const float x = rec[(size_t)(e / L) * REC + 3 + 3 * (e % L)];
+        keys[e] = (x > kNoValue) ? make_key(mask4(x), (uint32_t)e) : kNoKey;
+    }
+    __syncthreads();
+    float Mx = red_m[0], X2 = 0.f;
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) Mx = fmaxf(Mx, red_m[w]);
+    float S = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) {
+        S += (red_m[w] == kNegInf) ? 0.f : red_s[w] * __builtin_amdgcn_exp2f(red_m[w] - Mx);
+        X2 += red_x[w];
+    }
+    const float lse = (Mx + __builtin_amdgcn_logf(S)) * kLn2;
+
+    if (X2 == 0.f) {
+        // zero contraction input (for instance a padded batch slot): every logit is exactly +0
+        if (tid < k) {
+            out_ids[(size_t)row * k + tid] = tid;
+            out_logprobs[(size_t)row * k + tid] = -__builtin_amdgcn_logf((float)V) * kLn2;
+        }
+        return;
+    }
+
+    // ---- tau: the k-th largest listed maximum (best k of every 64 keys, then all pairs)
+    for (int e = tid; e < n; e += NT) {
+        const uint64_t mine = keys[e];
+        if (mine == kNoKey) continue;
+        const int g0 = e & ~63, g1 = min(n, g0 + 64);
+        int rank = 0;
+        for (int q = g0; q < g1; ++q) rank += (keys[q] > mine) ? 1 : 0;
+        if (rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
+    }
+    __syncthreads();
+    const int n_surv = (int)cnt_surv;
+    rank_all_pairs(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
+    __syncthreads();
+    const bool have_tau = tau_key != kNoKey;
+    const float tau = have_tau ? key_value(tau_key) : kNegInf;
+    float eps;
+    if (stat != nullptr) eps = kEpsSigmas * sqrtf(stat[row].x) * brms[0] + fabsf(tau) * 1.2e-5f + 1e-30f;
+    else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
+    const float theta = have_tau ? tau - 2.f * eps : kNegInf;
+    bool exhaustive = !(eps < 1e30f) || !(lse == lse) || !(fabsf(lse) < 1e30f);   // overflow of the 16-bit input
+
+    // ---- collect
+    auto push = [&](int id, float val, int need) {
+        const uint32_t slot = atomicAdd(&cnt_work, 1u);
+        if (slot < (uint32_t)kWorkCap) { w_id[slot] = id; w_val[slot] = val; w_need[slot] = need; }
+        if (need) atomicAdd(&cnt_hidden, 1u);
+    };
+    auto id_of = [&](int tag, int i, int half) { return (tag >> 3) * 256 + 8 * (8 * (i >> 2) + 4 * half + (i & 3)) + (tag & 7); };
+    if (!exhaustive) {
+        for (int sidx = tid; sidx < nsr; sidx += NT) {
+            const float *r = rec + (size_t)sidx * REC;
+            const int half = sidx & 1;
+            int listed[L];
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                const float x = r[3 + 3 * l], y = r[4 + 3 * l];
+                const int tag = __float_as_int(r[5 + 3 * l]);
+                listed[l] = (x > kNoValue) ? tag : -1;
+                if (!(x > kNoValue) || !(mask4(x) >= theta)) continue;
+                const int imax = (int)(__float_as_uint(x) & 15u);
+                push(id_of(tag, imax, half), mask4(x), 0);
+                if (y > kNoValue && mask4(y) >= theta) {
+                    for (int i = 0; i < 16; ++i) {
+                        const int id = id_of(tag, i, half);
+                        if (i != imax && id < V) push(id, 0.f, 1);
+                    }
+                }
+            }
+            const float U = r[2];
+            if (U > kNoValue && mask4(U) >= theta) {
+                const int wv = (sidx >> 1) % n_wv, col = (sidx >> 1) / n_wv;
+                for (int vt = col; vt < n_vt; vt += gw)
+                    for (int j = wv * tv; j < wv * tv + tv; ++j) {
+                        const int tag = vt * 8 + j;
+                        bool is_listed = false;
+#pragma unroll
+                        for (int l = 0; l < L; ++l) is_listed |= (listed[l] == tag);
+                        if (is_listed) continue;
+                        for (int i = 0; i < 16; ++i) {
+                            const int id = id_of(tag, i, half);
+                            if (id < V) push(id, 0.f, 1);
+                        }
+                    }
+            }
+        }
+    }
+    __syncthreads();
+    int n_work = (int)cnt_work;
+    if (n_work > kWorkCap || n_work < k) exhaustive = true;
+
+    if (!exhaustive) {
+        // ---- which listed maxima need the exact value
+        const bool any_hidden = cnt_hidden != 0u;
+        for (int c = tid; c < n_work; c += NT) {
+            if (w_need[c]) continue;
+            bool need = any_hidden;
+            const float mine = w_val[c];
+            for (int q = 0; q < n_work && !need; ++q)
+                if (q != c && fabsf(w_val[q] - mine) <= 2.f * eps) need = true;
+            if (need) w_need[c] = 2;                      // 2: decided in this pass (w_val still the computed value)
+        }
+        __syncthreads();
+        for (int c = wave; c < n_work; c += NWAVES) {
+            if (w_need[c] == 0) continue;                 // wavefront-uniform
+            const float z = exact_logit_wave(ctx, w_id[c], lane);
+            if (lane == 0) w_val[c] = z;
+        }
+        __syncthreads();
+        for (int c = tid; c < n_work; c += NT) work[c] = make_key(w_val[c], (uint32_t)w_id[c]);
+        __syncthreads();
+        rank_all_pairs(work, n_work, tid, NT, [&](int c, uint64_t, int rank) { if (rank < k) winners[rank] = (uint32_t)c; });
+        __syncthreads();
+        if (tid < k) {
+            const uint32_t c = winners[tid];
+            out_ids[(size_t)row * k + tid] = w_id[c];
+            out_logprobs[(size_t)row * k + tid] = w_val[c] - lse;
+        }
+        return;
+    }
+
+    // ---- exhaustive exact pass: every logit of the row in fp32, running top-k in `work`
+    // (also recomputes the log-sum-exp, since the streams' sums may have overflowed)
+    __shared__ uint64_t thr_key;
+    __shared__ uint32_t cnt_buf;
+    if (tid == 0) { thr_key = kNoKey; cnt_buf = 0u; }
+    __syncthreads();
+    float em = kNegInf, es = 0.f;
+    for (int c0 = 0; c0 < V; c0 += NT * 4) {
+        const int col = c0 + tid * 4;
+        if (col < V) {
+            float z[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int j = 0; j < K; ++j) {
+                const uint2 w = *reinterpret_cast<const uint2 *>(M + (size_t)j * V + col);
+                const float xj = x_at(ctx, j);
+                z[0] = fmaf(xj, bf16_lo(w.x), z[0]); z[1] = fmaf(xj, bf16_hi(w.x), z[1]);
+                z[2] = fmaf(xj, bf16_lo(w.y), z[2]); z[3] = fmaf(xj, bf16_hi(w.y), z[3]);
+            }
+            const uint64_t thr = thr_key;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float m_new = fmaxf(em, z[e]);
+                es = es * fast_exp(em - m_new) + fast_exp(z[e] - m_new);
+                em = m_new;
+                const uint64_t key = make_key(z[e], (uint32_t)(col + e));
+                if (key > thr) work[atomicAdd(&cnt_buf, 1u)] = key;     // at most k + 1024 entries: fits
+            }
+        }
+        __syncthreads();
+        const int nb = (int)cnt_buf;
+        uint64_t mykey[(kWorkCap + NT - 1) / NT];
+        int myrank[(kWorkCap + NT - 1) / NT];
+        int cnt_mine = 0;
+        rank_all_pairs(work, nb, tid, NT, [&](int, uint64_t key, int rank) { mykey[cnt_mine] = key; myrank[cnt_mine] = rank; ++cnt_mine; });
+        __syncthreads();
+        for (int q = 0; q < cnt_mine; ++q)
+            if (myrank[q] < k) { work[myrank[q]] = mykey[q]; if (myrank[q] == k - 1) thr_key = mykey[q]; }
+        if (tid == 0) cnt_buf = (uint32_t)min(nb, k);
+        __syncthreads();
+    }
+    // exact log-sum-exp of the row
+    const float em_w = wave_max(em);
+    float es_w = (em == kNegInf) ? 0.f : es * fast_exp(em - em_w);
+    es_w = wave_sum(es_w);
+    __syncthreads();
+    if (lane == 0) { red_m[wave] = em_w; red_s[wave] = es_w; }
+    __syncthreads();
+    float EM = red_m[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) EM = fmaxf(EM, red_m[w]);
+    float ES = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) ES += (red_m[w] == kNegInf) ? 0.f : red_s[w] * fast_exp(red_m[w] - EM);
+    const float lse_exact = EM + fast_log(ES);
+    if (tid < k) {                                          // work[0..k) is sorted by rank
+        out_ids[(size_t)row * k + tid] = (int)key_tiebreak(work[tid]);
+        out_logprobs[(size_t)row * k + tid] = key_value(work[tid]) - lse_exact;
+    }
+}
+
+size_t merge_streams_lds_bytes(int nsr, int k) {
+    const size_t n = (size_t)nsr * kStreamList;
+    const size_t ngroups = (n + 63) / 64;
+    return sizeof(uint64_t) * (n + ngroups * k + kWorkCap) + 12u * kWorkCap;
+}
+
+hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
+                                const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
+                                const float2 *stat, const float *brms, int k,
+                                int32_t *out_ids, float *out_logprobs, hipStream_t st)
+{
+    const size_t lds = merge_streams_lds_bytes(nsr, k);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_wv, tv, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
+                                                           M, K, V, stat, brms, k, out_ids, out_logprobs);
+    return hipGetLastError();
+}
+
+}  // namespace slimspec

@@ -1,0 +1,246 @@
+// Matrix-core building blocks for calls with many rows (paper section 4.1: the two dense
+// products of the low-rank head, t = h A and z = t B, and the full head z = h W).
+//
+// Orientation.  The weight matrix M is [K, N] row-major (A: K = d, N = r;  B: K = r, N = V;
+// W: K = d, N = V) and the activations X are [rows, K].  The kernels compute the transposed
+// product  Z^T[n, row] = sum_k M[k, n] X[row, k]  with v_mfma_f32_32x32x16_{f16,bf16}:
+// the MFMA "A" operand is a 32 (n) x 16 (k) piece of M^T, the "B" operand a 16 (k) x 32 (row)
+// piece of X^T.  In the 32x32 result a lane then owns ONE row (lane % 32) and 16 values of n,
+// so everything that is reduced per row (running max, sum of exp, top-k) stays inside a lane.
+//
+// Both operands want, per lane, 8 consecutive k for a fixed n (or row).  M has n contiguous, so
+// its tiles are transposed on the way into LDS: a lane loads 8 rows k of 8 adjacent n (eight
+// 128-bit loads), regroups them in registers into 8 vectors "8 consecutive k of one n" (the
+// bf16 -> f16 conversion of the low-rank head happens in the same step) and writes each vector
+// with one ds_write_b128.
+//
+// LDS tile layout, in units of 16 bytes (= 8 k-values of one n or one row):
+//   M tile  [KB/8 kgroups][8 j][32 g]     vector (kg, j, g) holds n = n0 + 8 g + j
+//   X tile  [KB/8 kgroups][XS]            vector (kg, row)
+// so MFMA tile j of the 256-wide n tile reads 32 consecutive vectors (lanes 0..31: kgroup 2s,
+// lanes 32..63: kgroup 2s + 1, for k-step s), and its result element i of lane l is
+//   n = n0 + 8 m + j,  m = 8 (i / 4) + 4 (l / 32) + (i % 4),   row = l % 32.
+#pragma once
+#include "device_utils.hpp"
+
+namespace slimspec {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kKB = 64;          // k per LDS stage
+constexpr int kKG = kKB / 8;     // k-groups of 8 per stage
+constexpr int kNT = 256;         // n (vocabulary / rank columns) per tile
+
+// WR x WV wavefronts; a wavefront owns TR row tiles x TV n-tiles of 32 x 32.
+template <int WR_, int WV_, int TR_, int TV_>
+struct TileCfg {
+    static constexpr int WR = WR_, WV = WV_, TR = TR_, TV = TV_;
+    static_assert(WV * TV == 8, "the n tile is 8 MFMA tiles wide");
+    static constexpr int THREADS = WR * WV * 64;
+    static constexpr int RT = WR * TR * 32;                 // rows per tile
+    static constexpr int XS = RT + 1;                       // X k-group stride (vectors); odd: spreads banks
+    static constexpr int M_VECS = kKG * kNT;                // 2048 vectors = 32 KB
+    static constexpr int X_VECS = kKG * XS;
+    static constexpr int STAGE_VECS = M_VECS + X_VECS;
+    static constexpr int LDS_BYTES = 2 * STAGE_VECS * 16;
+    static constexpr int M_TASKS = (kKG * 32) / THREADS;    // (kgroup, g) load tasks per thread
+    static_assert(M_TASKS >= 1 && M_TASKS * THREADS == kKG * 32, "thread count must divide 256");
+    static constexpr int X_PIECES = (kKG * RT + THREADS - 1) / THREADS;
+};
+
+// ---------------------------------------------------------------------------
+// M tile: global -> registers (raw bf16 rows) -> LDS (k-contiguous, f16 or bf16).
+template <class C>
+struct MRegs { uint4 w[C::M_TASKS][8]; };
+
+// K here is the end of the k range to load (rows k >= K read as zero).
+template <class C>
+__device__ __forceinline__ void load_m_regs(MRegs<C> &r, const uint16_t *__restrict__ M,
+                                            int K, int N, int k0, int n0, int tid)
+{
+#pragma unroll
+    for (int t = 0; t < C::M_TASKS; ++t) {
+        const int q = tid + t * C::THREADS;
+        const int kg = q >> 5, g = q & 31;
+        const int n = n0 + g * 8;
+        const int k = k0 + kg * 8;
+        const bool ok = (n < N) && (k < K);                 // N and K are multiples of 8
+        const uint16_t *p = M + (size_t)k * N + n;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            r.w[t][i] = ok ? *reinterpret_cast<const uint4 *>(p + (size_t)i * N) : make_uint4(0, 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ uint32_t pack_f16_from_bf16_lo(uint32_t a, uint32_t b) {
+    auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(a << 16), __uint_as_float(b << 16));
+    return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ uint32_t pack_f16_from_bf16_hi(uint32_t a, uint32_t b) {
+    auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(a & 0xffff0000u), __uint_as_float(b & 0xffff0000u));
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// 8 rows k (a[0..7]) of one 32-bit column pair -> the two k-contiguous vectors of that pair.
+template <bool F16>
+__device__ __forceinline__ void regroup_pair(const uint32_t (&a)[8], uint4 &even, uint4 &odd)
+{
+    if constexpr (F16) {
+        // every finite bf16 in the f16 range converts exactly (8 significand bits fit in 11)
+        even = make_uint4(pack_f16_from_bf16_lo(a[0], a[1]), pack_f16_from_bf16_lo(a[2], a[3]),
+                          pack_f16_from_bf16_lo(a[4], a[5]), pack_f16_from_bf16_lo(a[6], a[7]));
+        odd = make_uint4(pack_f16_from_bf16_hi(a[0], a[1]), pack_f16_from_bf16_hi(a[2], a[3]),
+                         pack_f16_from_bf16_hi(a[4], a[5]), pack_f16_from_bf16_hi(a[6], a[7]));
+    } else {
+        constexpr uint32_t LO = 0x05040100u, HI = 0x07060302u;   // v_perm_b32 byte selectors
+        even = make_uint4(__builtin_amdgcn_perm(a[1], a[0], LO), __builtin_amdgcn_perm(a[3], a[2], LO),
+                          __builtin_amdgcn_perm(a[5], a[4], LO), __builtin_amdgcn_perm(a[7], a[6], LO));
+        odd = make_uint4(__builtin_amdgcn_perm(a[1], a[0], HI), __builtin_amdgcn_perm(a[3], a[2], HI),
+                         __builtin_amdgcn_perm(a[5], a[4], HI), __builtin_amdgcn_perm(a[7], a[6], HI));
+    }
+}
+
+template <class C, bool F16>
+__device__ __forceinline__ void store_m_lds(const MRegs<C> &r, uint4 *__restrict__ m_tile, int tid)
+{
+#pragma unroll
+    for (int t = 0; t < C::M_TASKS; ++t) {
+        const int q = tid + t * C::THREADS;
+        const int kg = q >> 5, g = q & 31;
+        uint4 *dst = m_tile + (kg * 8) * 32 + g;            // + j * 32
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+            uint32_t a[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint4 &w = r.w[t][i];
+                a[i] = pr == 0 ? w.x : pr == 1 ? w.y : pr == 2 ? w.z : w.w;
+            }
+            uint4 even, odd;
+            regroup_pair<F16>(a, even, odd);
+            dst[(2 * pr) * 32] = even;
+            dst[(2 * pr + 1) * 32] = odd;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// X tile.  Two sources: the k-grouped scratch layout [K/8][rows_pad] of 16-byte vectors written
+// by the down-projection (straight copy), or row-major bf16 activations [rows, K] (h itself).
+template <class C>
+struct XRegs { uint4 w[C::X_PIECES]; };
+
+// K: end of the k range to load; ldx: row stride of row-major X (elements).
+template <class C, bool ROW_MAJOR>
+__device__ __forceinline__ void load_x_regs(XRegs<C> &r, const uint16_t *__restrict__ X,
+                                            int K, int ldx, int rows, int rows_pad, int k0, int row0, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < C::X_PIECES; ++i) {
+        const int p = tid + i * C::THREADS;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (p < kKG * C::RT) {
+            if constexpr (ROW_MAJOR) {
+                const int row = row0 + (p >> 3), k = k0 + (p & 7) * 8;
+                if (row < rows && k < K) v = *reinterpret_cast<const uint4 *>(X + (size_t)row * ldx + k);
+            } else {
+                const int kg = p / C::RT, row = row0 + p % C::RT, k = k0 + kg * 8;
+                if (k < K) v = *reinterpret_cast<const uint4 *>(X + ((size_t)(k >> 3) * rows_pad + row) * 8);
+            }
+        }
+        r.w[i] = v;
+    }
+}
+
+template <class C, bool ROW_MAJOR>
+__device__ __forceinline__ void store_x_lds(const XRegs<C> &r, uint4 *__restrict__ x_tile, int tid)
+{
+#pragma unroll
+    for (int i = 0; i < C::X_PIECES; ++i) {
+        const int p = tid + i * C::THREADS;
+        if (p < kKG * C::RT) {
+            if constexpr (ROW_MAJOR) x_tile[(p & 7) * C::XS + (p >> 3)] = r.w[i];
+            else x_tile[(p / C::RT) * C::XS + p % C::RT] = r.w[i];
+        }
+    }
+}
+
+// k-grouped X straight from global memory into an LDS tile (global_load_lds_dwordx4: no data
+// registers; the wavefront's 64 lanes land in 64 consecutive vectors).  The writes are
+// asynchronous: they are complete after the next s_waitcnt vmcnt(0) / __syncthreads().
+template <class C>
+__device__ __forceinline__ void load_x_direct(const uint16_t *__restrict__ X, uint4 *__restrict__ x_tile,
+                                              int K, int rows_pad, int k0, int row0, int wave, int lane)
+{
+    static_assert(C::RT % 64 == 0, "a wavefront must stay inside one k-group");
+#pragma unroll
+    for (int i = 0; i < C::X_PIECES; ++i) {
+        const int p0 = wave * 64 + i * C::THREADS;           // first piece of this wavefront
+        if (p0 >= kKG * C::RT) continue;
+        const int kg = p0 / C::RT, rbase = p0 % C::RT;
+        const int k = k0 + kg * 8;
+        uint4 *dst = x_tile + kg * C::XS + rbase;            // wavefront-uniform
+        if (k < K) {
+            const uint16_t *src = X + ((size_t)(k >> 3) * rows_pad + row0 + rbase + lane) * 8;
+            __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+        } else {
+            dst[lane] = make_uint4(0, 0, 0, 0);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One LDS stage (kKB of k) into the accumulators of this wavefront.
+template <bool F16>
+__device__ __forceinline__ void mfma_32x32x16(const uint4 &a, const uint4 &b, f32x16 &c)
+{
+    if constexpr (F16)
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+template <class C>
+struct Frags { uint4 x[C::TR], m[C::TV]; };
+
+template <class C>
+__device__ __forceinline__ void load_frags(Frags<C> &f, const uint4 *__restrict__ m_tile,
+                                           const uint4 *__restrict__ x_tile, int s, int wr, int wv, int lane)
+{
+    const int kg = 2 * s + (lane >> 5), l32 = lane & 31;
+#pragma unroll
+    for (int rt = 0; rt < C::TR; ++rt) f.x[rt] = x_tile[kg * C::XS + (wr * C::TR + rt) * 32 + l32];
+#pragma unroll
+    for (int j = 0; j < C::TV; ++j) f.m[j] = m_tile[(kg * 8 + wv * C::TV + j) * 32 + l32];
+}
+
+// Operands of k-step s + 1 are read from LDS while the MFMAs of k-step s run; the scheduling
+// barriers keep the compiler from hoisting all reads of the stage to the top (which would hold
+// four k-steps of operands in registers at once).
+template <class C, bool F16>
+__device__ __forceinline__ void mma_stage(f32x16 (&acc)[C::TR][C::TV], const uint4 *__restrict__ m_tile,
+                                          const uint4 *__restrict__ x_tile, int wr, int wv, int lane)
+{
+    constexpr int S = kKB / 16;
+    Frags<C> f[2];
+    load_frags<C>(f[0], m_tile, x_tile, 0, wr, wv, lane);
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        if (s + 1 < S) load_frags<C>(f[(s + 1) & 1], m_tile, x_tile, s + 1, wr, wv, lane);
+#pragma unroll
+        for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+            for (int j = 0; j < C::TV; ++j) mfma_32x32x16<F16>(f[s & 1].m[j], f[s & 1].x[rt], acc[rt][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// n offset (inside the 256-wide tile) of result element i of MFMA tile j, for a lane in half `half`
+__device__ __forceinline__ int tile_n_offset(int j, int i, int half) {
+    return 8 * (8 * (i >> 2) + 4 * half + (i & 3)) + j;
+}
+
+}  // namespace slimspec

@@ -1,0 +1,382 @@
+// Matrix-core kernels for calls with many rows (paper section 4.1).
+//
+//   down_gemm_kernel     partial sums of t = h A over a slice of d (bf16 MFMA, fp32 accumulate)
+//   down_finish_kernel   fixed-order sum of the slices -> fp32 t, f16 t in the k-grouped layout the
+//                        up-projection reads, per-row rounding statistics, an rms estimate of B
+//   head_mfma_kernel     persistent vocabulary-tiled up-projection z^T = M^T x^T with the fused
+//                        epilogue: every lane keeps, for each row it owns, a running max / sum of exp
+//                        and the L largest "group maxima" of its own share of the vocabulary; one
+//                        partial per lane stream goes to the merge.  No logit is written to memory.
+//
+// Epilogue bookkeeping.  One 32x32 MFMA tile gives a lane 16 logits of one row (a "group").  The
+// low 4 bits of each logit are replaced by its position in the group, so that plain max / min /
+// median instructions carry the argmax along; a 37-instruction network yields the group's largest
+// and second largest value.  Per (lane, row) a short list holds the L groups with the largest
+// maxima, each with its second largest value and a tag naming the group; U is the largest
+// maximum that fell off the list.  The merge knows from these bounds exactly which logits might
+// still belong to the top-k and re-evaluates those in fp32.
+#include "mfma_core.hpp"
+#include "launch.hpp"
+
+namespace slimspec {
+
+// plain VALU min / max / median without the canonicalising pre-ops the compiler adds for fmaxf
+__device__ __forceinline__ float vmax(float a, float b) { float d; asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b)); return d; }
+__device__ __forceinline__ float vmin(float a, float b) { float d; asm("v_min_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b)); return d; }
+__device__ __forceinline__ float vmed3(float a, float b, float c) { float d; asm("v_med3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c)); return d; }
+
+// ---------------------------------------------------------------------------
+// t = h A, slice z of the contraction.  grid = (ceil(r / 256), row blocks, slices).
+template <class C>
+__global__ __launch_bounds__(C::THREADS) void down_gemm_kernel(
+    const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ part,
+    int rows, int d, int r, int kslice)
+{
+    extern __shared__ uint4 lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave / C::WV, wv = wave % C::WV;
+    const int n0 = blockIdx.x * kNT, row0 = blockIdx.y * C::RT;
+    const int kbeg = blockIdx.z * kslice, kend = min(d, kbeg + kslice);
+    const int nkb = (kend - kbeg + kKB - 1) / kKB;
+
+    f32x16 acc[C::TR][C::TV];
+#pragma unroll
+    for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+        for (int j = 0; j < C::TV; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[rt][j][i] = 0.f;
+
+    MRegs<C> mr;
+    XRegs<C> xr;
+    load_m_regs<C>(mr, A, kend, r, kbeg, n0, tid);
+    load_x_regs<C, true>(xr, h, kend, d, rows, 0, kbeg, row0, tid);
+    store_m_lds<C, false>(mr, lds, tid);
+    store_x_lds<C, true>(xr, lds + C::M_VECS, tid);
+    __syncthreads();
+    for (int kb = 0; kb < nkb; ++kb) {
+        uint4 *cur = lds + (kb & 1) * C::STAGE_VECS, *nxt = lds + ((kb + 1) & 1) * C::STAGE_VECS;
+        const bool more = kb + 1 < nkb;
+        if (more) {
+            load_m_regs<C>(mr, A, kend, r, kbeg + (kb + 1) * kKB, n0, tid);
+            load_x_regs<C, true>(xr, h, kend, d, rows, 0, kbeg + (kb + 1) * kKB, row0, tid);
+        }
+        mma_stage<C, false>(acc, cur, cur + C::M_VECS, wr, wv, lane);
+        if (more) {
+            store_m_lds<C, false>(mr, nxt, tid);
+            store_x_lds<C, true>(xr, nxt + C::M_VECS, tid);
+        }
+        __syncthreads();
+    }
+    const int half = lane >> 5, l32 = lane & 31;
+    float *dst = part + (size_t)blockIdx.z * rows * r;
+#pragma unroll
+    for (int rt = 0; rt < C::TR; ++rt) {
+        const int row = row0 + (wr * C::TR + rt) * 32 + l32;
+        if (row >= rows) continue;
+#pragma unroll
+        for (int j = 0; j < C::TV; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int n = n0 + tile_n_offset(wv * C::TV + j, i, half);
+                if (n < r) dst[(size_t)row * r + n] = acc[rt][j][i];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One block per row (r / 8 threads, one 8-wide k-group each); block `rows_pad` estimates rms(B).
+//   t32   [rows_pad, r]       fp32 t (zero for padding rows)
+//   t16   [r / 8, rows_pad]   16-byte vectors of 8 f16 (round to nearest even)
+//   stat  [rows_pad]          (sum of (t - f16(t))^2, sum of t^2)
+//   brms  [1]                 sqrt(mean of B^2 over a fixed sample of entries)
+__global__ __launch_bounds__(1024) void down_finish_kernel(
+    const float *__restrict__ part, int slices, int rows, int rows_pad, int r,
+    float *__restrict__ t32, uint4 *__restrict__ t16, float2 *__restrict__ stat,
+    const uint16_t *__restrict__ B, int V, float *__restrict__ brms)
+{
+    __shared__ float red_a[16], red_b[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = (blockDim.x + 63) / 64;
+    float a = 0.f, b = 0.f;
+    const int row = blockIdx.x;
+    if (row < rows_pad) {
+        for (int kg = tid; kg < r / 8; kg += blockDim.x) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = 0.f;
+            if (row < rows) {
+                for (int s = 0; s < slices; ++s) {            // fixed order
+                    const float4 *src = reinterpret_cast<const float4 *>(part + ((size_t)s * rows + row) * r + kg * 8);
+                    float4 p = src[0], q = src[1];
+                    v[0] += p.x; v[1] += p.y; v[2] += p.z; v[3] += p.w;
+                    v[4] += q.x; v[5] += q.y; v[6] += q.z; v[7] += q.w;
+                }
+            }
+            float4 *o = reinterpret_cast<float4 *>(t32 + (size_t)row * r + kg * 8);
+            o[0] = make_float4(v[0], v[1], v[2], v[3]);
+            o[1] = make_float4(v[4], v[5], v[6], v[7]);
+            f16x8 hv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                hv[e] = (_Float16)v[e];
+                float dlt = v[e] - (float)hv[e];
+                a += dlt * dlt;
+                b += v[e] * v[e];
+            }
+            t16[(size_t)kg * rows_pad + row] = __builtin_bit_cast(uint4, hv);
+        }
+    } else {
+        // sample: 8 adjacent entries of every row of B at 16 column positions spread over V
+        const int npos = 16;
+        for (int q = tid; q < r * npos; q += blockDim.x) {
+            const int j = q / npos, pos = q % npos;
+            const int col = (int)(((long long)pos * (V / 8)) / npos) * 8;
+            uint4 w = *reinterpret_cast<const uint4 *>(B + (size_t)j * V + col);
+            float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                          bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a += f[e] * f[e];
+        }
+        b = 0.f;
+    }
+    a = wave_sum(a);
+    b = wave_sum(b);
+    if (lane == 0) { red_a[wave] = a; red_b[wave] = b; }
+    __syncthreads();
+    if (tid == 0) {
+        float sa = 0.f, sb = 0.f;
+        for (int w = 0; w < nw; ++w) { sa += red_a[w]; sb += red_b[w]; }
+        if (row < rows_pad) stat[row] = make_float2(sa, sb);
+        else brms[0] = sqrtf(sa / (float)(r * 16 * 8));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-lane stream of one row.
+template <int L>
+struct Stream {
+    float mc, s, U;          // running max (times log2 e), sum of exp relative to it, best dropped group maximum
+    float x[L], y[L];        // group maxima (low 4 bits = position in the group) and second largest values
+    int tag[L];              // group name: vocabulary tile * 8 + MFMA tile
+};
+
+constexpr float kNegBig = -3.0e38f;     // stands for "no value" (finite, so that tagging its low bits stays a number)
+
+template <int L>
+__device__ __forceinline__ void stream_init(Stream<L> &st) {
+    st.mc = kNegBig; st.s = 0.f; st.U = kNegBig;
+#pragma unroll
+    for (int l = 0; l < L; ++l) { st.x[l] = kNegBig; st.y[l] = kNegBig; st.tag[l] = 0; }
+}
+
+// Fold one group (16 logits of one row) into the stream.
+template <int L>
+__device__ __forceinline__ void stream_group(Stream<L> &st, const float (&v)[16], int tag)
+{
+    float p[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) p[i] = __uint_as_float((__float_as_uint(v[i]) & 0xfffffff0u) | (uint32_t)i);
+    // largest and second largest of the 16 tagged values
+    float a[8], b[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { a[q] = vmax(p[2 * q], p[2 * q + 1]); b[q] = vmin(p[2 * q], p[2 * q + 1]); }
+#pragma unroll
+    for (int w = 4; w >= 1; w >>= 1)
+#pragma unroll
+        for (int q = 0; q < w; ++q) {
+            float hi = vmax(a[2 * q], a[2 * q + 1]);
+            float lo = vmed3(a[2 * q], a[2 * q + 1], vmax(b[2 * q], b[2 * q + 1]));
+            a[q] = hi; b[q] = lo;
+        }
+    float gm = a[0], g2 = b[0];
+
+    // running log-sum-exp (base 2 inside)
+    const float mc_new = vmax(st.mc, gm * kLog2e);
+    float sum = st.s * __builtin_amdgcn_exp2f(st.mc - mc_new);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(v[i], kLog2e, -mc_new));
+    st.s = sum;
+    st.mc = mc_new;
+
+    // keep the L groups with the largest maxima
+    int tg = tag;
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        const bool c = gm > st.x[l];
+        const float nx = c ? gm : st.x[l], ny = c ? g2 : st.y[l];
+        const int nt = c ? tg : st.tag[l];
+        gm = c ? st.x[l] : gm; g2 = c ? st.y[l] : g2; tg = c ? st.tag[l] : tg;
+        st.x[l] = nx; st.y[l] = ny; st.tag[l] = nt;
+    }
+    st.U = vmax(st.U, gm);
+}
+
+// Work of block g: row block rb and the vocabulary tiles col, col + gw, col + 2 gw, ...
+// Blocks are dealt round-robin to the 8 XCDs, so blocks g and g + 8 share an L2: they get the same
+// vocabulary tiles and different row blocks, and so read each tile of M from HBM once.
+struct HeadGrid { int n_rb, gw, n_vt; };
+
+template <class C, bool F16, bool XROW, int L>
+__global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
+    const uint16_t *__restrict__ X, const uint16_t *__restrict__ M, float *__restrict__ part,
+    int rows, int rows_pad, int K, int V, HeadGrid hg)
+{
+    extern __shared__ uint4 lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave / C::WV, wv = wave % C::WV;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int rb = slot % hg.n_rb, col = (slot / hg.n_rb) * 8 + xcd;
+    const int row0 = rb * C::RT;
+    const int nkb = (K + kKB - 1) / kKB;
+    const int njobs = (col < hg.n_vt) ? (hg.n_vt - col + hg.gw - 1) / hg.gw : 0;
+    const int total = njobs * nkb;
+
+    Stream<L> st[C::TR];
+#pragma unroll
+    for (int rt = 0; rt < C::TR; ++rt) stream_init(st[rt]);
+    f32x16 acc[C::TR][C::TV];
+#pragma unroll
+    for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+        for (int j = 0; j < C::TV; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[rt][j][i] = 0.f;
+
+    MRegs<C> mr;
+    XRegs<C> xr;        // used only for row-major X; k-grouped X goes straight to LDS
+    if (total > 0) {
+        load_m_regs<C>(mr, M, K, V, 0, col * kNT, tid);
+        if constexpr (XROW) load_x_regs<C, true>(xr, X, K, K, rows, rows_pad, 0, row0, tid);
+        else load_x_direct<C>(X, lds + C::M_VECS, K, rows_pad, 0, row0, wave, lane);
+        store_m_lds<C, F16>(mr, lds, tid);
+        if constexpr (XROW) store_x_lds<C, true>(xr, lds + C::M_VECS, tid);
+    }
+    __syncthreads();
+    int vt = col, kb = 0;
+    for (int q = 0; q < total; ++q) {
+        uint4 *cur = lds + (q & 1) * C::STAGE_VECS, *nxt = lds + ((q + 1) & 1) * C::STAGE_VECS;
+        const bool more = q + 1 < total;
+        int vt_n = vt, kb_n = kb + 1;
+        if (kb_n == nkb) { kb_n = 0; vt_n = vt + hg.gw; }
+        if (more) {
+            load_m_regs<C>(mr, M, K, V, kb_n * kKB, vt_n * kNT, tid);
+            if constexpr (XROW) load_x_regs<C, true>(xr, X, K, K, rows, rows_pad, kb_n * kKB, row0, tid);
+            else load_x_direct<C>(X, nxt + C::M_VECS, K, rows_pad, kb_n * kKB, row0, wave, lane);
+        }
+        mma_stage<C, F16>(acc, cur, cur + C::M_VECS, wr, wv, lane);
+        if (kb == nkb - 1) {
+            const int n0 = vt * kNT;
+            const bool tail = n0 + kNT > V;
+            const int mlim = (V - n0) >> 3;               // groups of 8 columns that exist in this tile
+#pragma unroll
+            for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+                for (int j = 0; j < C::TV; ++j) {
+                    float v[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        v[i] = acc[rt][j][i];
+                        acc[rt][j][i] = 0.f;
+                    }
+                    if (tail) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            if (8 * (i >> 2) + 4 * half + (i & 3) >= mlim) v[i] = kNegBig;
+                    }
+                    stream_group<L>(st[rt], v, vt * 8 + wv * C::TV + j);
+                    __builtin_amdgcn_sched_barrier(0);      // one group at a time: keeps register pressure flat
+                }
+        }
+        if (more) {
+            store_m_lds<C, F16>(mr, nxt, tid);
+            if constexpr (XROW) store_x_lds<C, true>(xr, nxt + C::M_VECS, tid);
+        }
+        __syncthreads();
+        vt = vt_n; kb = kb_n;
+    }
+    // one partial per (row, stream): stream = (col * WV + wv) * 2 + half
+    const int nsr = hg.gw * C::WV * 2;
+    const int sidx = (col * C::WV + wv) * 2 + half;
+    constexpr int REC = 3 + 3 * L;
+#pragma unroll
+    for (int rt = 0; rt < C::TR; ++rt) {
+        const int row = row0 + (wr * C::TR + rt) * 32 + l32;
+        if (row >= rows) continue;
+        float *o = part + ((size_t)row * nsr + sidx) * REC;
+        o[0] = st[rt].mc; o[1] = st[rt].s; o[2] = st[rt].U;
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            o[3 + 3 * l] = st[rt].x[l];
+            o[4 + 3 * l] = st[rt].y[l];
+            o[5 + 3 * l] = __int_as_float(st[rt].tag[l]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+
+using CfgMid = TileCfg<2, 2, 2, 4>;      // 128 rows x 256 columns per block, rows > 64
+using CfgSmall = TileCfg<1, 4, 2, 2>;    //  64 rows; also the down-projection tile
+
+int mfma_rows_per_tile(int rows) { return rows > 64 ? CfgMid::RT : CfgSmall::RT; }
+int mfma_streams_per_block(int rows) { return 2 * (rows > 64 ? CfgMid::WV : CfgSmall::WV); }
+int mfma_cols_per_wave(int rows) { return rows > 64 ? CfgMid::TV : CfgSmall::TV; }
+
+template <class C>
+static hipError_t set_lds(const void *fn) {
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+}
+
+hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int d, int r,
+                            int slices, int kslice, hipStream_t st)
+{
+    using C = CfgSmall;
+    auto fn = down_gemm_kernel<C>;
+    hipError_t e = set_lds<C>(reinterpret_cast<const void *>(fn));
+    if (e != hipSuccess) return e;
+    dim3 grid((r + kNT - 1) / kNT, (rows + C::RT - 1) / C::RT, slices);
+    fn<<<grid, C::THREADS, C::LDS_BYTES, st>>>(h, A, part, rows, d, r, kslice);
+    return hipGetLastError();
+}
+
+hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_pad, int r,
+                              float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
+                              hipStream_t st)
+{
+    int threads = ((r / 8 + 63) / 64) * 64;
+    if (threads > 1024) threads = 1024;
+    down_finish_kernel<<<rows_pad + 1, threads, 0, st>>>(part, slices, rows, rows_pad, r, t32,
+                                                         static_cast<uint4 *>(t16), stat, B, V, brms);
+    return hipGetLastError();
+}
+
+template <class C, bool F16, bool XROW, int L>
+static hipError_t launch_head_cfg(const uint16_t *X, const uint16_t *M, float *part, int rows, int rows_pad,
+                                  int K, int V, int n_rb, int gw, hipStream_t st)
+{
+    auto fn = head_mfma_kernel<C, F16, XROW, L>;
+    hipError_t e = set_lds<C>(reinterpret_cast<const void *>(fn));
+    if (e != hipSuccess) return e;
+    HeadGrid hg{n_rb, gw, (V + kNT - 1) / kNT};
+    fn<<<n_rb * gw, C::THREADS, C::LDS_BYTES, st>>>(X, M, part, rows, rows_pad, K, V, hg);
+    return hipGetLastError();
+}
+
+hipError_t launch_head_mfma(const uint16_t *X, bool x_row_major, const uint16_t *M, float *part,
+                            int rows, int rows_pad, int K, int V, int n_rb, int gw, hipStream_t st)
+{
+    constexpr int L = kStreamList;
+#define SLIMSPEC_HEAD(C)                                                                              \
+    (x_row_major ? launch_head_cfg<C, false, true, L>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st)  \
+                 : launch_head_cfg<C, true, false, L>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
+    if (rows > 64) return SLIMSPEC_HEAD(CfgMid);
+    return SLIMSPEC_HEAD(CfgSmall);
+#undef SLIMSPEC_HEAD
+}
+
+}  // namespace slimspec

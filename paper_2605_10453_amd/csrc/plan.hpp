@@ -52,4 +52,59 @@ inline size_t merge_lds_bytes(int chunks, int k) {
 }
 constexpr size_t kMergeLdsLimit = 160 * 1024 - 1024;
 
+// ---- matrix-core path -------------------------------------------------------------------
+constexpr int kPlanSlotsPerXcd = 32;     // blocks per XCD of the persistent kernel (256 CUs / 8 XCDs)
+constexpr int kStreamListPlan = 3;       // must equal kStreamList (launch.hpp)
+constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
+
+int mfma_rows_per_tile(int rows);
+int mfma_streams_per_block(int rows);
+
+struct MfmaPlan {
+    int rows = 0, rows_pad = 0, rt = 0, n_rb = 0, gw = 0, nsr = 0, n_vt = 0;
+    int slices = 0, kslice = 0;          // down-projection split of d
+    size_t off_down_part = 0;            // fp32 [slices, rows, r]
+    size_t off_t32 = 0;                  // fp32 [rows_pad, r]
+    size_t off_t16 = 0;                  // 16-byte vectors [r / 8, rows_pad]
+    size_t off_stat = 0;                 // float2 [rows_pad]
+    size_t off_brms = 0;                 // float
+    size_t off_streams = 0;              // fp32 [rows, nsr, kStreamRec]
+    size_t bytes = 0;
+};
+
+// rows here is the number of rows of ONE launch (at most kPlanSlotsPerXcd row blocks)
+inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
+    MfmaPlan p;
+    p.rows = rows;
+    p.rt = mfma_rows_per_tile(rows);
+    p.n_rb = (rows + p.rt - 1) / p.rt;
+    p.rows_pad = p.n_rb * p.rt;
+    p.n_vt = (V + 255) / 256;
+    int colgroups = kPlanSlotsPerXcd / p.n_rb;
+    if (colgroups < 1) colgroups = 1;
+    const int need = (p.n_vt + 7) / 8;
+    if (colgroups > need) colgroups = need;
+    p.gw = 8 * colgroups;
+    p.nsr = p.gw * mfma_streams_per_block(rows);
+    size_t off = 0;
+    if (kind == HeadKind::LowRank) {
+        const int tiles = ((r + 255) / 256) * ((rows + 63) / 64);
+        int slices = 256 / tiles;
+        if (slices > d / 256) slices = d / 256;
+        if (slices < 1) slices = 1;
+        p.kslice = (((d + slices - 1) / slices) + 63) / 64 * 64;
+        p.slices = (d + p.kslice - 1) / p.kslice;
+        p.off_down_part = off; off = align_up(off + sizeof(float) * (size_t)p.slices * rows * r);
+        p.off_t32 = off;       off = align_up(off + sizeof(float) * (size_t)p.rows_pad * r);
+        p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * r);
+        p.off_stat = off;      off = align_up(off + 2 * sizeof(float) * (size_t)p.rows_pad);
+        p.off_brms = off;      off = align_up(off + sizeof(float));
+    }
+    p.off_streams = off;       off = align_up(off + sizeof(float) * (size_t)rows * p.nsr * kStreamRecPlan);
+    p.bytes = off;
+    return p;
+}
+inline int mfma_max_rows_per_launch(int rows) { return kPlanSlotsPerXcd * mfma_rows_per_tile(rows); }
+size_t merge_streams_lds_bytes(int nsr, int k);
+
 }  // namespace slimspec

@@ -39,6 +39,65 @@ int check_shape(HeadKind kind, const slimspec_shape *s, int32_t k)
     return SLIMSPEC_OK;
 }
 
+constexpr int kMfmaMaxK = 16;      // the lane streams keep 3 groups: enough for k <= 16 (larger k: streaming path)
+
+size_t mfma_workspace_bytes(HeadKind kind, const slimspec_shape *s)
+{
+    const int per = mfma_max_rows_per_launch(s->rows);
+    const int rows0 = s->rows < per ? s->rows : per;
+    return make_mfma_plan(kind, rows0, s->d, s->r, s->V).bytes;
+}
+
+int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
+                  const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
+                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (workspace_bytes < mfma_workspace_bytes(kind, shape)) return SLIMSPEC_WORKSPACE_TOO_SMALL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    const int d = shape->d, r = shape->r, V = shape->V;
+    const int per = mfma_max_rows_per_launch(shape->rows);
+    const uint16_t *hb = static_cast<const uint16_t *>(h);
+    const uint16_t *Mb = static_cast<const uint16_t *>(M);
+    for (int row0 = 0; row0 < shape->rows; row0 += per) {
+        const int rows = (shape->rows - row0 < per) ? shape->rows - row0 : per;
+        // a last, smaller batch may fall below the matrix-core threshold; it still runs here
+        const MfmaPlan p = make_mfma_plan(kind, rows, d, r, V);
+        float *streams = reinterpret_cast<float *>(ws + p.off_streams);
+        const uint16_t *hrow = hb + (size_t)row0 * d;
+        const int n_wv = mfma_streams_per_block(rows) / 2, tv = mfma_cols_per_wave(rows);
+        hipError_t e;
+        const bool timed = g_ev_start && row0 == 0;
+        if (kind == HeadKind::LowRank) {
+            float *down_part = reinterpret_cast<float *>(ws + p.off_down_part);
+            float *t32 = reinterpret_cast<float *>(ws + p.off_t32);
+            void *t16 = ws + p.off_t16;
+            float2 *stat = reinterpret_cast<float2 *>(ws + p.off_stat);
+            float *brms = reinterpret_cast<float *>(ws + p.off_brms);
+            e = launch_down_gemm(hrow, static_cast<const uint16_t *>(A), down_part, rows, d, r, p.slices, p.kslice, s);
+            if (e != hipSuccess) return fail_hip(e);
+            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, s);
+            if (e != hipSuccess) return fail_hip(e);
+            if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
+            e = launch_head_mfma(static_cast<const uint16_t *>(t16), false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
+            if (e != hipSuccess) return fail_hip(e);
+            if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, t32, false, r, Mb, r, V, stat, brms, k,
+                                     out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+            if (e != hipSuccess) return fail_hip(e);
+        } else {
+            if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
+            e = launch_head_mfma(hrow, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, s);
+            if (e != hipSuccess) return fail_hip(e);
+            if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, hrow, true, d, Mb, d, V, nullptr, nullptr, k,
+                                     out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+            if (e != hipSuccess) return fail_hip(e);
+        }
+    }
+    return SLIMSPEC_OK;
+}
+
 int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_is_f32,
              const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
              void *workspace, size_t workspace_bytes, void *stream)
@@ -51,6 +110,9 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         return SLIMSPEC_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(out_ids) & 3u) || (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
         return SLIMSPEC_UNSUPPORTED;
+    const bool use_mfma = shape->rows > kGemvMaxRows && !m_is_f32 && k <= kMfmaMaxK;
+    if (use_mfma)
+        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
     const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
     if (workspace_bytes < p.bytes) return SLIMSPEC_WORKSPACE_TOO_SMALL;
 
@@ -95,11 +157,21 @@ size_t slimspec_workspace_bytes(const slimspec_shape *shape, int32_t k)
 {
     if (!shape) return 0;
     size_t need = 0;
-    if (check_shape(HeadKind::Full, shape, k) == SLIMSPEC_OK)
+    // the larger of: streaming path (also serves fp32 W and large k), matrix-core path, for both heads
+    if (check_shape(HeadKind::Full, shape, k) == SLIMSPEC_OK) {
         need = make_plan(HeadKind::Full, shape->rows, shape->d, shape->r, shape->V, k).bytes;
+        if (shape->rows > kGemvMaxRows) {
+            size_t m = mfma_workspace_bytes(HeadKind::Full, shape);
+            if (m > need) need = m;
+        }
+    }
     if (check_shape(HeadKind::LowRank, shape, k) == SLIMSPEC_OK) {
         size_t lo = make_plan(HeadKind::LowRank, shape->rows, shape->d, shape->r, shape->V, k).bytes;
         if (lo > need) need = lo;
+        if (shape->rows > kGemvMaxRows) {
+            size_t m = mfma_workspace_bytes(HeadKind::LowRank, shape);
+            if (m > need) need = m;
+        }
     }
     return need;
 }
