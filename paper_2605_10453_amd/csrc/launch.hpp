@@ -29,7 +29,7 @@ constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial
 int mfma_cols_per_wave(int rows);       // MFMA tiles (of the 8 in a 256-wide tile) owned by one wavefront
 
 // partial sums of t = h A over `slices` slices of d (kslice entries each, a multiple of 64)
-hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int d, int r,
+hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int rows_pad, int d, int r,
                             int slices, int kslice, hipStream_t st);
 // slices -> fp32 t, f16 t (k-grouped), per-row rounding statistics, rms estimate of B
 hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_pad, int r,
@@ -43,7 +43,7 @@ hipError_t launch_head_mfma(const uint16_t *X, bool x_row_major, const uint16_t 
 // stream partials -> final ids / log-probabilities, with exact fp32 re-evaluation of uncertain ranks
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
-                                const float2 *stat, const float *brms, int k,
+                                const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
                                 int32_t *out_ids, float *out_logprobs, hipStream_t st);
 
 }  // namespace slimspec

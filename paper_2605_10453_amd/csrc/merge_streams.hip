@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const float *__restrict__ part, int nsr, int gw, int n_wv, int tv, int n_vt,
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
-    const float2 *__restrict__ stat, const float *__restrict__ brms,
+    const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ brms,
     int k, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
@@ -152,7 +152,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const bool have_tau = tau_key != kNoKey;
     const float tau = have_tau ? key_value(tau_key) : kNegInf;
     float eps;
-    if (stat != nullptr) eps = kEpsSigmas * sqrtf(stat[row].x) * brms[0] + fabsf(tau) * 1.2e-5f + 1e-30f;
+    if (stat != nullptr) {
+        float dt2 = 0.f;                                     // squared norm of t - f16(t), summed in a fixed order
+        for (int q = 0; q < n_stat; ++q) dt2 += stat[(size_t)q * rows_pad + row].x;
+        eps = kEpsSigmas * sqrtf(dt2) * brms[0] + fabsf(tau) * 1.2e-5f + 1e-30f;
+    }
     else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
     const float theta = have_tau ? tau - 2.f * eps : kNegInf;
     bool exhaustive = !(eps < 1e30f) || !(lse == lse) || !(fabsf(lse) < 1e30f);   // overflow of the 16-bit input
@@ -303,7 +307,7 @@ size_t merge_streams_lds_bytes(int nsr, int k) {
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
-                                const float2 *stat, const float *brms, int k,
+                                const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
                                 int32_t *out_ids, float *out_logprobs, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k);
@@ -311,7 +315,7 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_wv, tv, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, brms, k, out_ids, out_logprobs);
+                                                           M, K, V, stat, n_stat, rows_pad, brms, k, out_ids, out_logprobs);
     return hipGetLastError();
 }
 

@@ -103,28 +103,35 @@ __device__ __forceinline__ void regroup_pair(const uint32_t (&a)[8], uint4 &even
     }
 }
 
-template <class C, bool F16>
-__device__ __forceinline__ void store_m_lds(const MRegs<C> &r, uint4 *__restrict__ m_tile, int tid)
+// Quarter PR (0..3) of the regroup-and-store of a loaded M tile: column pair PR of every task.
+template <class C, bool F16, int PR>
+__device__ __forceinline__ void store_m_quarter(const MRegs<C> &r, uint4 *__restrict__ m_tile, int tid)
 {
 #pragma unroll
     for (int t = 0; t < C::M_TASKS; ++t) {
         const int q = tid + t * C::THREADS;
         const int kg = q >> 5, g = q & 31;
         uint4 *dst = m_tile + (kg * 8) * 32 + g;            // + j * 32
+        uint32_t a[8];
 #pragma unroll
-        for (int pr = 0; pr < 4; ++pr) {
-            uint32_t a[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint4 &w = r.w[t][i];
-                a[i] = pr == 0 ? w.x : pr == 1 ? w.y : pr == 2 ? w.z : w.w;
-            }
-            uint4 even, odd;
-            regroup_pair<F16>(a, even, odd);
-            dst[(2 * pr) * 32] = even;
-            dst[(2 * pr + 1) * 32] = odd;
+        for (int i = 0; i < 8; ++i) {
+            const uint4 &w = r.w[t][i];
+            a[i] = PR == 0 ? w.x : PR == 1 ? w.y : PR == 2 ? w.z : w.w;
         }
+        uint4 even, odd;
+        regroup_pair<F16>(a, even, odd);
+        dst[(2 * PR) * 32] = even;
+        dst[(2 * PR + 1) * 32] = odd;
     }
+}
+
+template <class C, bool F16>
+__device__ __forceinline__ void store_m_lds(const MRegs<C> &r, uint4 *__restrict__ m_tile, int tid)
+{
+    store_m_quarter<C, F16, 0>(r, m_tile, tid);
+    store_m_quarter<C, F16, 1>(r, m_tile, tid);
+    store_m_quarter<C, F16, 2>(r, m_tile, tid);
+    store_m_quarter<C, F16, 3>(r, m_tile, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -220,15 +227,34 @@ __device__ __forceinline__ void load_frags(Frags<C> &f, const uint4 *__restrict_
 // Operands of k-step s + 1 are read from LDS while the MFMAs of k-step s run; the scheduling
 // barriers keep the compiler from hoisting all reads of the stage to the top (which would hold
 // four k-steps of operands in registers at once).
+//
+// `fresh` starts a new accumulation: the first k-step then takes a zero C operand instead of the
+// old accumulators.  The accumulators are never written by anything but an MFMA and are read (in
+// the epilogues) only through read_acc(), so that the register allocator can keep them in AGPRs
+// for the whole kernel instead of copying them in and out of VGPRs around every stage.
 template <class C, bool F16>
 __device__ __forceinline__ void mma_stage(f32x16 (&acc)[C::TR][C::TV], const uint4 *__restrict__ m_tile,
-                                          const uint4 *__restrict__ x_tile, int wr, int wv, int lane)
+                                          const uint4 *__restrict__ x_tile, int wr, int wv, int lane, bool fresh)
 {
     constexpr int S = kKB / 16;
     Frags<C> f[2];
     load_frags<C>(f[0], m_tile, x_tile, 0, wr, wv, lane);
+    load_frags<C>(f[1], m_tile, x_tile, 1, wr, wv, lane);
+    if (fresh) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int s = 0; s < S; ++s) {
+        for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+            for (int j = 0; j < C::TV; ++j) { acc[rt][j] = zero; mfma_32x32x16<F16>(f[0].m[j], f[0].x[rt], acc[rt][j]); }
+    } else {
+#pragma unroll
+        for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+            for (int j = 0; j < C::TV; ++j) mfma_32x32x16<F16>(f[0].m[j], f[0].x[rt], acc[rt][j]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 1; s < S; ++s) {
         if (s + 1 < S) load_frags<C>(f[(s + 1) & 1], m_tile, x_tile, s + 1, wr, wv, lane);
 #pragma unroll
         for (int rt = 0; rt < C::TR; ++rt)
@@ -236,6 +262,63 @@ __device__ __forceinline__ void mma_stage(f32x16 (&acc)[C::TR][C::TV], const uin
             for (int j = 0; j < C::TV; ++j) mfma_32x32x16<F16>(f[s & 1].m[j], f[s & 1].x[rt], acc[rt][j]);
         __builtin_amdgcn_sched_barrier(0);
     }
+}
+
+// The same stage, with the regroup-and-store of the NEXT stage's M tile (already in registers)
+// spread over its four k-steps: the matrix cores work through the 8 MFMAs of a k-step while the
+// wavefront issues one quarter of the conversion and its LDS writes.
+template <class C, bool F16>
+__device__ __forceinline__ void mma_stage_and_store(f32x16 (&acc)[C::TR][C::TV], const uint4 *__restrict__ m_tile,
+                                                    const uint4 *__restrict__ x_tile, int wr, int wv, int lane, bool fresh,
+                                                    const MRegs<C> &next_regs, uint4 *__restrict__ next_m_tile, bool do_store, int tid)
+{
+    static_assert(kKB / 16 == 4, "four k-steps, four quarters");
+    Frags<C> f[2];
+    load_frags<C>(f[0], m_tile, x_tile, 0, wr, wv, lane);
+    load_frags<C>(f[1], m_tile, x_tile, 1, wr, wv, lane);
+    if (fresh) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+            for (int j = 0; j < C::TV; ++j) { acc[rt][j] = zero; mfma_32x32x16<F16>(f[0].m[j], f[0].x[rt], acc[rt][j]); }
+    } else {
+#pragma unroll
+        for (int rt = 0; rt < C::TR; ++rt)
+#pragma unroll
+            for (int j = 0; j < C::TV; ++j) mfma_32x32x16<F16>(f[0].m[j], f[0].x[rt], acc[rt][j]);
+    }
+    if (do_store) store_m_quarter<C, F16, 0>(next_regs, next_m_tile, tid);
+    __builtin_amdgcn_sched_barrier(0);
+#define SLIMSPEC_KSTEP(S)                                                                               \
+    if (S + 1 < 4) load_frags<C>(f[(S + 1) & 1], m_tile, x_tile, S + 1, wr, wv, lane);                  \
+    _Pragma("unroll") for (int rt = 0; rt < C::TR; ++rt)                                                \
+        _Pragma("unroll") for (int j = 0; j < C::TV; ++j)                                               \
+            mfma_32x32x16<F16>(f[S & 1].m[j], f[S & 1].x[rt], acc[rt][j]);                              \
+    if (do_store) store_m_quarter<C, F16, S>(next_regs, next_m_tile, tid);                              \
+    __builtin_amdgcn_sched_barrier(0);
+    SLIMSPEC_KSTEP(1) SLIMSPEC_KSTEP(2) SLIMSPEC_KSTEP(3)
+#undef SLIMSPEC_KSTEP
+}
+
+// one accumulator element, read straight from its AGPR
+__device__ __forceinline__ float read_acc(const float &a) {
+    float v;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
+// Block-wide barrier that orders LDS traffic only.  PENDING = number of the youngest global loads
+// each thread may leave in flight (the register prefetch of the stage after next); everything
+// older (the direct-to-LDS loads of the next stage) completes first because vector memory returns
+// in issue order.
+template <int PENDING>
+__device__ __forceinline__ void lds_barrier_keep_loads() {
+    static_assert(PENDING >= 0 && PENDING < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt(0x0070 | (PENDING & 15) | ((PENDING >> 4) << 14));   // vmcnt(PENDING) expcnt(7) lgkmcnt(0)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // n offset (inside the 256-wide tile) of result element i of MFMA tile j, for a lane in half `half`

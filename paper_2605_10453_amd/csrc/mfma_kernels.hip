@@ -17,6 +17,7 @@
 // still belong to the top-k and re-evaluates those in fp32.
 #include "mfma_core.hpp"
 #include "launch.hpp"
+#include <type_traits>
 
 namespace slimspec {
 
@@ -30,7 +31,7 @@ __device__ __forceinline__ float vmed3(float a, float b, float c) { float d; asm
 template <class C>
 __global__ __launch_bounds__(C::THREADS) void down_gemm_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ part,
-    int rows, int d, int r, int kslice)
+    int rows, int ld, int d, int r, int kslice)
 {
     extern __shared__ uint4 lds[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -41,13 +42,6 @@ __global__ __launch_bounds__(C::THREADS) void down_gemm_kernel(
     const int nkb = (kend - kbeg + kKB - 1) / kKB;
 
     f32x16 acc[C::TR][C::TV];
-#pragma unroll
-    for (int rt = 0; rt < C::TR; ++rt)
-#pragma unroll
-        for (int j = 0; j < C::TV; ++j)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[rt][j][i] = 0.f;
-
     MRegs<C> mr;
     XRegs<C> xr;
     load_m_regs<C>(mr, A, kend, r, kbeg, n0, tid);
@@ -62,95 +56,102 @@ __global__ __launch_bounds__(C::THREADS) void down_gemm_kernel(
             load_m_regs<C>(mr, A, kend, r, kbeg + (kb + 1) * kKB, n0, tid);
             load_x_regs<C, true>(xr, h, kend, d, rows, 0, kbeg + (kb + 1) * kKB, row0, tid);
         }
-        mma_stage<C, false>(acc, cur, cur + C::M_VECS, wr, wv, lane);
+        mma_stage<C, false>(acc, cur, cur + C::M_VECS, wr, wv, lane, kb == 0);
         if (more) {
             store_m_lds<C, false>(mr, nxt, tid);
             store_x_lds<C, true>(xr, nxt + C::M_VECS, tid);
         }
         __syncthreads();
     }
+    // partial sums are stored column-major, part[slice][n][ld]: the 32 lanes of a half-wavefront hold
+    // 32 consecutive rows of one n, so every store instruction writes two full 128-byte lines
     const int half = lane >> 5, l32 = lane & 31;
-    float *dst = part + (size_t)blockIdx.z * rows * r;
+    float *dst = part + (size_t)blockIdx.z * r * ld;
 #pragma unroll
     for (int rt = 0; rt < C::TR; ++rt) {
-        const int row = row0 + (wr * C::TR + rt) * 32 + l32;
-        if (row >= rows) continue;
+        const int row = row0 + (wr * C::TR + rt) * 32 + l32;      // < ld by construction
 #pragma unroll
         for (int j = 0; j < C::TV; ++j)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int n = n0 + tile_n_offset(wv * C::TV + j, i, half);
-                if (n < r) dst[(size_t)row * r + n] = acc[rt][j][i];
+                if (n < r) dst[(size_t)n * ld + row] = read_acc(acc[rt][j][i]);
             }
     }
 }
 
 // ---------------------------------------------------------------------------
-// One block per row (r / 8 threads, one 8-wide k-group each); block `rows_pad` estimates rms(B).
+// Fixed-order sum of the slices.  grid = (rows_pad / 64 + 1, ceil(r / 32)); block (bx, by) of 256
+// threads owns rows [64 bx, 64 bx + 64) and the four 8-wide k-groups 4 by .. 4 by + 3 (thread =
+// (row, k-group)); the extra block row bx = rows_pad / 64 estimates rms(B) (by = 0 only).
+//   part  [slices, r, ld]     fp32 partial sums, ld = rows_pad
 //   t32   [rows_pad, r]       fp32 t (zero for padding rows)
 //   t16   [r / 8, rows_pad]   16-byte vectors of 8 f16 (round to nearest even)
-//   stat  [rows_pad]          (sum of (t - f16(t))^2, sum of t^2)
+//   stat  [ceil(r / 32), rows_pad]   per block column: (sum of (t - f16(t))^2, sum of t^2) of its 32 entries
 //   brms  [1]                 sqrt(mean of B^2 over a fixed sample of entries)
-__global__ __launch_bounds__(1024) void down_finish_kernel(
+constexpr int kBrmsPositions = 4;
+
+__global__ __launch_bounds__(256) void down_finish_kernel(
     const float *__restrict__ part, int slices, int rows, int rows_pad, int r,
     float *__restrict__ t32, uint4 *__restrict__ t16, float2 *__restrict__ stat,
     const uint16_t *__restrict__ B, int V, float *__restrict__ brms)
 {
-    __shared__ float red_a[16], red_b[16];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nw = (blockDim.x + 63) / 64;
-    float a = 0.f, b = 0.f;
-    const int row = blockIdx.x;
-    if (row < rows_pad) {
-        for (int kg = tid; kg < r / 8; kg += blockDim.x) {
-            float v[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = 0.f;
-            if (row < rows) {
-                for (int s = 0; s < slices; ++s) {            // fixed order
-                    const float4 *src = reinterpret_cast<const float4 *>(part + ((size_t)s * rows + row) * r + kg * 8);
-                    float4 p = src[0], q = src[1];
-                    v[0] += p.x; v[1] += p.y; v[2] += p.z; v[3] += p.w;
-                    v[4] += q.x; v[5] += q.y; v[6] += q.z; v[7] += q.w;
-                }
-            }
-            float4 *o = reinterpret_cast<float4 *>(t32 + (size_t)row * r + kg * 8);
-            o[0] = make_float4(v[0], v[1], v[2], v[3]);
-            o[1] = make_float4(v[4], v[5], v[6], v[7]);
-            f16x8 hv;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                hv[e] = (_Float16)v[e];
-                float dlt = v[e] - (float)hv[e];
-                a += dlt * dlt;
-                b += v[e] * v[e];
-            }
-            t16[(size_t)kg * rows_pad + row] = __builtin_bit_cast(uint4, hv);
-        }
-    } else {
-        // sample: 8 adjacent entries of every row of B at 16 column positions spread over V
-        const int npos = 16;
-        for (int q = tid; q < r * npos; q += blockDim.x) {
-            const int j = q / npos, pos = q % npos;
-            const int col = (int)(((long long)pos * (V / 8)) / npos) * 8;
-            uint4 w = *reinterpret_cast<const uint4 *>(B + (size_t)j * V + col);
-            float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
-                          bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+    __shared__ float red_a[4][64], red_b[4][64];
+    const int tid = threadIdx.x, lane = tid & 63, kgl = tid >> 6;
+    if ((int)blockIdx.x * 64 >= rows_pad) {
+        if (blockIdx.y != 0) return;
+        // sample: 8 adjacent entries of every row of B at a few column positions spread over V
+        float a = 0.f;
+        for (int q = tid; q < r * kBrmsPositions; q += 256) {
+            const int j = q / kBrmsPositions, pos = q % kBrmsPositions;
+            const int col = (int)(((long long)pos * (V / 8)) / kBrmsPositions) * 8;
+            const uint4 w = *reinterpret_cast<const uint4 *>(B + (size_t)j * V + col);
+            const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
 #pragma unroll
             for (int e = 0; e < 8; ++e) a += f[e] * f[e];
         }
-        b = 0.f;
+        a = wave_sum(a);
+        if (lane == 0) red_a[kgl][0] = a;
+        __syncthreads();
+        if (tid == 0)
+            brms[0] = sqrtf((((red_a[0][0] + red_a[1][0]) + red_a[2][0]) + red_a[3][0]) / (float)(r * kBrmsPositions * 8));
+        return;
     }
-    a = wave_sum(a);
-    b = wave_sum(b);
-    if (lane == 0) { red_a[wave] = a; red_b[wave] = b; }
+    const int row = blockIdx.x * 64 + lane;
+    const int kg = blockIdx.y * 4 + kgl;
+    float a = 0.f, b = 0.f;
+    if (kg < r / 8) {
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0.f;
+        if (row < rows) {
+            for (int s = 0; s < slices; ++s) {                // fixed order
+                const float *src = part + ((size_t)s * r + kg * 8) * rows_pad + row;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] += src[(size_t)e * rows_pad];
+            }
+        }
+        float4 *o = reinterpret_cast<float4 *>(t32 + (size_t)row * r + kg * 8);
+        o[0] = make_float4(v[0], v[1], v[2], v[3]);
+        o[1] = make_float4(v[4], v[5], v[6], v[7]);
+        f16x8 hv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            hv[e] = (_Float16)v[e];
+            const float dlt = v[e] - (float)hv[e];
+            a += dlt * dlt;
+            b += v[e] * v[e];
+        }
+        t16[(size_t)kg * rows_pad + row] = __builtin_bit_cast(uint4, hv);
+    }
+    red_a[kgl][lane] = a;
+    red_b[kgl][lane] = b;
     __syncthreads();
-    if (tid == 0) {
-        float sa = 0.f, sb = 0.f;
-        for (int w = 0; w < nw; ++w) { sa += red_a[w]; sb += red_b[w]; }
-        if (row < rows_pad) stat[row] = make_float2(sa, sb);
-        else brms[0] = sqrtf(sa / (float)(r * 16 * 8));
-    }
+    if (kgl == 0)
+        stat[(size_t)blockIdx.y * rows_pad + row] =
+            make_float2(((red_a[0][lane] + red_a[1][lane]) + red_a[2][lane]) + red_a[3][lane],
+                        ((red_b[0][lane] + red_b[1][lane]) + red_b[2][lane]) + red_b[3][lane]);
 }
 
 // ---------------------------------------------------------------------------
@@ -239,35 +240,46 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
 #pragma unroll
     for (int rt = 0; rt < C::TR; ++rt) stream_init(st[rt]);
     f32x16 acc[C::TR][C::TV];
-#pragma unroll
-    for (int rt = 0; rt < C::TR; ++rt)
-#pragma unroll
-        for (int j = 0; j < C::TV; ++j)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[rt][j][i] = 0.f;
-
-    MRegs<C> mr;
-    XRegs<C> xr;        // used only for row-major X; k-grouped X goes straight to LDS
+    // Software pipeline over the flattened (tile, k-block) stages q = 0 .. total - 1:
+    //   stage q + 2: M rows -> registers (global loads issued at the start of stage q)
+    //   stage q + 1: registers -> f16/bf16 k-contiguous vectors -> LDS, interleaved with the MFMAs of
+    //                stage q; X (k-grouped) goes from global memory straight to LDS
+    //   stage q    : MFMAs from LDS
+    MRegs<C> mreg[2];
+    XRegs<C> xr;        // used only for row-major X
+    const auto stage_pos = [&](int sq, int &vt_o, int &kb_o) { vt_o = col + (sq / nkb) * hg.gw; kb_o = sq % nkb; };
     if (total > 0) {
-        load_m_regs<C>(mr, M, K, V, 0, col * kNT, tid);
         if constexpr (XROW) load_x_regs<C, true>(xr, X, K, K, rows, rows_pad, 0, row0, tid);
         else load_x_direct<C>(X, lds + C::M_VECS, K, rows_pad, 0, row0, wave, lane);
-        store_m_lds<C, F16>(mr, lds, tid);
+        load_m_regs<C>(mreg[0], M, K, V, 0, col * kNT, tid);
+        store_m_lds<C, F16>(mreg[0], lds, tid);
         if constexpr (XROW) store_x_lds<C, true>(xr, lds + C::M_VECS, tid);
-    }
-    __syncthreads();
-    int vt = col, kb = 0;
-    for (int q = 0; q < total; ++q) {
-        uint4 *cur = lds + (q & 1) * C::STAGE_VECS, *nxt = lds + ((q + 1) & 1) * C::STAGE_VECS;
-        const bool more = q + 1 < total;
-        int vt_n = vt, kb_n = kb + 1;
-        if (kb_n == nkb) { kb_n = 0; vt_n = vt + hg.gw; }
-        if (more) {
-            load_m_regs<C>(mr, M, K, V, kb_n * kKB, vt_n * kNT, tid);
-            if constexpr (XROW) load_x_regs<C, true>(xr, X, K, K, rows, rows_pad, kb_n * kKB, row0, tid);
-            else load_x_direct<C>(X, nxt + C::M_VECS, K, rows_pad, kb_n * kKB, row0, wave, lane);
+        if (total > 1) {
+            int vt1, kb1;
+            stage_pos(1, vt1, kb1);
+            load_m_regs<C>(mreg[1], M, K, V, kb1 * kKB, vt1 * kNT, tid);
         }
-        mma_stage<C, F16>(acc, cur, cur + C::M_VECS, wr, wv, lane);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);     // every load so far, including the direct-to-LDS ones
+    __syncthreads();
+
+    // one stage; PAR = q & 1 selects the LDS stage and the register set at compile time
+    auto run_stage = [&](auto par_tag, int q) {
+        constexpr int PAR = decltype(par_tag)::value;
+        uint4 *cur = lds + PAR * C::STAGE_VECS, *nxt = lds + (PAR ^ 1) * C::STAGE_VECS;
+        const bool more = q + 1 < total, more2 = q + 2 < total;
+        int vt, kb, vt1, kb1, vt2, kb2;
+        stage_pos(q, vt, kb);
+        stage_pos(q + 1, vt1, kb1);
+        stage_pos(q + 2, vt2, kb2);
+        if (more) {
+            if constexpr (XROW) load_x_regs<C, true>(xr, X, K, K, rows, rows_pad, kb1 * kKB, row0, tid);
+            else load_x_direct<C>(X, nxt + C::M_VECS, K, rows_pad, kb1 * kKB, row0, wave, lane);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (more2) load_m_regs<C>(mreg[PAR], M, K, V, kb2 * kKB, vt2 * kNT, tid);      // youngest loads of the stage
+        __builtin_amdgcn_sched_barrier(0);
+        mma_stage_and_store<C, F16>(acc, cur, cur + C::M_VECS, wr, wv, lane, kb == 0, mreg[PAR ^ 1], nxt, more, tid);
         if (kb == nkb - 1) {
             const int n0 = vt * kNT;
             const bool tail = n0 + kNT > V;
@@ -278,10 +290,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
                 for (int j = 0; j < C::TV; ++j) {
                     float v[16];
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        v[i] = acc[rt][j][i];
-                        acc[rt][j][i] = 0.f;
-                    }
+                    for (int i = 0; i < 16; ++i) v[i] = read_acc(acc[rt][j][i]);
                     if (tail) {
 #pragma unroll
                         for (int i = 0; i < 16; ++i)
@@ -291,12 +300,13 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
                     __builtin_amdgcn_sched_barrier(0);      // one group at a time: keeps register pressure flat
                 }
         }
-        if (more) {
-            store_m_lds<C, F16>(mr, nxt, tid);
-            if constexpr (XROW) store_x_lds<C, true>(xr, nxt + C::M_VECS, tid);
-        }
-        __syncthreads();
-        vt = vt_n; kb = kb_n;
+        if constexpr (XROW) { if (more) store_x_lds<C, true>(xr, nxt + C::M_VECS, tid); }
+        if (more2) lds_barrier_keep_loads<8 * C::M_TASKS>();
+        else lds_barrier_keep_loads<0>();
+    };
+    for (int q = 0; q < total; q += 2) {
+        run_stage(std::integral_constant<int, 0>{}, q);
+        if (q + 1 < total) run_stage(std::integral_constant<int, 1>{}, q + 1);
     }
     // one partial per (row, stream): stream = (col * WV + wv) * 2 + half
     const int nsr = hg.gw * C::WV * 2;
@@ -332,7 +342,7 @@ static hipError_t set_lds(const void *fn) {
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
 }
 
-hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int d, int r,
+hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int rows_pad, int d, int r,
                             int slices, int kslice, hipStream_t st)
 {
     using C = CfgSmall;
@@ -340,7 +350,7 @@ hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, i
     hipError_t e = set_lds<C>(reinterpret_cast<const void *>(fn));
     if (e != hipSuccess) return e;
     dim3 grid((r + kNT - 1) / kNT, (rows + C::RT - 1) / C::RT, slices);
-    fn<<<grid, C::THREADS, C::LDS_BYTES, st>>>(h, A, part, rows, d, r, kslice);
+    fn<<<grid, C::THREADS, C::LDS_BYTES, st>>>(h, A, part, rows, rows_pad, d, r, kslice);
     return hipGetLastError();
 }
 
@@ -348,10 +358,9 @@ hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_
                               float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
                               hipStream_t st)
 {
-    int threads = ((r / 8 + 63) / 64) * 64;
-    if (threads > 1024) threads = 1024;
-    down_finish_kernel<<<rows_pad + 1, threads, 0, st>>>(part, slices, rows, rows_pad, r, t32,
-                                                         static_cast<uint4 *>(t16), stat, B, V, brms);
+    dim3 grid(rows_pad / 64 + 1, (r + 31) / 32);
+    down_finish_kernel<<<grid, 256, 0, st>>>(part, slices, rows, rows_pad, r, t32,
+                                             static_cast<uint4 *>(t16), stat, B, V, brms);
     return hipGetLastError();
 }
 

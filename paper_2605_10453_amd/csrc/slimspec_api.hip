@@ -74,7 +74,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             void *t16 = ws + p.off_t16;
             float2 *stat = reinterpret_cast<float2 *>(ws + p.off_stat);
             float *brms = reinterpret_cast<float *>(ws + p.off_brms);
-            e = launch_down_gemm(hrow, static_cast<const uint16_t *>(A), down_part, rows, d, r, p.slices, p.kslice, s);
+            e = launch_down_gemm(hrow, static_cast<const uint16_t *>(A), down_part, rows, p.rows_pad, d, r, p.slices, p.kslice, s);
             if (e != hipSuccess) return fail_hip(e);
             e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, s);
             if (e != hipSuccess) return fail_hip(e);
@@ -82,7 +82,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             e = launch_head_mfma(static_cast<const uint16_t *>(t16), false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, t32, false, r, Mb, r, V, stat, brms, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, t32, false, r, Mb, r, V, stat, (r + 31) / 32, p.rows_pad, brms, k,
                                      out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
@@ -90,7 +90,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             e = launch_head_mfma(hrow, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, hrow, true, d, Mb, d, V, nullptr, nullptr, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
                                      out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         }
