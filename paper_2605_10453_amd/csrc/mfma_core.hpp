@@ -56,7 +56,13 @@ struct TileCfg {
 template <class C>
 struct MRegs { uint4 w[C::M_TASKS][8]; };
 
-// K here is the end of the k range to load (rows k >= K read as zero).
+// Branch-free: addresses past the end of the k range [.., K) or of the columns [.., N) are clamped
+// to the last valid group of 8, so every load is in bounds and returns real (finite) weights.
+// Clamped k rows meet zero activations (the X tile is zero there); clamped columns are ignored
+// by the epilogues.  Straight-line loads let the compiler count outstanding loads exactly, which
+// the two-stage-deep prefetch relies on.
+// Addresses are formed as (uniform row pointer M + i N) + one 32-bit per-lane offset, so that the
+// 8 loads of a task share a single offset register (scalar base + vector offset addressing).
 template <class C>
 __device__ __forceinline__ void load_m_regs(MRegs<C> &r, const uint16_t *__restrict__ M,
                                             int K, int N, int k0, int n0, int tid)
@@ -65,13 +71,14 @@ __device__ __forceinline__ void load_m_regs(MRegs<C> &r, const uint16_t *__restr
     for (int t = 0; t < C::M_TASKS; ++t) {
         const int q = tid + t * C::THREADS;
         const int kg = q >> 5, g = q & 31;
-        const int n = n0 + g * 8;
-        const int k = k0 + kg * 8;
-        const bool ok = (n < N) && (k < K);                 // N and K are multiples of 8
-        const uint16_t *p = M + (size_t)k * N + n;
+        const int n = min(n0 + g * 8, N - 8);
+        const int k = min(k0 + kg * 8, K - 8);
+        const uint32_t off = (uint32_t)k * (uint32_t)N + (uint32_t)n;      // < 2^31 elements (checked on the host)
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            r.w[t][i] = ok ? *reinterpret_cast<const uint4 *>(p + (size_t)i * N) : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < 8; ++i) {
+            const uint16_t *row_i = M + (size_t)i * N;                       // uniform
+            r.w[t][i] = *reinterpret_cast<const uint4 *>(row_i + off);
+        }
     }
 }
 
@@ -138,65 +145,64 @@ __device__ __forceinline__ void store_m_lds(const MRegs<C> &r, uint4 *__restrict
 // X tile.  Two sources: the k-grouped scratch layout [K/8][rows_pad] of 16-byte vectors written
 // by the down-projection (straight copy), or row-major bf16 activations [rows, K] (h itself).
 template <class C>
-struct XRegs { uint4 w[C::X_PIECES]; };
+struct XRegs { u32x4 w[C::X_PIECES]; };      // native vectors: plain register copies, global -> LDS
 
-// K: end of the k range to load; ldx: row stride of row-major X (elements).
+// Branch-free.  Row-major X [rows, ldx] (bf16 activations): rows past the end are clamped (their
+// results are never used), k >= K reads as zero (select after an in-bounds load).  k-grouped X
+// (the f16 scratch [Kpad / 8][rows_pad] written by the down-projection) is zero-padded to a
+// multiple of kKB in k and to rows_pad rows, so it needs no guard at all.
 template <class C, bool ROW_MAJOR>
 __device__ __forceinline__ void load_x_regs(XRegs<C> &r, const uint16_t *__restrict__ X,
                                             int K, int ldx, int rows, int rows_pad, int k0, int row0, int tid)
 {
+    if constexpr (ROW_MAJOR) {
 #pragma unroll
-    for (int i = 0; i < C::X_PIECES; ++i) {
-        const int p = tid + i * C::THREADS;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (p < kKG * C::RT) {
-            if constexpr (ROW_MAJOR) {
-                const int row = row0 + (p >> 3), k = k0 + (p & 7) * 8;
-                if (row < rows && k < K) v = *reinterpret_cast<const uint4 *>(X + (size_t)row * ldx + k);
-            } else {
-                const int kg = p / C::RT, row = row0 + p % C::RT, k = k0 + kg * 8;
-                if (k < K) v = *reinterpret_cast<const uint4 *>(X + ((size_t)(k >> 3) * rows_pad + row) * 8);
-            }
+        for (int i = 0; i < C::X_PIECES; ++i) {
+            const int p = min(tid + i * C::THREADS, kKG * C::RT - 1);
+            const int row = min(row0 + (p >> 3), rows - 1), k = k0 + (p & 7) * 8;
+            const uint32_t off = (uint32_t)row * (uint32_t)ldx + (uint32_t)min(k, K - 8);
+            u32x4 v = *reinterpret_cast<const u32x4 *>(X + off);
+            if (k >= K) v = u32x4{0u, 0u, 0u, 0u};
+            r.w[i] = v;
         }
-        r.w[i] = v;
+    } else {
+        // piece p = tid + i THREADS -> (k-group p / RT, row p % RT); THREADS is a multiple or a divisor of RT,
+        // so consecutive pieces of a thread differ by a uniform stride: one per-lane offset register
+        static_assert(C::THREADS % C::RT == 0 || C::RT % C::THREADS == 0, "piece stride must be uniform");
+        const int p0 = min(tid, kKG * C::RT - 1);
+        const uint32_t off = ((uint32_t)((k0 >> 3) + p0 / C::RT) * (uint32_t)rows_pad + (uint32_t)(row0 + p0 % C::RT)) * 8u;
+#pragma unroll
+        for (int i = 0; i < C::X_PIECES; ++i) {
+            const size_t step = (C::THREADS >= C::RT)
+                ? (size_t)i * (C::THREADS / C::RT) * rows_pad * 8                  // whole k-groups further
+                : (size_t)((i * C::THREADS) / C::RT) * rows_pad * 8 + (size_t)((i * C::THREADS) % C::RT) * 8;
+            r.w[i] = *reinterpret_cast<const u32x4 *>(X + step + off);
+        }
+    }
+}
+
+// piece I of the X tile into LDS
+template <class C, bool ROW_MAJOR, int I>
+__device__ __forceinline__ void store_x_piece(const XRegs<C> &r, uint4 *__restrict__ x_tile, int tid)
+{
+    if constexpr (I < C::X_PIECES) {
+        const int p = tid + I * C::THREADS;
+        if (C::X_PIECES * C::THREADS == kKG * C::RT || p < kKG * C::RT) {
+            u32x4 *xt = reinterpret_cast<u32x4 *>(x_tile);
+            if constexpr (ROW_MAJOR) xt[(p & 7) * C::XS + (p >> 3)] = r.w[I];
+            else xt[(p / C::RT) * C::XS + p % C::RT] = r.w[I];
+        }
     }
 }
 
 template <class C, bool ROW_MAJOR>
 __device__ __forceinline__ void store_x_lds(const XRegs<C> &r, uint4 *__restrict__ x_tile, int tid)
 {
-#pragma unroll
-    for (int i = 0; i < C::X_PIECES; ++i) {
-        const int p = tid + i * C::THREADS;
-        if (p < kKG * C::RT) {
-            if constexpr (ROW_MAJOR) x_tile[(p & 7) * C::XS + (p >> 3)] = r.w[i];
-            else x_tile[(p / C::RT) * C::XS + p % C::RT] = r.w[i];
-        }
-    }
-}
-
-// k-grouped X straight from global memory into an LDS tile (global_load_lds_dwordx4: no data
-// registers; the wavefront's 64 lanes land in 64 consecutive vectors).  The writes are
-// asynchronous: they are complete after the next s_waitcnt vmcnt(0) / __syncthreads().
-template <class C>
-__device__ __forceinline__ void load_x_direct(const uint16_t *__restrict__ X, uint4 *__restrict__ x_tile,
-                                              int K, int rows_pad, int k0, int row0, int wave, int lane)
-{
-    static_assert(C::RT % 64 == 0, "a wavefront must stay inside one k-group");
-#pragma unroll
-    for (int i = 0; i < C::X_PIECES; ++i) {
-        const int p0 = wave * 64 + i * C::THREADS;           // first piece of this wavefront
-        if (p0 >= kKG * C::RT) continue;
-        const int kg = p0 / C::RT, rbase = p0 % C::RT;
-        const int k = k0 + kg * 8;
-        uint4 *dst = x_tile + kg * C::XS + rbase;            // wavefront-uniform
-        if (k < K) {
-            const uint16_t *src = X + ((size_t)(k >> 3) * rows_pad + row0 + rbase + lane) * 8;
-            __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-        } else {
-            dst[lane] = make_uint4(0, 0, 0, 0);
-        }
-    }
+    static_assert(C::X_PIECES <= 8, "piece count");
+    store_x_piece<C, ROW_MAJOR, 0>(r, x_tile, tid); store_x_piece<C, ROW_MAJOR, 1>(r, x_tile, tid);
+    store_x_piece<C, ROW_MAJOR, 2>(r, x_tile, tid); store_x_piece<C, ROW_MAJOR, 3>(r, x_tile, tid);
+    store_x_piece<C, ROW_MAJOR, 4>(r, x_tile, tid); store_x_piece<C, ROW_MAJOR, 5>(r, x_tile, tid);
+    store_x_piece<C, ROW_MAJOR, 6>(r, x_tile, tid); store_x_piece<C, ROW_MAJOR, 7>(r, x_tile, tid);
 }
 
 // ---------------------------------------------------------------------------
@@ -264,13 +270,14 @@ __device__ __forceinline__ void mma_stage(f32x16 (&acc)[C::TR][C::TV], const uin
     }
 }
 
-// The same stage, with the regroup-and-store of the NEXT stage's M tile (already in registers)
-// spread over its four k-steps: the matrix cores work through the 8 MFMAs of a k-step while the
-// wavefront issues one quarter of the conversion and its LDS writes.
-template <class C, bool F16>
+// The same stage, with the regroup-and-store of the NEXT stage's tiles (already in registers)
+// spread over its four k-steps: the matrix cores work through the MFMAs of a k-step while the
+// wavefront issues one quarter of the M conversion, its LDS writes and a share of the X writes.
+template <class C, bool F16, bool XROW>
 __device__ __forceinline__ void mma_stage_and_store(f32x16 (&acc)[C::TR][C::TV], const uint4 *__restrict__ m_tile,
                                                     const uint4 *__restrict__ x_tile, int wr, int wv, int lane, bool fresh,
-                                                    const MRegs<C> &next_regs, uint4 *__restrict__ next_m_tile, bool do_store, int tid)
+                                                    const MRegs<C> &next_m, const XRegs<C> &next_x,
+                                                    uint4 *__restrict__ next_m_tile, uint4 *__restrict__ next_x_tile, int tid)
 {
     static_assert(kKB / 16 == 4, "four k-steps, four quarters");
     Frags<C> f[2];
@@ -288,14 +295,18 @@ __device__ __forceinline__ void mma_stage_and_store(f32x16 (&acc)[C::TR][C::TV],
 #pragma unroll
             for (int j = 0; j < C::TV; ++j) mfma_32x32x16<F16>(f[0].m[j], f[0].x[rt], acc[rt][j]);
     }
-    if (do_store) store_m_quarter<C, F16, 0>(next_regs, next_m_tile, tid);
+    store_m_quarter<C, F16, 0>(next_m, next_m_tile, tid);
+    store_x_piece<C, XROW, 0>(next_x, next_x_tile, tid);
+    store_x_piece<C, XROW, 4>(next_x, next_x_tile, tid);
     __builtin_amdgcn_sched_barrier(0);
 #define SLIMSPEC_KSTEP(S)                                                                               \
     if (S + 1 < 4) load_frags<C>(f[(S + 1) & 1], m_tile, x_tile, S + 1, wr, wv, lane);                  \
     _Pragma("unroll") for (int rt = 0; rt < C::TR; ++rt)                                                \
         _Pragma("unroll") for (int j = 0; j < C::TV; ++j)                                               \
             mfma_32x32x16<F16>(f[S & 1].m[j], f[S & 1].x[rt], acc[rt][j]);                              \
-    if (do_store) store_m_quarter<C, F16, S>(next_regs, next_m_tile, tid);                              \
+    store_m_quarter<C, F16, S>(next_m, next_m_tile, tid);                                               \
+    store_x_piece<C, XROW, S>(next_x, next_x_tile, tid);                                                \
+    store_x_piece<C, XROW, S + 4>(next_x, next_x_tile, tid);                                            \
     __builtin_amdgcn_sched_barrier(0);
     SLIMSPEC_KSTEP(1) SLIMSPEC_KSTEP(2) SLIMSPEC_KSTEP(3)
 #undef SLIMSPEC_KSTEP
@@ -308,14 +319,9 @@ __device__ __forceinline__ float read_acc(const float &a) {
     return v;
 }
 
-// Block-wide barrier that orders LDS traffic only.  PENDING = number of the youngest global loads
-// each thread may leave in flight (the register prefetch of the stage after next); everything
-// older (the direct-to-LDS loads of the next stage) completes first because vector memory returns
-// in issue order.
-template <int PENDING>
-__device__ __forceinline__ void lds_barrier_keep_loads() {
-    static_assert(PENDING >= 0 && PENDING < 64, "vmcnt field");
-    __builtin_amdgcn_s_waitcnt(0x0070 | (PENDING & 15) | ((PENDING >> 4) << 14));   // vmcnt(PENDING) expcnt(7) lgkmcnt(0)
+// Block-wide barrier that orders LDS traffic only: global loads in flight (the register prefetch
+// of later stages) are not waited for.
+__device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");

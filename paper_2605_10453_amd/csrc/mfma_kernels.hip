@@ -81,13 +81,13 @@ __global__ __launch_bounds__(C::THREADS) void down_gemm_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Fixed-order sum of the slices.  grid = (rows_pad / 64 + 1, ceil(r / 32)); block (bx, by) of 256
+// Fixed-order sum of the slices.  grid = (rows_pad / 64 + 1, 2 ceil(r / 64)); block (bx, by) of 256
 // threads owns rows [64 bx, 64 bx + 64) and the four 8-wide k-groups 4 by .. 4 by + 3 (thread =
 // (row, k-group)); the extra block row bx = rows_pad / 64 estimates rms(B) (by = 0 only).
 //   part  [slices, r, ld]     fp32 partial sums, ld = rows_pad
 //   t32   [rows_pad, r]       fp32 t (zero for padding rows)
-//   t16   [r / 8, rows_pad]   16-byte vectors of 8 f16 (round to nearest even)
-//   stat  [ceil(r / 32), rows_pad]   per block column: (sum of (t - f16(t))^2, sum of t^2) of its 32 entries
+//   t16   [8 ceil(r / 64), rows_pad]   16-byte vectors of 8 f16 (round to nearest even), zero for k >= r
+//   stat  [2 ceil(r / 64), rows_pad]   per block column: (sum of (t - f16(t))^2, sum of t^2) of its 32 entries
 //   brms  [1]                 sqrt(mean of B^2 over a fixed sample of entries)
 constexpr int kBrmsPositions = 4;
 
@@ -144,6 +144,8 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
             b += v[e] * v[e];
         }
         t16[(size_t)kg * rows_pad + row] = __builtin_bit_cast(uint4, hv);
+    } else {
+        t16[(size_t)kg * rows_pad + row] = make_uint4(0, 0, 0, 0);     // zero padding of k up to a multiple of 64
     }
     red_a[kgl][lane] = a;
     red_b[kgl][lane] = b;
@@ -241,47 +243,40 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
     for (int rt = 0; rt < C::TR; ++rt) stream_init(st[rt]);
     f32x16 acc[C::TR][C::TV];
     // Software pipeline over the flattened (tile, k-block) stages q = 0 .. total - 1:
-    //   stage q + 2: M rows -> registers (global loads issued at the start of stage q)
-    //   stage q + 1: registers -> f16/bf16 k-contiguous vectors -> LDS, interleaved with the MFMAs of
-    //                stage q; X (k-grouped) goes from global memory straight to LDS
+    //   stage q + 2: rows of M and the X tile -> registers (global loads issued at the start of stage q)
+    //   stage q + 1: registers -> k-contiguous f16/bf16 vectors -> LDS, interleaved with the MFMAs of stage q
     //   stage q    : MFMAs from LDS
+    // The steady state has no branch around a load, so that the compiler's count of loads in flight
+    // stays exact and a stage never waits for the loads it has just issued.
+    struct Pos { int vt, kb; };
+    const auto advance = [&](Pos p) { Pos o = p; if (++o.kb == nkb) { o.kb = 0; o.vt += hg.gw; } return o; };
     MRegs<C> mreg[2];
-    XRegs<C> xr;        // used only for row-major X
-    const auto stage_pos = [&](int sq, int &vt_o, int &kb_o) { vt_o = col + (sq / nkb) * hg.gw; kb_o = sq % nkb; };
+    XRegs<C> xreg[2];
+    const auto load_stage = [&](MRegs<C> &m, XRegs<C> &x, Pos p) {
+        load_x_regs<C, XROW>(x, X, K, K, rows, rows_pad, p.kb * kKB, row0, tid);
+        load_m_regs<C>(m, M, K, V, p.kb * kKB, p.vt * kNT, tid);
+    };
+    Pos cur{col, 0}, loaded{col, 0};
     if (total > 0) {
-        if constexpr (XROW) load_x_regs<C, true>(xr, X, K, K, rows, rows_pad, 0, row0, tid);
-        else load_x_direct<C>(X, lds + C::M_VECS, K, rows_pad, 0, row0, wave, lane);
-        load_m_regs<C>(mreg[0], M, K, V, 0, col * kNT, tid);
+        load_stage(mreg[0], xreg[0], cur);
         store_m_lds<C, F16>(mreg[0], lds, tid);
-        if constexpr (XROW) store_x_lds<C, true>(xr, lds + C::M_VECS, tid);
-        if (total > 1) {
-            int vt1, kb1;
-            stage_pos(1, vt1, kb1);
-            load_m_regs<C>(mreg[1], M, K, V, kb1 * kKB, vt1 * kNT, tid);
-        }
+        store_x_lds<C, XROW>(xreg[0], lds + C::M_VECS, tid);
+        if (total > 1) loaded = advance(cur);
+        load_stage(mreg[1], xreg[1], loaded);             // stage 1 (a harmless reload of stage 0 if there is none)
     }
-    __builtin_amdgcn_s_waitcnt(0x0070);     // every load so far, including the direct-to-LDS ones
     __syncthreads();
 
-    // one stage; PAR = q & 1 selects the LDS stage and the register set at compile time
+    // one stage; PAR = q & 1 selects the LDS stage and the register sets at compile time
     auto run_stage = [&](auto par_tag, int q) {
         constexpr int PAR = decltype(par_tag)::value;
-        uint4 *cur = lds + PAR * C::STAGE_VECS, *nxt = lds + (PAR ^ 1) * C::STAGE_VECS;
-        const bool more = q + 1 < total, more2 = q + 2 < total;
-        int vt, kb, vt1, kb1, vt2, kb2;
-        stage_pos(q, vt, kb);
-        stage_pos(q + 1, vt1, kb1);
-        stage_pos(q + 2, vt2, kb2);
-        if (more) {
-            if constexpr (XROW) load_x_regs<C, true>(xr, X, K, K, rows, rows_pad, kb1 * kKB, row0, tid);
-            else load_x_direct<C>(X, nxt + C::M_VECS, K, rows_pad, kb1 * kKB, row0, wave, lane);
-        }
+        uint4 *st_cur = lds + PAR * C::STAGE_VECS, *st_nxt = lds + (PAR ^ 1) * C::STAGE_VECS;
+        const Pos ahead = (q + 2 < total) ? advance(loaded) : loaded;      // past the end: reload the last stage
+        load_stage(mreg[PAR], xreg[PAR], ahead);
         __builtin_amdgcn_sched_barrier(0);
-        if (more2) load_m_regs<C>(mreg[PAR], M, K, V, kb2 * kKB, vt2 * kNT, tid);      // youngest loads of the stage
-        __builtin_amdgcn_sched_barrier(0);
-        mma_stage_and_store<C, F16>(acc, cur, cur + C::M_VECS, wr, wv, lane, kb == 0, mreg[PAR ^ 1], nxt, more, tid);
-        if (kb == nkb - 1) {
-            const int n0 = vt * kNT;
+        mma_stage_and_store<C, F16, XROW>(acc, st_cur, st_cur + C::M_VECS, wr, wv, lane, cur.kb == 0,
+                                          mreg[PAR ^ 1], xreg[PAR ^ 1], st_nxt, st_nxt + C::M_VECS, tid);
+        if (cur.kb == nkb - 1) {
+            const int n0 = cur.vt * kNT;
             const bool tail = n0 + kNT > V;
             const int mlim = (V - n0) >> 3;               // groups of 8 columns that exist in this tile
 #pragma unroll
@@ -296,13 +291,13 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
                         for (int i = 0; i < 16; ++i)
                             if (8 * (i >> 2) + 4 * half + (i & 3) >= mlim) v[i] = kNegBig;
                     }
-                    stream_group<L>(st[rt], v, vt * 8 + wv * C::TV + j);
+                    stream_group<L>(st[rt], v, cur.vt * 8 + wv * C::TV + j);
                     __builtin_amdgcn_sched_barrier(0);      // one group at a time: keeps register pressure flat
                 }
         }
-        if constexpr (XROW) { if (more) store_x_lds<C, true>(xr, nxt + C::M_VECS, tid); }
-        if (more2) lds_barrier_keep_loads<8 * C::M_TASKS>();
-        else lds_barrier_keep_loads<0>();
+        lds_barrier();
+        loaded = ahead;
+        if (q + 1 < total) cur = advance(cur);
     };
     for (int q = 0; q < total; q += 2) {
         run_stage(std::integral_constant<int, 0>{}, q);
@@ -358,7 +353,7 @@ hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_
                               float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
                               hipStream_t st)
 {
-    dim3 grid(rows_pad / 64 + 1, (r + 31) / 32);
+    dim3 grid(rows_pad / 64 + 1, 2 * ((r + 63) / 64));
     down_finish_kernel<<<grid, 256, 0, st>>>(part, slices, rows, rows_pad, r, t32,
                                              static_cast<uint4 *>(t16), stat, B, V, brms);
     return hipGetLastError();

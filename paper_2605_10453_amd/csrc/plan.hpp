@@ -65,8 +65,8 @@ struct MfmaPlan {
     int slices = 0, kslice = 0;          // down-projection split of d
     size_t off_down_part = 0;            // fp32 [slices, r, rows_pad]
     size_t off_t32 = 0;                  // fp32 [rows_pad, r]
-    size_t off_t16 = 0;                  // 16-byte vectors [r / 8, rows_pad]
-    size_t off_stat = 0;                 // float2 [ceil(r / 32), rows_pad]
+    size_t off_t16 = 0;                  // 16-byte vectors [8 ceil(r / 64), rows_pad]
+    size_t off_stat = 0;                 // float2 [2 ceil(r / 64), rows_pad]
     size_t off_brms = 0;                 // float
     size_t off_streams = 0;              // fp32 [rows, nsr, kStreamRec]
     size_t bytes = 0;
@@ -96,8 +96,8 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
         p.slices = (d + p.kslice - 1) / p.kslice;
         p.off_down_part = off; off = align_up(off + sizeof(float) * (size_t)p.slices * p.rows_pad * r);
         p.off_t32 = off;       off = align_up(off + sizeof(float) * (size_t)p.rows_pad * r);
-        p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * r);
-        p.off_stat = off;      off = align_up(off + 2 * sizeof(float) * (size_t)p.rows_pad * ((r + 31) / 32));
+        p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((r + 63) / 64 * 64));
+        p.off_stat = off;      off = align_up(off + 2 * sizeof(float) * (size_t)p.rows_pad * 2 * ((r + 63) / 64));
         p.off_brms = off;      off = align_up(off + sizeof(float));
     }
     p.off_streams = off;       off = align_up(off + sizeof(float) * (size_t)rows * p.nsr * kStreamRecPlan);

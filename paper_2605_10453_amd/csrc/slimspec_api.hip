@@ -82,7 +82,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             e = launch_head_mfma(static_cast<const uint16_t *>(t16), false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, t32, false, r, Mb, r, V, stat, (r + 31) / 32, p.rows_pad, brms, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
                                      out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
