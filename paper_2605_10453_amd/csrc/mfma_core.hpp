@@ -270,35 +270,32 @@ __device__ __forceinline__ void mma_stage(f32x16 (&acc)[C::TR][C::TV], const uin
     }
 }
 
+// Scheduling request for one k-step: after every MFMA, one LDS read (operands of the next k-step)
+// and a few VALU instructions (the conversion), then the LDS writes.  A wavefront issues in order,
+// so the conversion only overlaps the matrix cores if it sits between the MFMAs in program order.
+template <int NMFMA>
+__device__ __forceinline__ void interleave_hint() {
+#pragma unroll
+    for (int i = 0; i < NMFMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // DS read
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);      // VALU
+    }
+    __builtin_amdgcn_sched_group_barrier(0x200, 8, 0);          // DS write
+}
+
 // The same stage, with the regroup-and-store of the NEXT stage's tiles (already in registers)
 // spread over its four k-steps: the matrix cores work through the MFMAs of a k-step while the
 // wavefront issues one quarter of the M conversion, its LDS writes and a share of the X writes.
 template <class C, bool F16, bool XROW>
 __device__ __forceinline__ void mma_stage_and_store(f32x16 (&acc)[C::TR][C::TV], const uint4 *__restrict__ m_tile,
-                                                    const uint4 *__restrict__ x_tile, int wr, int wv, int lane, bool fresh,
+                                                    const uint4 *__restrict__ x_tile, int wr, int wv, int lane,
                                                     const MRegs<C> &next_m, const XRegs<C> &next_x,
                                                     uint4 *__restrict__ next_m_tile, uint4 *__restrict__ next_x_tile, int tid)
 {
     static_assert(kKB / 16 == 4, "four k-steps, four quarters");
     Frags<C> f[2];
     load_frags<C>(f[0], m_tile, x_tile, 0, wr, wv, lane);
-    load_frags<C>(f[1], m_tile, x_tile, 1, wr, wv, lane);
-    if (fresh) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int rt = 0; rt < C::TR; ++rt)
-#pragma unroll
-            for (int j = 0; j < C::TV; ++j) { acc[rt][j] = zero; mfma_32x32x16<F16>(f[0].m[j], f[0].x[rt], acc[rt][j]); }
-    } else {
-#pragma unroll
-        for (int rt = 0; rt < C::TR; ++rt)
-#pragma unroll
-            for (int j = 0; j < C::TV; ++j) mfma_32x32x16<F16>(f[0].m[j], f[0].x[rt], acc[rt][j]);
-    }
-    store_m_quarter<C, F16, 0>(next_m, next_m_tile, tid);
-    store_x_piece<C, XROW, 0>(next_x, next_x_tile, tid);
-    store_x_piece<C, XROW, 4>(next_x, next_x_tile, tid);
-    __builtin_amdgcn_sched_barrier(0);
 #define SLIMSPEC_KSTEP(S)                                                                               \
     if (S + 1 < 4) load_frags<C>(f[(S + 1) & 1], m_tile, x_tile, S + 1, wr, wv, lane);                  \
     _Pragma("unroll") for (int rt = 0; rt < C::TR; ++rt)                                                \
@@ -307,9 +304,22 @@ __device__ __forceinline__ void mma_stage_and_store(f32x16 (&acc)[C::TR][C::TV],
     store_m_quarter<C, F16, S>(next_m, next_m_tile, tid);                                               \
     store_x_piece<C, XROW, S>(next_x, next_x_tile, tid);                                                \
     store_x_piece<C, XROW, S + 4>(next_x, next_x_tile, tid);                                            \
+    interleave_hint<C::TR * C::TV>();                                                                   \
     __builtin_amdgcn_sched_barrier(0);
-    SLIMSPEC_KSTEP(1) SLIMSPEC_KSTEP(2) SLIMSPEC_KSTEP(3)
+    SLIMSPEC_KSTEP(0) SLIMSPEC_KSTEP(1) SLIMSPEC_KSTEP(2) SLIMSPEC_KSTEP(3)
 #undef SLIMSPEC_KSTEP
+}
+
+// Accumulators are zeroed in place in their AGPRs (an inline-asm write keeps them in the AGPR class,
+// like read_acc below).
+template <int TR, int TV>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[TR][TV]) {
+#pragma unroll
+    for (int rt = 0; rt < TR; ++rt)
+#pragma unroll
+        for (int j = 0; j < TV; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(acc[rt][j][i]));
 }
 
 // one accumulator element, read straight from its AGPR

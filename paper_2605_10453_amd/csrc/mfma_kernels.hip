@@ -257,6 +257,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
         load_m_regs<C>(m, M, K, V, p.kb * kKB, p.vt * kNT, tid);
     };
     Pos cur{col, 0}, loaded{col, 0};
+    zero_acc(acc);
     if (total > 0) {
         load_stage(mreg[0], xreg[0], cur);
         store_m_lds<C, F16>(mreg[0], lds, tid);
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
         const Pos ahead = (q + 2 < total) ? advance(loaded) : loaded;      // past the end: reload the last stage
         load_stage(mreg[PAR], xreg[PAR], ahead);
         __builtin_amdgcn_sched_barrier(0);
-        mma_stage_and_store<C, F16, XROW>(acc, st_cur, st_cur + C::M_VECS, wr, wv, lane, cur.kb == 0,
+        mma_stage_and_store<C, F16, XROW>(acc, st_cur, st_cur + C::M_VECS, wr, wv, lane,
                                           mreg[PAR ^ 1], xreg[PAR ^ 1], st_nxt, st_nxt + C::M_VECS, tid);
         if (cur.kb == nkb - 1) {
             const int n0 = cur.vt * kNT;
@@ -294,6 +295,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
                     stream_group<L>(st[rt], v, cur.vt * 8 + wv * C::TV + j);
                     __builtin_amdgcn_sched_barrier(0);      // one group at a time: keeps register pressure flat
                 }
+            zero_acc(acc);
         }
         lds_barrier();
         loaded = ahead;
