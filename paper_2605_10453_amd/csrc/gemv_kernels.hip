@@ -7,7 +7,7 @@
 //   stream_topk_kernel    z[:, chunk] = x M[:, chunk] for a 512-column chunk, then the
 //                         chunk's running max, sum of exp and top-k, one partial per
 //                         (row, chunk); no logit is written to memory
-#include "device_utils.hpp"
+#include "gemv_parts.hpp"
 #include "launch.hpp"
 
 namespace slimspec {
@@ -87,46 +87,18 @@ __global__ __launch_bounds__(256) void widen_rows_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// 8 adjacent columns of one matrix row: kept as loaded (raw) while in flight, widened
-// to fp32 only when consumed, so that many loads can be outstanding per lane.
-struct Raw8Bf16 { uint4 w; };
-struct Raw8F32 { float4 a, b; };
-__device__ __forceinline__ Raw8Bf16 load_raw8(const uint16_t *p) { return {*reinterpret_cast<const uint4 *>(p)}; }
-__device__ __forceinline__ Raw8F32 load_raw8(const float *p) {
-    return {*reinterpret_cast<const float4 *>(p), *reinterpret_cast<const float4 *>(p + 4)};
-}
-__device__ __forceinline__ void widen8(const Raw8Bf16 &q, float (&f)[8]) {
-    f[0] = bf16_lo(q.w.x); f[1] = bf16_hi(q.w.x); f[2] = bf16_lo(q.w.y); f[3] = bf16_hi(q.w.y);
-    f[4] = bf16_lo(q.w.z); f[5] = bf16_hi(q.w.z); f[6] = bf16_lo(q.w.w); f[7] = bf16_hi(q.w.w);
-}
-__device__ __forceinline__ void widen8(const Raw8F32 &q, float (&f)[8]) {
-    f[0] = q.a.x; f[1] = q.a.y; f[2] = q.a.z; f[3] = q.a.w; f[4] = q.b.x; f[5] = q.b.y; f[6] = q.b.z; f[7] = q.b.w;
-}
-
 // One block per 512-column chunk of the vocabulary.  x is the fp32 contraction
 // input [R, K] (t or h), M the [K, V] weight matrix (bf16 or fp32).  The NW
 // wavefronts split K; every lane owns 8 adjacent columns and keeps R x 8 fp32
 // accumulators.  After a fixed-order sum over the wavefronts, wavefront i % NW
 // reduces row i of the chunk to (max, sum of exp, top-k) and writes the partial.
-//
-// Top-k of a chunk in three steps whose cost does not grow with k: the k-th largest
-// of the 64 lane maxima (by all-pairs counting) bounds the answer from below; the
-// few elements that reach the bound are gathered in shared memory; they are ranked
-// among themselves by (logit desc, id asc), again by counting.  Lanes own increasing
-// columns, so ordering lane maxima by (value, lane) is consistent with ordering
-// elements by (value, id): an element below the bound is preceded by k lane maxima.
 template <int R, int NW, typename WT>
 __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     const float *__restrict__ x, const WT *__restrict__ M,
     float2 *__restrict__ part_ms, float *__restrict__ part_val, int *__restrict__ part_id,
     int rows_here, int row0, int K, int V, int chunks, int k)
 {
-    __shared__ float red[NW][R][kChunkCols];
-    constexpr int EW = (R < NW) ? R : NW;           // wavefronts that run the per-row epilogue
-    __shared__ uint64_t sel_keys[EW][64];
-    __shared__ uint64_t sel_cand[EW][kChunkCols];
-    __shared__ uint64_t sel_bound[EW];
-    __shared__ uint32_t sel_cnt[EW];
+    __shared__ ChunkLds<R, NW> L;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int chunk = blockIdx.x;
@@ -175,79 +147,14 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     }
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-        float4 *dst = reinterpret_cast<float4 *>(&red[wave][i][lane * 8]);
+        float4 *dst = reinterpret_cast<float4 *>(&L.red[wave][i][lane * 8]);
         dst[0] = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
         dst[1] = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
     }
     __syncthreads();
-
-    for (int i = wave; i < rows_here; i += NW) {
-        float z[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) z[e] = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {          // fixed order: wavefront 0 first
-            const float4 *src = reinterpret_cast<const float4 *>(&red[w][i][lane * 8]);
-            float4 a = src[0], b = src[1];
-            z[0] += a.x; z[1] += a.y; z[2] += a.z; z[3] += a.w;
-            z[4] += b.x; z[5] += b.y; z[6] += b.z; z[7] += b.w;
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) z[e] = active ? z[e] : kNegInf;
-
-        // running max and sum of exp of the chunk
-        float lm = z[0];
-#pragma unroll
-        for (int e = 1; e < 8; ++e) lm = fmaxf(lm, z[e]);
-        const float m = wave_max(lm);
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s += fast_exp(z[e] - m);     // exp(-inf) = 0 for padding lanes
-        s = wave_sum(s);
-
-        // top-k of the chunk, without k serial rounds
-        // (1) bound: the k-th largest of the 64 lane maxima, as keys (value, lane)
-        uint64_t *lane_keys = sel_keys[wave];
-        uint64_t *cand = sel_cand[wave];
-        const uint64_t my_lane_key = active ? make_key(lm, (uint32_t)lane) : kNoKey;
-        lane_keys[lane] = my_lane_key;
-        if (lane == 0) { sel_cnt[wave] = 0u; sel_bound[wave] = kNoKey; }
-        lds_wave_sync();
-        int rank = 0;
-#pragma unroll 8
-        for (int q = 0; q < 64; ++q) rank += (lane_keys[q] > my_lane_key) ? 1 : 0;
-        if (rank == k - 1 && my_lane_key != kNoKey) sel_bound[wave] = my_lane_key;   // keys are unique: one lane at most
-        lds_wave_sync();
-        const uint64_t bound = sel_bound[wave];          // kNoKey when fewer than k lanes hold columns: keep everything
-        // (2) every element whose (value, lane) key reaches the bound is a candidate
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (active && make_key(z[e], (uint32_t)lane) >= bound) {
-                uint32_t pos = atomicAdd(&sel_cnt[wave], 1u);
-                cand[pos] = make_key(z[e], (uint32_t)(col + e));
-            }
-        }
-        lds_wave_sync();
-        const int n_cand = (int)sel_cnt[wave];
-        // (3) rank the candidates among themselves by (value desc, id asc); ranks below k are the answer
-        const size_t slot = (size_t)(row0 + i) * chunks + chunk;
-        for (int c0 = 0; c0 < n_cand; c0 += 64) {
-            const int c = c0 + lane;
-            const uint64_t mine = (c < n_cand) ? cand[c] : kNoKey;
-            int rk = 0;
-            for (int q = 0; q < n_cand; ++q) rk += (cand[q] > mine) ? 1 : 0;
-            if (c < n_cand && rk < k) {
-                part_val[slot * k + rk] = key_value(mine);
-                part_id[slot * k + rk] = (int)key_tiebreak(mine);
-            }
-        }
-        if (lane >= n_cand && lane < k) {                  // fewer than k columns in this chunk
-            part_val[slot * k + lane] = kNegInf;
-            part_id[slot * k + lane] = kNoId;
-        }
-        if (lane == 0) part_ms[slot] = make_float2(m, s);
-        lds_wave_sync();                                   // the buffers are reused by this wavefront's next row
-    }
+    for (int i = wave; i < rows_here; i += NW)
+        chunk_row_epilogue<R, NW>(L, i, wave, lane, active, col, k, (size_t)(row0 + i) * chunks + chunk,
+                                  part_ms, part_val, part_id);
 }
 
 // ---------------------------------------------------------------------------

@@ -1,0 +1,215 @@
+// Device-side pieces shared by the streaming ("lane owns columns") kernels: raw weight loads,
+// the per-chunk epilogue (running max, sum of exp, top-k of one 512-column chunk) and the
+// per-row merge of the chunk partials.
+#pragma once
+#include "device_utils.hpp"
+#include "plan.hpp"
+
+namespace slimspec {
+
+// 8 adjacent columns of one matrix row: kept as loaded (raw) while in flight, widened
+// to fp32 only when consumed, so that many loads can be outstanding per lane.
+struct Raw8Bf16 { uint4 w; };
+struct Raw8F32 { float4 a, b; };
+__device__ __forceinline__ Raw8Bf16 load_raw8(const uint16_t *p) { return {*reinterpret_cast<const uint4 *>(p)}; }
+__device__ __forceinline__ Raw8F32 load_raw8(const float *p) {
+    return {*reinterpret_cast<const float4 *>(p), *reinterpret_cast<const float4 *>(p + 4)};
+}
+__device__ __forceinline__ void widen8(const Raw8Bf16 &q, float (&f)[8]) {
+    f[0] = bf16_lo(q.w.x); f[1] = bf16_hi(q.w.x); f[2] = bf16_lo(q.w.y); f[3] = bf16_hi(q.w.y);
+    f[4] = bf16_lo(q.w.z); f[5] = bf16_hi(q.w.z); f[6] = bf16_lo(q.w.w); f[7] = bf16_hi(q.w.w);
+}
+__device__ __forceinline__ void widen8(const Raw8F32 &q, float (&f)[8]) {
+    f[0] = q.a.x; f[1] = q.a.y; f[2] = q.a.z; f[3] = q.a.w; f[4] = q.b.x; f[5] = q.b.y; f[6] = q.b.z; f[7] = q.b.w;
+}
+
+// ---------------------------------------------------------------------------
+// Shared memory of the chunk epilogue: the partial sums of the NW wavefronts that split the
+// contraction, and the selection scratch of the wavefronts that reduce a row each.
+template <int R, int NW>
+struct ChunkLds {
+    static constexpr int EW = (R < NW) ? R : NW;
+    float red[NW][R][kChunkCols];
+    uint64_t sel_keys[EW][64];
+    uint64_t sel_cand[EW][kChunkCols];
+    uint64_t sel_bound[EW];
+    uint32_t sel_cnt[EW];
+};
+
+// Row i of the chunk: fixed-order sum of the NW partial sums, then (max, sum of exp, top-k) of its
+// 512 logits, written as the partial of (row, chunk).  One wavefront; all 64 lanes must call.
+//
+// Top-k in three steps whose cost does not grow with k: the k-th largest of the 64 lane maxima
+// (by all-pairs counting) bounds the answer from below; the few elements that reach the bound
+// are gathered in shared memory; they are ranked among themselves by (logit desc, id asc),
+// again by counting.  Lanes own increasing columns, so ordering lane maxima by (value, lane) is
+// consistent with ordering elements by (value, id): an element below the bound is preceded by
+// k lane maxima.
+template <int R, int NW>
+__device__ __forceinline__ void chunk_row_epilogue(ChunkLds<R, NW> &L, int i, int wave, int lane, bool active,
+                                                   int col, int k, size_t slot,
+                                                   float2 *__restrict__ part_ms, float *__restrict__ part_val,
+                                                   int *__restrict__ part_id)
+{
+    float z[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {          // fixed order: wavefront 0 first
+        const float4 *src = reinterpret_cast<const float4 *>(&L.red[w][i][lane * 8]);
+        float4 a = src[0], b = src[1];
+        z[0] += a.x; z[1] += a.y; z[2] += a.z; z[3] += a.w;
+        z[4] += b.x; z[5] += b.y; z[6] += b.z; z[7] += b.w;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = active ? z[e] : kNegInf;
+
+    float lm = z[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) lm = fmaxf(lm, z[e]);
+    const float m = wave_max(lm);
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += fast_exp(z[e] - m);     // exp(-inf) = 0 for padding lanes
+    s = wave_sum(s);
+
+    // (1) bound: the k-th largest of the 64 lane maxima, as keys (value, lane)
+    uint64_t *lane_keys = L.sel_keys[wave];
+    uint64_t *cand = L.sel_cand[wave];
+    const uint64_t my_lane_key = active ? make_key(lm, (uint32_t)lane) : kNoKey;
+    lane_keys[lane] = my_lane_key;
+    if (lane == 0) { L.sel_cnt[wave] = 0u; L.sel_bound[wave] = kNoKey; }
+    lds_wave_sync();
+    int rank = 0;
+#pragma unroll 8
+    for (int q = 0; q < 64; ++q) rank += (lane_keys[q] > my_lane_key) ? 1 : 0;
+    if (rank == k - 1 && my_lane_key != kNoKey) L.sel_bound[wave] = my_lane_key;   // keys are unique: one lane at most
+    lds_wave_sync();
+    const uint64_t bound = L.sel_bound[wave];          // kNoKey when fewer than k lanes hold columns: keep everything
+    // (2) every element whose (value, lane) key reaches the bound is a candidate
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (active && make_key(z[e], (uint32_t)lane) >= bound) {
+            uint32_t pos = atomicAdd(&L.sel_cnt[wave], 1u);
+            cand[pos] = make_key(z[e], (uint32_t)(col + e));
+        }
+    }
+    lds_wave_sync();
+    const int n_cand = (int)L.sel_cnt[wave];
+    // (3) rank the candidates among themselves by (value desc, id asc); ranks below k are the answer
+    for (int c0 = 0; c0 < n_cand; c0 += 64) {
+        const int c = c0 + lane;
+        const uint64_t mine = (c < n_cand) ? cand[c] : kNoKey;
+        int rk = 0;
+#pragma unroll 8
+        for (int q = 0; q < n_cand; ++q) rk += (cand[q] > mine) ? 1 : 0;
+        if (c < n_cand && rk < k) {
+            part_val[slot * k + rk] = key_value(mine);
+            part_id[slot * k + rk] = (int)key_tiebreak(mine);
+        }
+    }
+    if (lane >= n_cand && lane < k) {                  // fewer than k columns in this chunk
+        part_val[slot * k + lane] = kNegInf;
+        part_id[slot * k + lane] = kNoId;
+    }
+    if (lane == 0) part_ms[slot] = make_float2(m, s);
+    lds_wave_sync();                                   // the buffers are reused by this wavefront's next row
+}
+
+// ---------------------------------------------------------------------------
+// Merge of one row's chunk partials (running max m_c, sum of exp s_c, sorted top-k list per chunk):
+//     lse = M + ln sum_c s_c exp(m_c - M),   M = max_c m_c
+// and the k globally first (logit desc, id asc) candidates.  The order of every reduction is fixed
+// and the selection works on unique keys, so the output does not depend on scheduling.
+//
+// Partials of one row cover increasing, disjoint id ranges and each list is already in output
+// order, so "smaller list position e = c * k + p" breaks ties exactly like "smaller id".
+//   (1) the k-th largest list head (by all-pairs counting) bounds the answer from below;
+//   (2) the entries that reach the bound (at most k lists, k entries each) are gathered;
+//   (3) they are ranked among themselves by counting; ranks below k are the output.
+// NT threads (a multiple of 64, at most 1024) call together; `dyn` holds merge_lds_bytes(chunks, k).
+struct MergeSmall {
+    float red_m[16], red_s[16];
+    uint64_t bound;
+    uint32_t cnt;
+    uint32_t winners[SLIMSPEC_KMAX_INTERNAL];
+};
+
+template <int NT>
+__device__ __forceinline__ void merge_row(unsigned char *dyn, MergeSmall &S, int tid,
+                                          const float2 *__restrict__ ms, const float *__restrict__ pv,
+                                          const int *__restrict__ pi, int chunks, int k,
+                                          int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+{
+    constexpr int NWAVES = NT / 64;
+    uint64_t *heads = reinterpret_cast<uint64_t *>(dyn);                      // [chunks]
+    uint64_t *cand = heads + chunks;                                           // [k * k]
+    float *vals = reinterpret_cast<float *>(cand + (size_t)k * k);            // [chunks * k]
+    const int lane = tid & 63, wave = tid >> 6;
+
+    const int n = chunks * k;
+    for (int e = tid; e < n; e += NT) vals[e] = pv[e];
+    if (tid == 0) { S.bound = kNoKey; S.cnt = 0u; }
+
+    // log-sum-exp: every thread folds its chunks in increasing order, then the block combines
+    float m_t = kNegInf, s_t = 0.f;
+    for (int c = tid; c < chunks; c += NT) {
+        heads[c] = make_key(pv[(size_t)c * k], (uint32_t)(c * k));
+        float2 p = ms[c];
+        float m_new = fmaxf(m_t, p.x);
+        s_t = s_t * fast_exp(m_t - m_new) + p.y * fast_exp(p.x - m_new);
+        m_t = m_new;
+    }
+    const float m_w = wave_max(m_t);
+    float s_w = (m_t == kNegInf) ? 0.f : s_t * fast_exp(m_t - m_w);
+    s_w = wave_sum(s_w);
+    if (lane == 0) { S.red_m[wave] = m_w; S.red_s[wave] = s_w; }
+    __syncthreads();
+    float M = S.red_m[0];
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) M = fmaxf(M, S.red_m[w]);
+    float Ssum = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) Ssum += (S.red_m[w] == kNegInf) ? 0.f : S.red_s[w] * fast_exp(S.red_m[w] - M);
+    const float lse = M + fast_log(Ssum);
+
+    // (1) the k-th largest head
+    for (int c = tid; c < chunks; c += NT) {
+        const uint64_t mine = heads[c];
+        int rank = 0;
+#pragma unroll 8
+        for (int q = 0; q < chunks; ++q) rank += (heads[q] > mine) ? 1 : 0;
+        if (rank == k - 1) S.bound = mine;              // keys are unique: one writer at most
+    }
+    __syncthreads();
+    const uint64_t bound = S.bound;                     // kNoKey when there are fewer than k lists: keep everything
+    // (2) gather what reaches the bound
+    for (int c = tid; c < chunks; c += NT) {
+        if (heads[c] < bound) continue;
+        for (int p = 0; p < k; ++p) {
+            const float v = vals[c * k + p];
+            const uint64_t key = make_key(v, (uint32_t)(c * k + p));
+            if (v == kNegInf || key < bound) break;     // lists are sorted
+            cand[atomicAdd(&S.cnt, 1u)] = key;
+        }
+    }
+    __syncthreads();
+    // (3) rank the gathered entries
+    const int n_cand = (int)S.cnt;
+    for (int c = tid; c < n_cand; c += NT) {
+        const uint64_t mine = cand[c];
+        int rank = 0;
+#pragma unroll 8
+        for (int q = 0; q < n_cand; ++q) rank += (cand[q] > mine) ? 1 : 0;
+        if (rank < k) S.winners[rank] = key_tiebreak(mine);
+    }
+    __syncthreads();
+    if (tid < k) {                                      // n_cand >= k whenever k <= V
+        const uint32_t e = S.winners[tid];
+        out_ids[tid] = pi[e];
+        out_logprobs[tid] = vals[e] - lse;
+    }
+    __syncthreads();                                    // the buffers may be reused for the next row
+}
+
+}  // namespace slimspec

@@ -22,6 +22,12 @@ hipError_t launch_stream_topk(const float *x, const void *M, bool m_is_f32,
 hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int *part_id,
                         int rows, int chunks, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st);
 
+// whole head for up to kGemvMaxRows rows in one launch (down-projection, streaming, merge)
+hipError_t launch_fused_head(bool low_rank, const uint16_t *h, const uint16_t *A, const void *M, bool m_is_f32,
+                             float *tpart, uint32_t *flags, uint32_t *ticket, float2 *ms, float *pv, int *pi,
+                             int rows_here, int d, int K, int V, int chunks, int k, const FusedPlan &fp,
+                             int32_t *out_ids, float *out_lp, hipStream_t st);
+
 // ---- matrix-core path (rows > kGemvMaxRows, bf16 weights) ----
 constexpr int kStreamList = 3;          // groups kept per lane stream
 constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial

@@ -52,6 +52,7 @@ __device__ __forceinline__ void rank_all_pairs(const uint64_t *keys, int n, int 
     for (int c = tid; c < n; c += nthreads) {
         const uint64_t mine = keys[c];
         int rank = 0;
+#pragma unroll 8
         for (int q = 0; q < n; ++q) rank += (keys[q] > mine) ? 1 : 0;
         f(c, mine, rank);
     }
@@ -142,6 +143,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         if (mine == kNoKey) continue;
         const int g0 = e & ~63, g1 = min(n, g0 + 64);
         int rank = 0;
+#pragma unroll 8
         for (int q = g0; q < g1; ++q) rank += (keys[q] > mine) ? 1 : 0;
         if (rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
     }

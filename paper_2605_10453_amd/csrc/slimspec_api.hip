@@ -4,6 +4,7 @@
 #include "../../include/slimspec.h"
 #include "launch.hpp"
 #include <string.h>
+#include <stdlib.h>
 
 using namespace slimspec;
 
@@ -124,8 +125,28 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     int *part_id = reinterpret_cast<int *>(ws + p.off_part_id);
     const uint16_t *hb = static_cast<const uint16_t *>(h);
 
-    // Rows are processed in groups of kGemvMaxRows by the streaming kernels; the
-    // groups reuse the small x / down-projection scratch in stream order.
+    // Rows are processed in groups of kGemvMaxRows by the streaming kernels; the groups reuse the
+    // small scratch in stream order.  A group normally takes ONE launch (down-projection, streaming
+    // and merge fused); when the merge scratch does not fit that kernel (large k) it takes three.
+    const bool fused = fused_head_fits(kGemvMaxRows, p.chunks, k) && !getenv("SLIMSPEC_UNFUSED");
+    if (fused) {
+        const FusedPlan fp = make_fused_plan(kind == HeadKind::LowRank, p.d, p.r);
+        float *tpart = reinterpret_cast<float *>(ws + p.off_tpart);
+        uint32_t *flags = reinterpret_cast<uint32_t *>(ws + p.off_flags);
+        uint32_t *ticket = flags + fp.n_items + 1;
+        for (int row0 = 0; row0 < p.rows; row0 += kGemvMaxRows) {
+            const int rows_here = (p.rows - row0 < kGemvMaxRows) ? p.rows - row0 : kGemvMaxRows;
+            hipError_t e;
+            const bool timed = g_ev_start && row0 == 0;
+            if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
+            e = launch_fused_head(kind == HeadKind::LowRank, hb + (size_t)row0 * p.d, static_cast<const uint16_t *>(A), M, m_is_f32,
+                                  tpart, flags, ticket, part_ms, part_val, part_id, rows_here, p.d, p.K, p.V, p.chunks, k, fp,
+                                  out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+            if (e != hipSuccess) return fail_hip(e);
+            if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
+        }
+        return SLIMSPEC_OK;
+    }
     for (int row0 = 0; row0 < p.rows; row0 += kGemvMaxRows) {
         const int rows_here = (p.rows - row0 < kGemvMaxRows) ? p.rows - row0 : kGemvMaxRows;
         hipError_t e;
