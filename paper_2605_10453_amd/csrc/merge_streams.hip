@@ -20,13 +20,22 @@
 #include "device_utils.hpp"
 #include "launch.hpp"
 
+#ifdef SLIMSPEC_TRACE
+__device__ unsigned long long g_trace2[1024 * 12];
+#define TRACE2(slot) do { if (threadIdx.x == 0) g_trace2[blockIdx.x * 12 + (slot)] = wall_clock64(); } while (0)
+extern "C" void slimspec_read_trace2(unsigned long long *dst) { (void)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace2), sizeof(g_trace2)); }
+#else
+#define TRACE2(slot) do { } while (0)
+#endif
+
 namespace slimspec {
 
 namespace {
 
 constexpr int kWorkCap = 2048;          // collected logits per row before the exhaustive fallback
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
-constexpr float kEpsSigmas = 8.0f;      // eps = this many standard deviations of the rounding error of t
+constexpr float kEpsSigmas = 4.0f;      // eps = this many standard deviations of the rounding error of t
+                                        // (values are re-evaluated when within 2 eps = 5.6 sigma of their difference)
 
 __device__ __forceinline__ float mask4(float v) { return __uint_as_float(__float_as_uint(v) & 0xfffffff0u); }
 
@@ -37,13 +46,6 @@ struct RowCtx {
 
 __device__ __forceinline__ float x_at(const RowCtx &c, int j) {
     return c.x_is_bf16 ? bf16_to_float(static_cast<const uint16_t *>(c.x)[j]) : static_cast<const float *>(c.x)[j];
-}
-
-// exact fp32 logit of one vocabulary id, computed by one wavefront (all 64 lanes must call)
-__device__ __forceinline__ float exact_logit_wave(const RowCtx &c, int id, int lane) {
-    float acc = 0.f;
-    for (int j = lane; j < c.K; j += 64) acc = fmaf(x_at(c, j), bf16_to_float(c.M[(size_t)j * c.V + id]), acc);
-    return wave_sum(acc);
 }
 
 // rank of every key among keys[0, n) by counting; calls f(index, key, rank) for this thread's keys
@@ -71,15 +73,16 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int n = nsr * L;
     const int ngroups = (n + 63) / 64;
-    uint64_t *keys = reinterpret_cast<uint64_t *>(lds_raw);            // [n]            listed maxima
-    uint64_t *surv = keys + n;                                          // [ngroups * k]  best k of every 64
+    uint64_t *keys = reinterpret_cast<uint64_t *>(lds_raw);            // [ngroups * 64] listed maxima, padded with kNoKey
+    uint64_t *surv = keys + (size_t)ngroups * 64;                       // [ngroups * k]  best k of every 64
     uint64_t *work = surv + (size_t)ngroups * k;                        // [kWorkCap]     final keys / fallback buffer
     int *w_id = reinterpret_cast<int *>(work + kWorkCap);               // [kWorkCap]
     float *w_val = reinterpret_cast<float *>(w_id + kWorkCap);          // [kWorkCap]
-    int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]
+    int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]     0 no, 1 / 2 yes; later: list of items to evaluate
+    float *xrow = reinterpret_cast<float *>(w_need + kWorkCap);         // [K]            the row's exact contraction input
     __shared__ float red_m[NWAVES], red_s[NWAVES];
     __shared__ uint64_t tau_key;
-    __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden;
+    __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden, cnt_need;
     __shared__ uint32_t winners[SLIMSPEC_KMAX_INTERNAL];
 
     const int row = blockIdx.x;
@@ -90,19 +93,41 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                       : static_cast<const void *>(static_cast<const float *>(xexact) + (size_t)row * ldx);
     ctx.x_is_bf16 = x_is_bf16; ctx.M = M; ctx.K = K; ctx.V = V;
 
-    if (tid == 0) { tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; }
+    TRACE2(0);
+    if (tid == 0) { tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; cnt_need = 0u; }
+
+    // a stream record as three 16-byte loads; the thread's first stream stays in registers
+    static_assert(REC == 12, "three float4 per record");
+    float4 mine_rec[3];
+    {
+        const float4 *src = reinterpret_cast<const float4 *>(rec + (size_t)min(tid, nsr - 1) * REC);
+        mine_rec[0] = src[0]; mine_rec[1] = src[1]; mine_rec[2] = src[2];
+    }
+    auto load_rec = [&](int sidx, float (&f)[REC]) {
+        float4 a = mine_rec[0], b = mine_rec[1], c = mine_rec[2];
+        if (sidx != tid) {
+            const float4 *src = reinterpret_cast<const float4 *>(rec + (size_t)sidx * REC);
+            a = src[0]; b = src[1]; c = src[2];
+        }
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+        f[8] = c.x; f[9] = c.y; f[10] = c.z; f[11] = c.w;
+    };
 
     // ---- log-sum-exp of the streams, and the squared norm of the row's contraction input
     float m_t = kNegInf, s_t = 0.f, x2 = 0.f;
     for (int sidx = tid; sidx < nsr; sidx += NT) {
-        const float mc = rec[(size_t)sidx * REC], s = rec[(size_t)sidx * REC + 1];
+        float f[REC];
+        load_rec(sidx, f);
+        const float mc = f[0], s = f[1];
         if (s > 0.f) {
             const float m_new = fmaxf(m_t, mc);
             s_t = s_t * __builtin_amdgcn_exp2f(m_t - m_new) + s * __builtin_amdgcn_exp2f(mc - m_new);
             m_t = m_new;
         }
     }
-    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); x2 += v * v; }
+    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; }
+    __shared__ float stat_sh[64];
+    if (stat != nullptr && tid < n_stat && tid < 64) stat_sh[tid] = stat[(size_t)tid * rows_pad + row].x;
     const float m_w = wave_max(m_t);
     float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
     s_w = wave_sum(s_w);
@@ -111,11 +136,18 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __shared__ float red_x[NWAVES];
     if (lane == 0) red_x[wave] = x2;
 
+    TRACE2(1);
     // ---- keys of the listed maxima
-    for (int e = tid; e < n; e += NT) {
-        const float x = rec[(size_t)(e / L) * REC + 3 + 3 * (e % L)];
-        keys[e] = (x > kNoValue) ? make_key(mask4(x), (uint32_t)e) : kNoKey;
+    for (int sidx = tid; sidx < nsr; sidx += NT) {
+        float f[REC];
+        load_rec(sidx, f);
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            const float x = f[3 + 3 * l];
+            keys[sidx * L + l] = (x > kNoValue) ? make_key(mask4(x), (uint32_t)(sidx * L + l)) : kNoKey;
+        }
     }
+    for (int e = n + tid; e < ngroups * 64; e += NT) keys[e] = kNoKey;
     __syncthreads();
     float Mx = red_m[0], X2 = 0.f;
 #pragma unroll
@@ -137,26 +169,32 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         return;
     }
 
+    TRACE2(2);
     // ---- tau: the k-th largest listed maximum (best k of every 64 keys, then all pairs)
     for (int e = tid; e < n; e += NT) {
         const uint64_t mine = keys[e];
         if (mine == kNoKey) continue;
-        const int g0 = e & ~63, g1 = min(n, g0 + 64);
+        const uint4 *grp = reinterpret_cast<const uint4 *>(keys + (e & ~63));       // 64 keys, two per 16-byte read
         int rank = 0;
-#pragma unroll 8
-        for (int q = g0; q < g1; ++q) rank += (keys[q] > mine) ? 1 : 0;
+#pragma unroll
+        for (int q = 0; q < 32; ++q) {
+            const uint4 v = grp[q];
+            rank += (u64_from(v.y, v.x) > mine ? 1 : 0) + (u64_from(v.w, v.z) > mine ? 1 : 0);
+        }
         if (rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
     }
     __syncthreads();
+    TRACE2(3);
     const int n_surv = (int)cnt_surv;
     rank_all_pairs(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
     __syncthreads();
+    TRACE2(4);
     const bool have_tau = tau_key != kNoKey;
     const float tau = have_tau ? key_value(tau_key) : kNegInf;
     float eps;
     if (stat != nullptr) {
         float dt2 = 0.f;                                     // squared norm of t - f16(t), summed in a fixed order
-        for (int q = 0; q < n_stat; ++q) dt2 += stat[(size_t)q * rows_pad + row].x;
+        for (int q = 0; q < n_stat; ++q) dt2 += (q < 64) ? stat_sh[q] : stat[(size_t)q * rows_pad + row].x;
         eps = kEpsSigmas * sqrtf(dt2) * brms[0] + fabsf(tau) * 1.2e-5f + 1e-30f;
     }
     else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
@@ -172,7 +210,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     auto id_of = [&](int tag, int i, int half) { return (tag >> 3) * 256 + 8 * (8 * (i >> 2) + 4 * half + (i & 3)) + (tag & 7); };
     if (!exhaustive) {
         for (int sidx = tid; sidx < nsr; sidx += NT) {
-            const float *r = rec + (size_t)sidx * REC;
+            float r[REC];
+            load_rec(sidx, r);
             const int half = sidx & 1;
             int listed[L];
 #pragma unroll
@@ -209,6 +248,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         }
     }
     __syncthreads();
+    TRACE2(5);
     int n_work = (int)cnt_work;
     if (n_work > kWorkCap || n_work < k) exhaustive = true;
 
@@ -224,16 +264,53 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             if (need) w_need[c] = 2;                      // 2: decided in this pass (w_val still the computed value)
         }
         __syncthreads();
-        for (int c = wave; c < n_work; c += NWAVES) {
-            if (w_need[c] == 0) continue;                 // wavefront-uniform
-            const float z = exact_logit_wave(ctx, w_id[c], lane);
-            if (lane == 0) w_val[c] = z;
+        TRACE2(6);
+        // list the items to evaluate (any order: every result goes back to its own slot)
+        int my_need[(kWorkCap + NT - 1) / NT];
+        int n_mine = 0;
+        for (int c = tid; c < n_work; c += NT) my_need[n_mine++] = w_need[c] ? c : -1;
+        __syncthreads();
+        n_mine = 0;
+        for (int c = tid; c < n_work; c += NT) {
+            const int item = my_need[n_mine++];
+            if (item >= 0) w_need[atomicAdd(&cnt_need, 1u)] = item;
         }
         __syncthreads();
+        // exact fp32 logits, 16 columns at a time: a lane owns (column lane % 16, row phase lane / 16), the
+        // four wavefronts interleave rows, so one load instruction touches 4 rows of M x 16 columns and the
+        // whole block has 16 rows in flight per step; partial sums are combined in a fixed order
+        const int n_need = (int)cnt_need;
+        __shared__ float red_ex[NWAVES][16];
+        for (int g0 = 0; g0 < n_need; g0 += 16) {
+            const int u = lane & 15, jsub = lane >> 4;
+            const int item = w_need[min(g0 + u, n_need - 1)];
+            const int id = w_id[item];
+            float acc = 0.f;
+#pragma unroll 8
+            for (int j = wave * 4 + jsub; j < K; j += 4 * NWAVES)
+                acc = fmaf(xrow[j], bf16_to_float(M[(size_t)j * V + id]), acc);
+            uint32_t a, b;
+            swap_pair<16>(__float_as_uint(acc), a, b);
+            acc = __uint_as_float(a) + __uint_as_float(b);
+            swap_pair<32>(__float_as_uint(acc), a, b);
+            acc = __uint_as_float(a) + __uint_as_float(b);
+            if (lane < 16) red_ex[wave][lane] = acc;
+            __syncthreads();
+            if (tid < 16 && g0 + tid < n_need) {
+                float z = red_ex[0][tid];
+#pragma unroll
+                for (int w = 1; w < NWAVES; ++w) z += red_ex[w][tid];
+                w_val[item] = z;                          // tid < 16: u == tid, so `item` is this column's slot
+            }
+            __syncthreads();
+        }
+        __syncthreads();
+        TRACE2(7);
         for (int c = tid; c < n_work; c += NT) work[c] = make_key(w_val[c], (uint32_t)w_id[c]);
         __syncthreads();
         rank_all_pairs(work, n_work, tid, NT, [&](int c, uint64_t, int rank) { if (rank < k) winners[rank] = (uint32_t)c; });
         __syncthreads();
+        TRACE2(8);
         if (tid < k) {
             const uint32_t c = winners[tid];
             out_ids[(size_t)row * k + tid] = w_id[c];
@@ -304,7 +381,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
 size_t merge_streams_lds_bytes(int nsr, int k) {
     const size_t n = (size_t)nsr * kStreamList;
     const size_t ngroups = (n + 63) / 64;
-    return sizeof(uint64_t) * (n + ngroups * k + kWorkCap) + 12u * kWorkCap;
+    return sizeof(uint64_t) * (ngroups * 64 + ngroups * k + kWorkCap) + 12u * kWorkCap;
 }
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
@@ -312,7 +389,7 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
                                 int32_t *out_ids, float *out_logprobs, hipStream_t st)
 {
-    const size_t lds = merge_streams_lds_bytes(nsr, k);
+    const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
