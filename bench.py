@@ -4,10 +4,10 @@
 One step = one call of the low-rank head (down-projection, vocabulary projection with the
 fused running log-sum-exp / top-k, cross-workgroup merge) through the C ABI on one batch of
 synthetic hidden states, with every input already resident in HBM.  The headline workload is
-the single-row latency shape d=4096, r=512, V=128256, k=10; the 512-row throughput shape and
-the full-head comparator are reported in the "extra" object of the same JSON line.
+the single-row latency shape d=4096, r=512, V=128256, k=10 (C2); the 512-row throughput shape
+(C4) and the full-head comparator are reported in the "extra" object of the same JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C4|...] [--quick]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C5] [--quick]
 
 Prints exactly one JSON line on stdout (progress goes to stderr).
 """
@@ -25,11 +25,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16 matrix peak
-# Rows at and above which the library runs the matrix-core path (must match the library).
-MFMA_MIN_ROWS_ENV = "SLIMSPEC_BENCH_MFMA_ROWS"
+GEMV_MAX_ROWS = 8              # rows up to which the library streams (above: matrix cores)
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (scaled by a plain copy kernel of known size); see profiles/.  None until measured.
+# HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/ (each scaled by the same counter's reading for a plain copy kernel of
+# known size); None where not measured.
 MEASURED_TRAFFIC_BYTES = {}
 
 
@@ -42,14 +42,10 @@ def algorithmic_bytes_low_rank(rows, d, r, V, k):
     return 2 * (d * r + r * V + rows * d) + rows * k * 8
 
 
-def algorithmic_bytes_full(rows, d, V, k):
-    return 2 * (d * V + rows * d) + rows * k * 8
-
-
-def projection_kernel_bytes(rows, K, V, k):
+def projection_kernel_bytes(rows, K, V):
     """Algorithmic bytes of one launch of the vocabulary-projection kernel: the [K, V] bf16 weight
-    matrix once plus its fp32 [rows, K] input."""
-    return 2 * K * V + 4 * rows * K
+    matrix once plus its [rows, K] input (fp32 when streaming, 16-bit on the matrix cores)."""
+    return 2 * K * V + (4 if rows <= GEMV_MAX_ROWS else 2) * rows * K
 
 
 def main():
@@ -85,8 +81,46 @@ def main():
     def upload(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(dev).view(torch.bfloat16)
 
-    def time_low_rank(cfg, x, steps, warmup, copies, with_events):
-        """Returns (seconds for `steps` calls, mean projection-kernel ms or None)."""
+    def null_event_pair_ms(n=50):
+        """Elapsed time between two HIP events recorded back to back on an idle stream position:
+        what an event pair reports around an empty interval."""
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        torch.cuda.synchronize()
+        for a, b in pairs:
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        v = sorted(a.elapsed_time(b) for a, b in pairs)
+        return v[len(v) // 2]
+
+    def _timed(step, steps, warmup, with_events):
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        kern_ms = None
+        if with_events:
+            # The same steps once more, with a HIP event pair recorded by the library around the
+            # projection kernel of every call, on the call's own stream.
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                     for _ in range(steps)]
+            for a, b in pairs:      # create the HIP handles
+                a.record()
+                b.record()
+            torch.cuda.synchronize()
+            for i, (a, b) in enumerate(pairs):
+                binding.slimspec_set_timing_events(a, b)
+                step(i)
+            binding.slimspec_set_timing_events(None, None)
+            torch.cuda.synchronize()
+            kern_ms = sum(a.elapsed_time(b) for a, b in pairs) / steps
+        return dt, kern_ms
+
+    def time_low_rank(cfg, x, steps, warmup, copies, with_events=True):
         h = upload(x.h)
         As = [upload(x.A)]
         Bs = [upload(x.B)]
@@ -104,7 +138,7 @@ def main():
 
         return _timed(step, steps, warmup, with_events)
 
-    def time_full(cfg, x, steps, warmup, copies, with_events):
+    def time_full(cfg, x, steps, warmup, copies, with_events=True):
         h = upload(x.h)
         Ws = [upload(x.W)]
         for _ in range(copies - 1):
@@ -119,60 +153,42 @@ def main():
 
         return _timed(step, steps, warmup, with_events)
 
-    def _timed(step, steps, warmup, with_events):
-        for i in range(warmup):
-            step(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            step(i)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        kern_ms = None
-        if with_events:
-            # Same steps once more, with a HIP event pair recorded by the library around the
-            # projection kernel of every call on the call's own stream.
-            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                     for _ in range(steps)]
-            for a, b in pairs:      # create the HIP handles
-                a.record()
-                b.record()
-            torch.cuda.synchronize()
-            for i, (a, b) in enumerate(pairs):
-                binding.slimspec_set_timing_events(a, b)
-                step(i)
-            binding.slimspec_set_timing_events(None, None)
-            torch.cuda.synchronize()
-            kern_ms = sum(a.elapsed_time(b) for a, b in pairs) / steps
-        return dt, kern_ms
+    def roofline_of(cfg, K, kern_ms, null_ms):
+        """Roofline entry of the vocabulary-projection kernel of one call."""
+        kbytes = projection_kernel_bytes(cfg.rows, K, cfg.V)
+        flops = 2.0 * cfg.rows * K * cfg.V
+        kern_s = kern_ms * 1e-3
+        if cfg.rows > GEMV_MAX_ROWS:
+            ach = flops / kern_s / 1e12
+            out = {"bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                   "frac": ach / MFMA_PEAK_TFLOPS,
+                   "hbm_frac_same_kernel": kbytes / kern_s / 1e9 / HBM_PEAK_GBS}
+        else:
+            ach = kbytes / kern_s / 1e9
+            out = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                   "frac": ach / HBM_PEAK_GBS}
+        out.update({"traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                    "kernel": "vocabulary projection + running log-sum-exp / top-k "
+                              + ("(head_mfma_kernel)" if cfg.rows > GEMV_MAX_ROWS else "(stream_topk_kernel)"),
+                    "kernel_us": kern_ms * 1e3,
+                    "kernel_us_minus_empty_event_pair": (kern_ms - null_ms) * 1e3,
+                    "empty_event_pair_us": null_ms * 1e3,
+                    "algorithmic_bytes_per_launch": kbytes,
+                    "algorithmic_flops_per_launch": flops})
+        return out
 
     # ------------------------------------------------------------------ headline workload
     cfg = synth.CONFIGS[args.workload]
     log(f"[bench] generating {cfg.name}: rows={cfg.rows} d={cfg.d} r={cfg.r} V={cfg.V} k={cfg.k}")
     x = synth.make_inputs(cfg, seed=0)
     copies = max(1, args.copies)
+    null_ms = null_event_pair_ms()
     log(f"[bench] timing low-rank head: {args.warmup} warm-up + {args.steps} steps, {copies} weight copies")
-    dt, kern_ms = time_low_rank(cfg, x, args.steps, args.warmup, copies, with_events=True)
+    dt, kern_ms = time_low_rank(cfg, x, args.steps, args.warmup, copies)
     ms_per_step = dt / args.steps * 1e3
     rows_per_s = cfg.rows * args.steps / dt
-    log(f"[bench] {ms_per_step * 1e3:.2f} us/call, {rows_per_s:.1f} rows/s, projection kernel {kern_ms * 1e3:.2f} us")
-
-    mfma_rows = int(os.environ.get(MFMA_MIN_ROWS_ENV, "16"))
-    kbytes = projection_kernel_bytes(min(cfg.rows, 8) if cfg.rows < mfma_rows else cfg.rows, cfg.r, cfg.V, cfg.k)
-    flops = 2.0 * cfg.rows * cfg.r * cfg.V
-    if cfg.rows >= mfma_rows:
-        ach = flops / (kern_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / MFMA_PEAK_TFLOPS}
-    else:
-        ach = kbytes / (kern_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": ach / HBM_PEAK_GBS}
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(cfg.name)
-    roofline["kernel"] = "vocabulary projection + running log-sum-exp/top-k"
-    roofline["kernel_us"] = kern_ms * 1e3
-    roofline["algorithmic_bytes_per_launch"] = kbytes
-    roofline["algorithmic_flops_per_launch"] = flops
+    log(f"[bench] {ms_per_step * 1e3:.2f} us/call, {rows_per_s:.1f} rows/s, projection kernel {kern_ms * 1e3:.2f} us "
+        f"(empty event pair {null_ms * 1e3:.2f} us)")
 
     out = {
         "metric": "LM-head rows/s (and us/call) at d=4096,r=512,V=128256; % HBM/MFMA peak",
@@ -184,7 +200,7 @@ def main():
         "config": {"workload": f"{cfg.name}: low-rank head rows={cfg.rows} d={cfg.d} r={cfg.r} V={cfg.V} k={cfg.k}, "
                                f"{copies} rotating weight copies (cold last-level cache)",
                    "rows": cfg.rows, "d": cfg.d, "r": cfg.r, "V": cfg.V, "k": cfg.k},
-        "roofline": roofline,
+        "roofline": roofline_of(cfg, cfg.r, kern_ms, null_ms),
         "call_hbm_frac": algorithmic_bytes_low_rank(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k)
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
@@ -215,31 +231,33 @@ def main():
     # ------------------------------------------------------------------ extra workloads (context)
     if not (args.quick or args.no_extra):
         extra = {}
-        # full head on the same shape: the comparator of the paper's relative head time
         log("[bench] full head on the same shape")
         xf = synth.make_inputs(cfg, seed=0, with_full_head=True)
-        fdt, fk = time_full(cfg, xf, max(10, args.steps // 4), 5, 2, with_events=True)
-        fms = fdt / max(10, args.steps // 4) * 1e3
+        nf = max(10, args.steps // 4)
+        fdt, fk = time_full(cfg, xf, nf, 5, 2)
+        fms = fdt / nf * 1e3
+        full_cfg_roof = roofline_of(cfg, cfg.d, fk, null_ms)
         extra["full_head"] = {"us_per_call": fms * 1e3, "projection_kernel_us": fk * 1e3,
-                              "hbm_frac_kernel": projection_kernel_bytes(cfg.rows, cfg.d, cfg.V, cfg.k)
-                                                 / (fk * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "roofline_frac_kernel": full_cfg_roof["frac"], "bound": full_cfg_roof["bound"],
                               "low_rank_speedup": fms / ms_per_step,
                               "ideal_speedup": 1.0 / ((cfg.r / cfg.d) * (1 + cfg.d / cfg.V)),
                               "paper_relative_head_time_r_d8": 0.21,
-                              "paper_hardware": "NVIDIA H200, vLLM 0.17.1 (context only)"}
+                              "paper_hardware": "NVIDIA H200, vLLM 0.17.1 (context only; the paper's head time "
+                                                "excludes softmax / top-k)"}
         del xf
         torch.cuda.empty_cache()
         if cfg.name == "C2":
             c4 = synth.CONFIGS["C4"]
-            log("[bench] 512-row throughput shape")
+            log("[bench] 512-row throughput shape (C4)")
             x4 = synth.make_inputs(c4, seed=0)
-            s4 = 20
-            dt4, k4 = time_low_rank(c4, x4, s4, 3, 2, with_events=True)
+            s4 = 50
+            dt4, k4 = time_low_rank(c4, x4, s4, 5, 2)
             ms4 = dt4 / s4 * 1e3
             fl4 = 2.0 * c4.rows * (c4.d * c4.r + c4.r * c4.V)
+            r4 = roofline_of(c4, c4.r, k4, null_ms)
             extra["C4_512_rows"] = {"us_per_call": ms4 * 1e3, "rows_per_s": c4.rows / (ms4 * 1e-3),
                                     "mfma_frac_call": fl4 / (ms4 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
-                                    "first_projection_kernel_us": k4 * 1e3}
+                                    "roofline": r4}
         out["extra"] = extra
 
     print(json.dumps(out), flush=True)

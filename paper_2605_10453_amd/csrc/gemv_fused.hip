@@ -34,7 +34,7 @@ extern "C" void slimspec_read_trace(unsigned long long *dst) { (void)hipMemcpyFr
 
 namespace {
 
-constexpr int kItemCols = 64;           // columns of A per down-projection item (one 128-byte line per row)
+constexpr int kFusedMergeBytes = 32 * 1024;     // shared memory the last block may use for the merge
 constexpr unsigned kSpinLimit = 1u << 22;
 
 // Polls are relaxed (an acquire load would invalidate the XCD's L2 on every spin); one acquire fence
@@ -46,65 +46,9 @@ __device__ __forceinline__ void store_flag(uint32_t *p, uint32_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// One down-projection item: columns [64 cb, 64 cb + 64) x rows [ds * slice, ds * slice + slice) of A.
-// Thread = (row slot tid / 8, 16-byte piece tid % 8).  tpart is [nds][R][r].
-template <int R, int NT>
-__device__ __forceinline__ void down_item(float (*redd)[R][kItemCols], const uint16_t *__restrict__ h,
-                                          const uint16_t *__restrict__ A, float *__restrict__ tpart,
-                                          int item, int n_cb, int slice, int rows_here, int d, int r, int tid)
-{
-    constexpr int NW = NT / 64;
-    const int cb = item % n_cb, ds = item / n_cb;
-    const int piece = tid & 7, slot = tid >> 3;
-    const int col = cb * kItemCols + piece * 8;
-    const int c_beg = ds * slice, c_end = min(d, c_beg + slice);
-    float acc[R][8];
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
-    if (col < r) {
-        for (int c = c_beg + slot; c < c_end; c += NT / 8) {
-            const uint4 w = *reinterpret_cast<const uint4 *>(A + (size_t)c * r + col);
-            const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
-                                bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                const float hv = (i < rows_here) ? bf16_to_float(h[(size_t)i * d + c]) : 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(hv, f[e], acc[i][e]);
-            }
-        }
-    }
-    // lanes with equal (lane % 8) hold the same columns: butterfly over lane bits 3, 4, 5
-    const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float v = acc[i][e];
-            v += dpp_f32<0x128>(v);                             // row_ror:8  = lane ^ 8 inside a row of 16
-            uint32_t a, b;
-            swap_pair<16>(__float_as_uint(v), a, b);
-            v = __uint_as_float(a) + __uint_as_float(b);
-            swap_pair<32>(__float_as_uint(v), a, b);
-            v = __uint_as_float(a) + __uint_as_float(b);
-            if (lane < 8) redd[wave][i][lane * 8 + e] = v;
-        }
-    __syncthreads();
-    for (int q = tid; q < R * kItemCols; q += NT) {
-        const int i = q / kItemCols, c = q % kItemCols;
-        float s = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) s += redd[w][i][c];        // fixed order
-        if (cb * kItemCols + c < r) tpart[((size_t)ds * R + i) * r + cb * kItemCols + c] = s;
-    }
-    __syncthreads();
-}
-
 }  // namespace
 
-template <int R, int NW, bool LOWRANK, typename WT>
+template <int R, int NW, int PF, bool LOWRANK, typename WT>
 __global__ __launch_bounds__(NW * 64) void fused_head_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, const WT *__restrict__ M,
     float *__restrict__ tpart, uint32_t *__restrict__ flags, uint32_t *__restrict__ ticket, uint32_t tag,
@@ -114,7 +58,8 @@ __global__ __launch_bounds__(NW * 64) void fused_head_kernel(
     int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     constexpr int NT = NW * 64;
-    __shared__ ChunkLds<R, NW> L;
+    __shared__ union { ChunkLds<R, NW> L; unsigned char merge_bytes[kFusedMergeBytes]; } lds_u;
+    ChunkLds<R, NW> &L = lds_u.L;
     __shared__ MergeSmall small;
     __shared__ uint32_t sh_flag;
     extern __shared__ __align__(16) unsigned char dyn[];         // low-rank: t as fp32 [R][K]
@@ -135,13 +80,15 @@ __global__ __launch_bounds__(NW * 64) void fused_head_kernel(
     // order below: the down-projection items first, then the weight prefetch, with wavefront 0
     // polling the flags BEFORE it issues its own prefetch.
     using RawT = decltype(load_raw8(static_cast<const WT *>(nullptr)));
-    RawT q0[U];
-    const bool first_full = active && (j0 + U <= j1);
+    RawT q0[PF][U];                                             // PF batches of U rows kept in flight ahead of t
+    const int n_first = active ? min(PF, (j1 - j0) / U) : 0;    // wavefront-uniform
     auto prefetch_first = [&]() {
-        if (first_full) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) q0[u] = load_raw8(base + (size_t)(j0 + u) * V);
-        }
+        for (int b = 0; b < PF; ++b)
+            if (b < n_first) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) q0[b][u] = load_raw8(base + (size_t)(j0 + b * U + u) * V);
+            }
     };
 
     TRACE(0);
@@ -249,10 +196,12 @@ __global__ __launch_bounds__(NW * 64) void fused_head_kernel(
     };
     if (active) {
         int j = j0;
-        if (first_full) {
-            fma_batch(q0, j);
-            j += U;
-        }
+#pragma unroll
+        for (int b = 0; b < PF; ++b)
+            if (b < n_first) {
+                fma_batch(q0[b], j);
+                j += U;
+            }
         for (; j + U <= j1; j += U) {
             RawT q[U];
 #pragma unroll
@@ -296,9 +245,9 @@ __global__ __launch_bounds__(NW * 64) void fused_head_kernel(
     __syncthreads();
     TRACE(6);
     if (sh_flag != gridDim.x - 1) return;
-    unsigned char *mdyn = reinterpret_cast<unsigned char *>(&L.red[0][0][0]);     // merge scratch: red is free now
+    unsigned char *mdyn = lds_u.merge_bytes;                    // merge scratch: the chunk buffers are free now
     for (int i = 0; i < rows_here; ++i)
-        merge_row<NT>(mdyn, small, tid, part_ms + (size_t)i * chunks, part_val + (size_t)i * chunks * k,
+        merge_row<NT>(mdyn, false, small, tid, part_ms + (size_t)i * chunks, part_val + (size_t)i * chunks * k,
                       part_id + (size_t)i * chunks * k, chunks, k, out_ids + (size_t)i * k, out_logprobs + (size_t)i * k);
     TRACE(7);
     const int n_flags = LOWRANK ? n_items : 1;
@@ -316,17 +265,20 @@ uint32_t next_tag() {
 }  // namespace
 
 bool fused_head_fits(int rows_here, int chunks, int k) {
-    // the merge reuses the 32 KB that hold the wavefronts' partial sums
     (void)rows_here;
-    return merge_lds_bytes(chunks, k) <= sizeof(float) * 16 * kChunkCols;
+    return merge_lds_bytes(chunks, k) <= (size_t)kFusedMergeBytes;
 }
 
 FusedPlan make_fused_plan(bool low_rank, int d, int r) {
     FusedPlan p;
     if (low_rank) {
         p.n_cb = (r + kItemCols - 1) / kItemCols;
-        int slice = ((d + 31) / 32 + 127) / 128 * 128;          // at most 32 slices, each a multiple of 128 rows
-        if (slice < 128) slice = 128;
+        // about 240 items in all (one round of blocks on 256 CUs), at most 32 slices, slices a multiple of 8 rows
+        int want = 240 / p.n_cb;
+        if (want > 32) want = 32;
+        if (want < 1) want = 1;
+        int slice = ((d + want - 1) / want + 7) / 8 * 8;
+        if (slice < 64) slice = 64;
         p.slice = slice;
         p.nds = (d + slice - 1) / slice;
         p.n_items = p.n_cb * p.nds;
@@ -334,12 +286,12 @@ FusedPlan make_fused_plan(bool low_rank, int d, int r) {
     return p;
 }
 
-template <int R, int NW, bool LOWRANK, typename WT>
+template <int R, int NW, int PF, bool LOWRANK, typename WT>
 static hipError_t launch_fused_cfg(const uint16_t *h, const uint16_t *A, const WT *M, float *tpart, uint32_t *flags,
                                    uint32_t *ticket, float2 *ms, float *pv, int *pi, int rows_here, int d, int K, int V,
                                    int chunks, int k, const FusedPlan &fp, int32_t *out_ids, float *out_lp, hipStream_t st)
 {
-    auto fn = fused_head_kernel<R, NW, LOWRANK, WT>;
+    auto fn = fused_head_kernel<R, NW, PF, LOWRANK, WT>;
     const size_t dyn = LOWRANK ? sizeof(float) * (size_t)R * K : 0;
     if (dyn > 16 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
@@ -355,11 +307,15 @@ static hipError_t launch_fused_rows(const uint16_t *h, const uint16_t *A, const 
                                     uint32_t *ticket, float2 *ms, float *pv, int *pi, int rows_here, int d, int K, int V,
                                     int chunks, int k, const FusedPlan &fp, int32_t *out_ids, float *out_lp, hipStream_t st)
 {
-#define SLIMSPEC_FUSED(R, NW) launch_fused_cfg<R, NW, LOWRANK, WT>(h, A, M, tpart, flags, ticket, ms, pv, pi, rows_here, d, K, V, chunks, k, fp, out_ids, out_lp, st)
-    if (rows_here <= 1) return SLIMSPEC_FUSED(1, 16);
-    if (rows_here <= 2) return SLIMSPEC_FUSED(2, 8);
-    if (rows_here <= 4) return SLIMSPEC_FUSED(4, 4);
-    return SLIMSPEC_FUSED(8, 2);
+#define SLIMSPEC_FUSED(R, NW, PF) launch_fused_cfg<R, NW, PF, LOWRANK, WT>(h, A, M, tpart, flags, ticket, ms, pv, pi, rows_here, d, K, V, chunks, k, fp, out_ids, out_lp, st)
+    // one row: 8 wavefronts (256 registers each) so that three batches of 16 rows can be in flight per lane
+    if (rows_here <= 1) {
+        if constexpr (sizeof(WT) == 2) return SLIMSPEC_FUSED(1, 8, 3);
+        else return SLIMSPEC_FUSED(1, 16, 1);
+    }
+    if (rows_here <= 2) return SLIMSPEC_FUSED(2, 8, 1);
+    if (rows_here <= 4) return SLIMSPEC_FUSED(4, 4, 1);
+    return SLIMSPEC_FUSED(8, 2, 1);
 #undef SLIMSPEC_FUSED
 }
 

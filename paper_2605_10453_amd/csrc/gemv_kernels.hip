@@ -2,7 +2,7 @@
 // is bound by reading the weight matrix once from HBM (paper section 4.1: the
 // O(rd + Vr) low-rank head and the O(Vd) full head).
 //
-//   down_strip_kernel     t = h A, one block per strip of 8 columns of A over all of d
+//   down_items_kernel     t = h A as slices over d, one block per (64 columns of A) x (slice of d)
 //   widen_rows_kernel     bf16 h -> fp32 (contraction input of the full head)
 //   stream_topk_kernel    z[:, chunk] = x M[:, chunk] for a 512-column chunk, then the
 //                         chunk's running max, sum of exp and top-k, one partial per
@@ -13,70 +13,17 @@
 namespace slimspec {
 
 // ---------------------------------------------------------------------------
-// t = h A for up to R rows.  A is [d, r] row-major bf16.  Block b owns columns
-// [8b, 8b + 8) (one 128-bit load per row of A); its 1024 threads take the rows of A
-// c = tid, tid + 1024, ... and the partial sums are combined in a fixed order: lanes
-// of a wavefront by the DPP butterfly, wavefronts in index order.  t is fp32 [R, r].
+// t = h A for up to R rows, as slices: block = one item (64 columns of A x a slice of d, read as
+// full 128-byte lines); tpart is [nds][R][r] and the consumer adds the nds slices in order.
 constexpr int kDownThreads = 1024;
 
 template <int R>
-__global__ __launch_bounds__(kDownThreads) void down_strip_kernel(
-    const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ t,
-    int rows_here, int d, int r)
+__global__ __launch_bounds__(kDownThreads) void down_items_kernel(
+    const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ tpart,
+    int rows_here, int d, int r, int n_cb, int slice)
 {
-    __shared__ float red[kDownThreads / 64][R * 8];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    // blocks are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of strips
-    // so that the 128-byte lines of A it touches are used in full inside its own L2
-    const int nstrips = r / 8;
-    const int per_xcd = gridDim.x / 8;              // the grid is 8 * ceil(nstrips / 8) blocks
-    const int strip = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (strip >= nstrips) return;
-    const int col = strip * 8;
-
-    float acc[R][8];
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
-
-    constexpr int U = 4;
-    for (int c0 = tid; c0 < d; c0 += kDownThreads * U) {
-        uint4 w[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int c = c0 + u * kDownThreads;
-            w[u] = (c < d) ? *reinterpret_cast<const uint4 *>(A + (size_t)c * r + col) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int c = c0 + u * kDownThreads;
-            float f[8] = {bf16_lo(w[u].x), bf16_hi(w[u].x), bf16_lo(w[u].y), bf16_hi(w[u].y),
-                          bf16_lo(w[u].z), bf16_hi(w[u].z), bf16_lo(w[u].w), bf16_hi(w[u].w)};
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                float hv = (c < d && i < rows_here) ? bf16_to_float(h[(size_t)i * d + c]) : 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(hv, f[e], acc[i][e]);
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < R; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float s = wave_sum(acc[i][e]);
-            if (lane == 0) red[wave][i * 8 + e] = s;
-        }
-    __syncthreads();
-    if (tid < R * 8) {
-        float s = 0.f;
-#pragma unroll
-        for (int w = 0; w < kDownThreads / 64; ++w) s += red[w][tid];
-        int i = tid >> 3, e = tid & 7;
-        if (i < rows_here) t[(size_t)i * r + col + e] = s;
-    }
+    __shared__ float redd[kDownThreads / 64][R][kItemCols];
+    down_item<R, kDownThreads>(redd, h, A, tpart, blockIdx.x, n_cb, slice, rows_here, d, r, threadIdx.x);
 }
 
 __global__ __launch_bounds__(256) void widen_rows_kernel(
@@ -92,13 +39,19 @@ __global__ __launch_bounds__(256) void widen_rows_kernel(
 // wavefronts split K; every lane owns 8 adjacent columns and keeps R x 8 fp32
 // accumulators.  After a fixed-order sum over the wavefronts, wavefront i % NW
 // reduces row i of the chunk to (max, sum of exp, top-k) and writes the partial.
-template <int R, int NW, typename WT>
+//
+// SLICES: x is not the contraction input itself but nds partial sums of it, [nds][R][K] (the
+// slices of t left by down_items_kernel); the block first adds them, in slice order, into shared
+// memory.  The first weight rows are requested before that, so the adds hide behind them.
+template <int R, int NW, typename WT, bool SLICES>
 __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
-    const float *__restrict__ x, const WT *__restrict__ M,
+    const float *__restrict__ x, int nds, const WT *__restrict__ M,
     float2 *__restrict__ part_ms, float *__restrict__ part_val, int *__restrict__ part_id,
     int rows_here, int row0, int K, int V, int chunks, int k)
 {
     __shared__ ChunkLds<R, NW> L;
+    extern __shared__ __align__(16) unsigned char dyn[];         // SLICES: t as fp32 [R][K]
+    float *xs = reinterpret_cast<float *>(dyn);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int chunk = blockIdx.x;
@@ -112,14 +65,86 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
         for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
 
     // rows [j0, j1) of M for this wavefront
-    const int per = (K + NW - 1) / NW;
+    const int per = ((K + NW - 1) / NW + 7) & ~7;            // multiple of 8: keeps 8-wide reads of x aligned
     const int j0 = min(K, wave * per), j1 = min(K, j0 + per);
-    if (active) {
-        constexpr int U = (sizeof(WT) == 2 && R <= 2) ? 16 : 8;
-        const WT *base = M + col;
+    constexpr int U = (sizeof(WT) == 2 && R <= 2) ? 16 : 8;
+    using RawT = decltype(load_raw8(static_cast<const WT *>(nullptr)));
+    const WT *base = M + (active ? col : 0);
+
+    if constexpr (SLICES) {
+        // slices of t first (they come from L2), then the first batch of weight rows, then the adds
+        constexpr int NT = NW * 64;
+        constexpr int PER_T = 8;
+        const size_t stride = (size_t)R * K;
+        RawT q0[U];
+        const bool first_full = active && (j0 + U <= j1);
+        for (int e0 = 0; e0 < R * K; e0 += NT) {
+            const int e = e0 + threadIdx.x;
+            float s = 0.f;
+            if (e < R * K) {
+                int ds = 0;
+                for (; ds + PER_T <= nds; ds += PER_T) {
+                    float v[PER_T];
+#pragma unroll
+                    for (int u = 0; u < PER_T; ++u) v[u] = x[(size_t)(ds + u) * stride + e];
+#pragma unroll
+                    for (int u = 0; u < PER_T; ++u) s += v[u];
+                }
+                for (; ds < nds; ++ds) s += x[(size_t)ds * stride + e];
+                xs[e] = s;
+            }
+        }
+        if (first_full) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) q0[u] = load_raw8(base + (size_t)(j0 + u) * V);
+        }
+        __syncthreads();
+        auto fma_batch = [&](const RawT (&q)[U], int j) {
+#pragma unroll
+            for (int g = 0; g < U / 8; ++g) {
+                float xv[R][8];
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    const float4 *p = reinterpret_cast<const float4 *>(xs + i * K + j + 8 * g);
+                    const float4 a = p[0], b = p[1];
+                    xv[i][0] = a.x; xv[i][1] = a.y; xv[i][2] = a.z; xv[i][3] = a.w;
+                    xv[i][4] = b.x; xv[i][5] = b.y; xv[i][6] = b.z; xv[i][7] = b.w;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    float f[8];
+                    widen8(q[8 * g + u], f);
+#pragma unroll
+                    for (int i = 0; i < R; ++i)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(xv[i][u], f[e], acc[i][e]);
+                }
+            }
+        };
+        if (active) {
+            int j = j0;
+            if (first_full) { fma_batch(q0, j); j += U; }
+            for (; j + U <= j1; j += U) {
+                RawT q[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) q[u] = load_raw8(base + (size_t)(j + u) * V);
+                fma_batch(q, j);
+            }
+            for (; j < j1; ++j) {
+                float f[8];
+                widen8(load_raw8(base + (size_t)j * V), f);
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    const float xv = xs[i * K + j];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(xv, f[e], acc[i][e]);
+                }
+            }
+        }
+    } else if (active) {
         int j = j0;
         for (; j + U <= j1; j += U) {
-            decltype(load_raw8(base)) q[U];
+            RawT q[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) q[u] = load_raw8(base + (size_t)(j + u) * V);
 #pragma unroll
@@ -161,20 +186,20 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
 // launchers
 
 template <int R>
-static hipError_t launch_down(const uint16_t *h, const uint16_t *A, float *t,
-                              int rows_here, int d, int r, hipStream_t st)
+static hipError_t launch_down(const uint16_t *h, const uint16_t *A, float *tpart,
+                              int rows_here, int d, int r, const FusedPlan &fp, hipStream_t st)
 {
-    down_strip_kernel<R><<<8 * ((r / 8 + 7) / 8), kDownThreads, 0, st>>>(h, A, t, rows_here, d, r);
+    down_items_kernel<R><<<fp.n_items, kDownThreads, 0, st>>>(h, A, tpart, rows_here, d, r, fp.n_cb, fp.slice);
     return hipGetLastError();
 }
 
-hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *t,
-                                  int rows_here, int d, int r, hipStream_t st)
+hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *tpart,
+                                  int rows_here, int d, int r, const FusedPlan &fp, hipStream_t st)
 {
-    if (rows_here <= 1) return launch_down<1>(h, A, t, rows_here, d, r, st);
-    if (rows_here <= 2) return launch_down<2>(h, A, t, rows_here, d, r, st);
-    if (rows_here <= 4) return launch_down<4>(h, A, t, rows_here, d, r, st);
-    return launch_down<8>(h, A, t, rows_here, d, r, st);
+    if (rows_here <= 1) return launch_down<1>(h, A, tpart, rows_here, d, r, fp, st);
+    if (rows_here <= 2) return launch_down<2>(h, A, tpart, rows_here, d, r, fp, st);
+    if (rows_here <= 4) return launch_down<4>(h, A, tpart, rows_here, d, r, fp, st);
+    return launch_down<8>(h, A, tpart, rows_here, d, r, fp, st);
 }
 
 hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)
@@ -184,30 +209,41 @@ hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)
 }
 
 template <int R, int NW, typename WT>
-static hipError_t launch_stream(const float *x, const WT *M, float2 *ms, float *pv, int *pi,
+static hipError_t launch_stream(const float *x, int nds, const WT *M, float2 *ms, float *pv, int *pi,
                                 int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st)
 {
-    stream_topk_kernel<R, NW, WT><<<chunks, NW * 64, 0, st>>>(x, M, ms, pv, pi, rows_here, row0, K, V, chunks, k);
+    if (nds > 0) {
+        auto fn = stream_topk_kernel<R, NW, WT, true>;
+        const size_t dyn = sizeof(float) * (size_t)R * K;
+        if (dyn > 16 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+            if (e != hipSuccess) return e;
+        }
+        fn<<<chunks, NW * 64, dyn, st>>>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k);
+    } else {
+        stream_topk_kernel<R, NW, WT, false><<<chunks, NW * 64, 0, st>>>(x, 0, M, ms, pv, pi, rows_here, row0, K, V, chunks, k);
+    }
     return hipGetLastError();
 }
 
 template <typename WT>
-static hipError_t launch_stream_rows(const float *x, const WT *M, float2 *ms, float *pv, int *pi,
+static hipError_t launch_stream_rows(const float *x, int nds, const WT *M, float2 *ms, float *pv, int *pi,
                                      int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st)
 {
     // shared memory is NW * R * 2 KB: keep it at 32 KB
-    if (rows_here <= 1) return launch_stream<1, 16, WT>(x, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    if (rows_here <= 2) return launch_stream<2, 8, WT>(x, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    if (rows_here <= 4) return launch_stream<4, 4, WT>(x, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    return launch_stream<8, 2, WT>(x, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+    if (rows_here <= 1) return launch_stream<1, 16, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+    if (rows_here <= 2) return launch_stream<2, 8, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+    if (rows_here <= 4) return launch_stream<4, 4, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+    return launch_stream<8, 2, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
 }
 
-hipError_t launch_stream_topk(const float *x, const void *M, bool m_is_f32, float2 *ms, float *pv, int *pi,
+// nds > 0: x holds nds slices [nds][R][K] of the contraction input (R = 1, 2, 4 or 8 as chosen for rows_here)
+hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_f32, float2 *ms, float *pv, int *pi,
                               int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st)
 {
     if (m_is_f32)
-        return launch_stream_rows<float>(x, (const float *)M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    return launch_stream_rows<uint16_t>(x, (const uint16_t *)M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+        return launch_stream_rows<float>(x, nds, (const float *)M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+    return launch_stream_rows<uint16_t>(x, nds, (const uint16_t *)M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
 }
 
 }  // namespace slimspec

@@ -24,6 +24,67 @@ __device__ __forceinline__ void widen8(const Raw8F32 &q, float (&f)[8]) {
 }
 
 // ---------------------------------------------------------------------------
+// Down-projection t = h A shared out in items of (64 columns of A) x (a slice of d).
+constexpr int kItemCols = 64;           // columns of A per item: one 128-byte line per row of A
+
+// One down-projection item: columns [64 cb, 64 cb + 64) x rows [ds * slice, ds * slice + slice) of A.
+// Thread = (row slot tid / 8, 16-byte piece tid % 8).  tpart is [nds][R][r].
+template <int R, int NT>
+__device__ __forceinline__ void down_item(float (*redd)[R][kItemCols], const uint16_t *__restrict__ h,
+                                          const uint16_t *__restrict__ A, float *__restrict__ tpart,
+                                          int item, int n_cb, int slice, int rows_here, int d, int r, int tid)
+{
+    constexpr int NW = NT / 64;
+    const int cb = item % n_cb, ds = item / n_cb;
+    const int piece = tid & 7, slot = tid >> 3;
+    const int col = cb * kItemCols + piece * 8;
+    const int c_beg = ds * slice, c_end = min(d, c_beg + slice);
+    float acc[R][8];
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
+    if (col < r) {
+        for (int c = c_beg + slot; c < c_end; c += NT / 8) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(A + (size_t)c * r + col);
+            const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                const float hv = (i < rows_here) ? bf16_to_float(h[(size_t)i * d + c]) : 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(hv, f[e], acc[i][e]);
+            }
+        }
+    }
+    // lanes with equal (lane % 8) hold the same columns: butterfly over lane bits 3, 4, 5
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[i][e];
+            v += dpp_f32<0x128>(v);                             // row_ror:8  = lane ^ 8 inside a row of 16
+            uint32_t a, b;
+            swap_pair<16>(__float_as_uint(v), a, b);
+            v = __uint_as_float(a) + __uint_as_float(b);
+            swap_pair<32>(__float_as_uint(v), a, b);
+            v = __uint_as_float(a) + __uint_as_float(b);
+            if (lane < 8) redd[wave][i][lane * 8 + e] = v;
+        }
+    __syncthreads();
+    for (int q = tid; q < R * kItemCols; q += NT) {
+        const int i = q / kItemCols, c = q % kItemCols;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += redd[w][i][c];        // fixed order
+        if (cb * kItemCols + c < r) tpart[((size_t)ds * R + i) * r + cb * kItemCols + c] = s;
+    }
+    __syncthreads();
+}
+
+
+// ---------------------------------------------------------------------------
 // Shared memory of the chunk epilogue: the partial sums of the NW wavefronts that split the
 // contraction, and the selection scratch of the wavefronts that reduce a row each.
 template <int R, int NW>
@@ -127,7 +188,7 @@ __device__ __forceinline__ void chunk_row_epilogue(ChunkLds<R, NW> &L, int i, in
 //   (1) the k-th largest list head (by all-pairs counting) bounds the answer from below;
 //   (2) the entries that reach the bound (at most k lists, k entries each) are gathered;
 //   (3) they are ranked among themselves by counting; ranks below k are the output.
-// NT threads (a multiple of 64, at most 1024) call together; `dyn` holds merge_lds_bytes(chunks, k).
+// NT threads (a multiple of 64, at most 1024) call together; `dyn` holds merge_lds_bytes(chunks, k, cache_ids).
 struct MergeSmall {
     float red_m[16], red_s[16];
     uint64_t bound;
@@ -136,7 +197,7 @@ struct MergeSmall {
 };
 
 template <int NT>
-__device__ __forceinline__ void merge_row(unsigned char *dyn, MergeSmall &S, int tid,
+__device__ __forceinline__ void merge_row(unsigned char *dyn, bool cache_ids, MergeSmall &S, int tid,
                                           const float2 *__restrict__ ms, const float *__restrict__ pv,
                                           const int *__restrict__ pi, int chunks, int k,
                                           int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
@@ -145,10 +206,14 @@ __device__ __forceinline__ void merge_row(unsigned char *dyn, MergeSmall &S, int
     uint64_t *heads = reinterpret_cast<uint64_t *>(dyn);                      // [chunks]
     uint64_t *cand = heads + chunks;                                           // [k * k]
     float *vals = reinterpret_cast<float *>(cand + (size_t)k * k);            // [chunks * k]
+    int *ids = reinterpret_cast<int *>(vals + (size_t)chunks * k);            // [chunks * k]
     const int lane = tid & 63, wave = tid >> 6;
 
     const int n = chunks * k;
-    for (int e = tid; e < n; e += NT) vals[e] = pv[e];
+    for (int e = tid; e < n; e += NT) {
+        vals[e] = pv[e];
+        if (cache_ids) ids[e] = pi[e];                  // when they fit: no dependent load at the end
+    }
     if (tid == 0) { S.bound = kNoKey; S.cnt = 0u; }
 
     // log-sum-exp: every thread folds its chunks in increasing order, then the block combines
@@ -206,7 +271,7 @@ __device__ __forceinline__ void merge_row(unsigned char *dyn, MergeSmall &S, int
     __syncthreads();
     if (tid < k) {                                      // n_cand >= k whenever k <= V
         const uint32_t e = S.winners[tid];
-        out_ids[tid] = pi[e];
+        out_ids[tid] = cache_ids ? ids[e] : pi[e];
         out_logprobs[tid] = vals[e] - lse;
     }
     __syncthreads();                                    // the buffers may be reused for the next row

@@ -6,15 +6,16 @@
 
 namespace slimspec {
 
-// t = h A (fp32) for up to kGemvMaxRows rows.
-hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *t,
-                                  int rows_here, int d, int r, hipStream_t st);
+// slices of t = h A (fp32, [nds][R][r] with R = 1, 2, 4 or 8 >= rows_here) for up to kGemvMaxRows rows
+hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *tpart,
+                                  int rows_here, int d, int r, const FusedPlan &fp, hipStream_t st);
 
 // x = float(h) for the full head.
 hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st);
 
-// One partial (max, sum of exp, top-k) per (row, 512-column chunk) from x [rows_here, K] and M [K, V].
-hipError_t launch_stream_topk(const float *x, const void *M, bool m_is_f32,
+// One partial (max, sum of exp, top-k) per (row, 512-column chunk) from x [rows_here, K] (nds = 0) or
+// from nds slices of it (the output of launch_down_projection), and M [K, V].
+hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_f32,
                               float2 *part_ms, float *part_val, int *part_id,
                               int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st);
 

@@ -7,12 +7,12 @@ namespace slimspec {
 
 __global__ __launch_bounds__(kMergeThreads) void merge_kernel(
     const float2 *__restrict__ part_ms, const float *__restrict__ part_val, const int *__restrict__ part_id,
-    int chunks, int k, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+    int chunks, int k, int cache_ids, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ MergeSmall small;
     const int row = blockIdx.x;
-    merge_row<kMergeThreads>(lds_raw, small, threadIdx.x, part_ms + (size_t)row * chunks,
+    merge_row<kMergeThreads>(lds_raw, cache_ids != 0, small, threadIdx.x, part_ms + (size_t)row * chunks,
                              part_val + (size_t)row * chunks * k, part_id + (size_t)row * chunks * k,
                              chunks, k, out_ids + (size_t)row * k, out_logprobs + (size_t)row * k);
 }
@@ -20,13 +20,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(
 hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int *part_id,
                         int rows, int chunks, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st)
 {
-    size_t lds = merge_lds_bytes(chunks, k);
+    const bool cache_ids = merge_lds_bytes(chunks, k, true) <= 64 * 1024;
+    size_t lds = merge_lds_bytes(chunks, k, cache_ids);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    merge_kernel<<<rows, kMergeThreads, lds, st>>>(part_ms, part_val, part_id, chunks, k, out_ids, out_logprobs);
+    merge_kernel<<<rows, kMergeThreads, lds, st>>>(part_ms, part_val, part_id, chunks, k, cache_ids ? 1 : 0, out_ids, out_logprobs);
     return hipGetLastError();
 }
 

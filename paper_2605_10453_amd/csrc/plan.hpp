@@ -58,9 +58,9 @@ inline Plan make_plan(HeadKind kind, int rows, int d, int r, int V, int k) {
 }
 
 // Dynamic shared memory of the merge kernel: the head key of every list, the gathered
-// candidates (at most k lists of k entries) and every list's k logits.
-inline size_t merge_lds_bytes(int chunks, int k) {
-    return sizeof(uint64_t) * ((size_t)chunks + (size_t)k * k) + sizeof(float) * (size_t)chunks * k;
+// candidates (at most k lists of k entries), every list's k logits and, optionally, its k ids.
+inline size_t merge_lds_bytes(int chunks, int k, bool with_ids = false) {
+    return sizeof(uint64_t) * ((size_t)chunks + (size_t)k * k) + (with_ids ? 2 : 1) * sizeof(float) * (size_t)chunks * k;
 }
 constexpr size_t kMergeLdsLimit = 160 * 1024 - 1024;
 

@@ -128,7 +128,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     // Rows are processed in groups of kGemvMaxRows by the streaming kernels; the groups reuse the
     // small scratch in stream order.  A group normally takes ONE launch (down-projection, streaming
     // and merge fused); when the merge scratch does not fit that kernel (large k) it takes three.
-    const bool fused = fused_head_fits(kGemvMaxRows, p.chunks, k) && !getenv("SLIMSPEC_UNFUSED");
+    const bool fused = fused_head_fits(kGemvMaxRows, p.chunks, k) && getenv("SLIMSPEC_FUSED");
     if (fused) {
         const FusedPlan fp = make_fused_plan(kind == HeadKind::LowRank, p.d, p.r);
         float *tpart = reinterpret_cast<float *>(ws + p.off_tpart);
@@ -147,18 +147,21 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         }
         return SLIMSPEC_OK;
     }
+    const FusedPlan dp = make_fused_plan(kind == HeadKind::LowRank, p.d, p.r);
+    float *tpart = reinterpret_cast<float *>(ws + p.off_tpart);
     for (int row0 = 0; row0 < p.rows; row0 += kGemvMaxRows) {
         const int rows_here = (p.rows - row0 < kGemvMaxRows) ? p.rows - row0 : kGemvMaxRows;
         hipError_t e;
         if (kind == HeadKind::LowRank)
             e = launch_down_projection(hb + (size_t)row0 * p.d, static_cast<const uint16_t *>(A),
-                                       x, rows_here, p.d, p.r, s);
+                                       tpart, rows_here, p.d, p.r, dp, s);
         else
             e = launch_widen_rows(hb + (size_t)row0 * p.d, x, rows_here * p.d, s);
         if (e != hipSuccess) return fail_hip(e);
         const bool timed = g_ev_start && row0 == 0;
         if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-        e = launch_stream_topk(x, M, m_is_f32, part_ms, part_val, part_id,
+        e = launch_stream_topk(kind == HeadKind::LowRank ? tpart : x, kind == HeadKind::LowRank ? dp.nds : 0, M, m_is_f32,
+                               part_ms, part_val, part_id,
                                rows_here, row0, p.K, p.V, p.chunks, k, s);
         if (e != hipSuccess) return fail_hip(e);
         if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
