@@ -30,7 +30,7 @@ GEMV_MAX_ROWS = 8              # rows up to which the library streams (above: ma
 # HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/ (each scaled by the same counter's reading for a plain copy kernel of
 # known size); None where not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"C2": 131977480, "C4": 142534173}
 
 
 def log(*a):
@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--quick", action="store_true", help="skip the extra workloads and the CPU baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra workloads only")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch a plain elementwise copy of 128 MiB a few times: the reference a counter run "
+                         "scales its FETCH_SIZE / WRITE_SIZE readings by")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -204,6 +207,16 @@ def main():
         "call_hbm_frac": algorithmic_bytes_low_rank(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k)
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
+
+    if args.copy_probe:
+        src = torch.ones(32 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)       # one elementwise kernel: reads 128 MiB, writes 128 MiB
+        torch.cuda.synchronize()
+        out["copy_probe"] = {"kernel": "torch elementwise mul by 1.0", "bytes_read": src.numel() * 4,
+                             "bytes_written": dst.numel() * 4, "launches": 5}
+        del src, dst
 
     # ------------------------------------------------------------------ CPU baseline (the fp64 checker)
     if not args.quick:
