@@ -34,6 +34,8 @@ namespace {
 
 constexpr int kWorkCap = 2048;          // collected logits per row before the exhaustive fallback
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
+constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
+constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
 constexpr float kEpsSigmas = 4.0f;      // eps = this many standard deviations of the rounding error of t
                                         // (values are re-evaluated when within 2 eps = 5.6 sigma of their difference)
 
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ brms,
-    int k, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+    int k, int contig, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -79,7 +81,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     int *w_id = reinterpret_cast<int *>(work + kWorkCap);               // [kWorkCap]
     float *w_val = reinterpret_cast<float *>(w_id + kWorkCap);          // [kWorkCap]
     int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]     0 no, 1 / 2 yes; later: list of items to evaluate
-    float *xrow = reinterpret_cast<float *>(w_need + kWorkCap);         // [K]            the row's exact contraction input
+    float *w_apx = reinterpret_cast<float *>(w_need + kWorkCap);        // [kWorkCap]     change of the item's term of the sum of exp; later by rank
+    float *xrow = w_apx + kWorkCap;                                     // [K]            the row's exact contraction input
     __shared__ float red_m[NWAVES], red_s[NWAVES];
     __shared__ uint64_t tau_key;
     __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden, cnt_need;
@@ -199,15 +202,21 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     }
     else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
     const float theta = have_tau ? tau - 2.f * eps : kNegInf;
+    // a computed value may be off by eps: beyond this bound the winners' log-probabilities take the exact value
+    const bool exact_all = eps > kExactWinnersEps;
     bool exhaustive = !(eps < 1e30f) || !(lse == lse) || !(fabsf(lse) < 1e30f);   // overflow of the 16-bit input
 
     // ---- collect
     auto push = [&](int id, float val, int need) {
         const uint32_t slot = atomicAdd(&cnt_work, 1u);
-        if (slot < (uint32_t)kWorkCap) { w_id[slot] = id; w_val[slot] = val; w_need[slot] = need; }
+        if (slot < (uint32_t)kWorkCap) { w_id[slot] = id; w_val[slot] = val; w_need[slot] = need; w_apx[slot] = 0.f; }
         if (need) atomicAdd(&cnt_hidden, 1u);
     };
-    auto id_of = [&](int tag, int i, int half) { return (tag >> 3) * 256 + 8 * (8 * (i >> 2) + 4 * half + (i & 3)) + (tag & 7); };
+    // column of member i of a group: an MFMA tile covers 32 adjacent columns (contig) or every eighth column
+    auto id_of = [&](int tag, int i, int half) {
+        const int pos = 8 * (i >> 2) + 4 * half + (i & 3);
+        return (tag >> 3) * 256 + (contig ? 32 * (tag & 7) + pos : 8 * pos + (tag & 7));
+    };
     if (!exhaustive) {
         for (int sidx = tid; sidx < nsr; sidx += NT) {
             float r[REC];
@@ -257,7 +266,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         const bool any_hidden = cnt_hidden != 0u;
         for (int c = tid; c < n_work; c += NT) {
             if (w_need[c]) continue;
-            bool need = any_hidden;
+            bool need = any_hidden || exact_all;
             const float mine = w_val[c];
             for (int q = 0; q < n_work && !need; ++q)
                 if (q != c && fabsf(w_val[q] - mine) <= 2.f * eps) need = true;
@@ -268,7 +277,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         // list the items to evaluate (any order: every result goes back to its own slot)
         int my_need[(kWorkCap + NT - 1) / NT];
         int n_mine = 0;
-        for (int c = tid; c < n_work; c += NT) my_need[n_mine++] = w_need[c] ? c : -1;
+        for (int c = tid; c < n_work; c += NT) my_need[n_mine++] = w_need[c] ? (c | (w_need[c] == 2 ? kListedBit : 0)) : -1;
         __syncthreads();
         n_mine = 0;
         for (int c = tid; c < n_work; c += NT) {
@@ -283,7 +292,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         __shared__ float red_ex[NWAVES][16];
         for (int g0 = 0; g0 < n_need; g0 += 16) {
             const int u = lane & 15, jsub = lane >> 4;
-            const int item = w_need[min(g0 + u, n_need - 1)];
+            const int entry = w_need[min(g0 + u, n_need - 1)];
+            const int item = entry & (kListedBit - 1);
             const int id = w_id[item];
             float acc = 0.f;
 #pragma unroll 8
@@ -300,7 +310,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 float z = red_ex[0][tid];
 #pragma unroll
                 for (int w = 1; w < NWAVES; ++w) z += red_ex[w][tid];
-                w_val[item] = z;                          // tid < 16: u == tid, so `item` is this column's slot
+                // tid < 16: u == tid, so `item` is this column's slot.  A listed maximum had its computed value
+                // in the streams' sum of exp: remember by how much its term changes
+                if (entry & kListedBit) w_apx[item] = __builtin_amdgcn_exp2f(z * kLog2e - Mx) - __builtin_amdgcn_exp2f(w_val[item] * kLog2e - Mx);
+                w_val[item] = z;
             }
             __syncthreads();
         }
@@ -308,13 +321,22 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         TRACE2(7);
         for (int c = tid; c < n_work; c += NT) work[c] = make_key(w_val[c], (uint32_t)w_id[c]);
         __syncthreads();
-        rank_all_pairs(work, n_work, tid, NT, [&](int c, uint64_t, int rank) { if (rank < k) winners[rank] = (uint32_t)c; });
+        // the changes of the re-evaluated terms of the sum of exp, ordered by rank so that their sum has a fixed order
+        float *by_rank = reinterpret_cast<float *>(w_need);
+        rank_all_pairs(work, n_work, tid, NT, [&](int c, uint64_t, int rank) {
+            if (rank < k) winners[rank] = (uint32_t)c;
+            by_rank[rank] = w_apx[c];
+        });
         __syncthreads();
         TRACE2(8);
+        float corr = 0.f;
+        for (int q = 0; q < n_work; ++q) corr += by_rank[q];
+        const float s_fixed = S + corr;
+        const float lse_fixed = (s_fixed > 0.f) ? (Mx + __builtin_amdgcn_logf(s_fixed)) * kLn2 : lse;
         if (tid < k) {
             const uint32_t c = winners[tid];
             out_ids[(size_t)row * k + tid] = w_id[c];
-            out_logprobs[(size_t)row * k + tid] = w_val[c] - lse;
+            out_logprobs[(size_t)row * k + tid] = w_val[c] - lse_fixed;
         }
         return;
     }
@@ -381,20 +403,20 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
 size_t merge_streams_lds_bytes(int nsr, int k) {
     const size_t n = (size_t)nsr * kStreamList;
     const size_t ngroups = (n + 63) / 64;
-    return sizeof(uint64_t) * (ngroups * 64 + ngroups * k + kWorkCap) + 12u * kWorkCap;
+    return sizeof(uint64_t) * (ngroups * 64 + ngroups * k + kWorkCap) + 16u * kWorkCap;
 }
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                int32_t *out_ids, float *out_logprobs, hipStream_t st)
+                                bool contiguous_tiles, int32_t *out_ids, float *out_logprobs, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_wv, tv, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, brms, k, out_ids, out_logprobs);
+                                                           M, K, V, stat, n_stat, rows_pad, brms, k, contiguous_tiles ? 1 : 0, out_ids, out_logprobs);
     return hipGetLastError();
 }
 

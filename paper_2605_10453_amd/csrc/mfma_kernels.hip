@@ -17,14 +17,10 @@
 // still belong to the top-k and re-evaluates those in fp32.
 #include "mfma_core.hpp"
 #include "launch.hpp"
+#include "head_stream.hpp"
 #include <type_traits>
 
 namespace slimspec {
-
-// plain VALU min / max / median without the canonicalising pre-ops the compiler adds for fmaxf
-__device__ __forceinline__ float vmax(float a, float b) { float d; asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b)); return d; }
-__device__ __forceinline__ float vmin(float a, float b) { float d; asm("v_min_f32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b)); return d; }
-__device__ __forceinline__ float vmed3(float a, float b, float c) { float d; asm("v_med3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c)); return d; }
 
 // ---------------------------------------------------------------------------
 // t = h A, slice z of the contraction.  grid = (ceil(r / 256), row blocks, slices).
@@ -94,7 +90,7 @@ constexpr int kBrmsPositions = 4;
 __global__ __launch_bounds__(256) void down_finish_kernel(
     const float *__restrict__ part, int slices, int rows, int rows_pad, int r,
     float *__restrict__ t32, uint4 *__restrict__ t16, float2 *__restrict__ stat,
-    const uint16_t *__restrict__ B, int V, float *__restrict__ brms)
+    const uint16_t *__restrict__ B, int V, float *__restrict__ brms, int as_bf16)
 {
     __shared__ float red_a[4][64], red_b[4][64];
     const int tid = threadIdx.x, lane = tid & 63, kgl = tid >> 6;
@@ -135,15 +131,29 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
         float4 *o = reinterpret_cast<float4 *>(t32 + (size_t)row * r + kg * 8);
         o[0] = make_float4(v[0], v[1], v[2], v[3]);
         o[1] = make_float4(v[4], v[5], v[6], v[7]);
-        f16x8 hv;
+        if (as_bf16) {
+            uint32_t hb[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            hv[e] = (_Float16)v[e];
-            const float dlt = v[e] - (float)hv[e];
-            a += dlt * dlt;
-            b += v[e] * v[e];
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t u = __float_as_uint(v[e]);
+                hb[e] = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;            // round to nearest even
+                const float dlt = v[e] - __uint_as_float(hb[e] << 16);
+                a += dlt * dlt;
+                b += v[e] * v[e];
+            }
+            t16[(size_t)kg * rows_pad + row] = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16),
+                                                          hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
+        } else {
+            f16x8 hv;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                hv[e] = (_Float16)v[e];
+                const float dlt = v[e] - (float)hv[e];
+                a += dlt * dlt;
+                b += v[e] * v[e];
+            }
+            t16[(size_t)kg * rows_pad + row] = __builtin_bit_cast(uint4, hv);
         }
-        t16[(size_t)kg * rows_pad + row] = __builtin_bit_cast(uint4, hv);
     } else {
         t16[(size_t)kg * rows_pad + row] = make_uint4(0, 0, 0, 0);     // zero padding of k up to a multiple of 64
     }
@@ -155,71 +165,6 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
             make_float2(((red_a[0][lane] + red_a[1][lane]) + red_a[2][lane]) + red_a[3][lane],
                         ((red_b[0][lane] + red_b[1][lane]) + red_b[2][lane]) + red_b[3][lane]);
 }
-
-// ---------------------------------------------------------------------------
-// Per-lane stream of one row.
-template <int L>
-struct Stream {
-    float mc, s, U;          // running max (times log2 e), sum of exp relative to it, best dropped group maximum
-    float x[L], y[L];        // group maxima (low 4 bits = position in the group) and second largest values
-    int tag[L];              // group name: vocabulary tile * 8 + MFMA tile
-};
-
-constexpr float kNegBig = -3.0e38f;     // stands for "no value" (finite, so that tagging its low bits stays a number)
-
-template <int L>
-__device__ __forceinline__ void stream_init(Stream<L> &st) {
-    st.mc = kNegBig; st.s = 0.f; st.U = kNegBig;
-#pragma unroll
-    for (int l = 0; l < L; ++l) { st.x[l] = kNegBig; st.y[l] = kNegBig; st.tag[l] = 0; }
-}
-
-// Fold one group (16 logits of one row) into the stream.
-template <int L>
-__device__ __forceinline__ void stream_group(Stream<L> &st, const float (&v)[16], int tag)
-{
-    float p[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) p[i] = __uint_as_float((__float_as_uint(v[i]) & 0xfffffff0u) | (uint32_t)i);
-    // largest and second largest of the 16 tagged values
-    float a[8], b[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) { a[q] = vmax(p[2 * q], p[2 * q + 1]); b[q] = vmin(p[2 * q], p[2 * q + 1]); }
-#pragma unroll
-    for (int w = 4; w >= 1; w >>= 1)
-#pragma unroll
-        for (int q = 0; q < w; ++q) {
-            float hi = vmax(a[2 * q], a[2 * q + 1]);
-            float lo = vmed3(a[2 * q], a[2 * q + 1], vmax(b[2 * q], b[2 * q + 1]));
-            a[q] = hi; b[q] = lo;
-        }
-    float gm = a[0], g2 = b[0];
-
-    // running log-sum-exp (base 2 inside)
-    const float mc_new = vmax(st.mc, gm * kLog2e);
-    float sum = st.s * __builtin_amdgcn_exp2f(st.mc - mc_new);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(v[i], kLog2e, -mc_new));
-    st.s = sum;
-    st.mc = mc_new;
-
-    // keep the L groups with the largest maxima
-    int tg = tag;
-#pragma unroll
-    for (int l = 0; l < L; ++l) {
-        const bool c = gm > st.x[l];
-        const float nx = c ? gm : st.x[l], ny = c ? g2 : st.y[l];
-        const int nt = c ? tg : st.tag[l];
-        gm = c ? st.x[l] : gm; g2 = c ? st.y[l] : g2; tg = c ? st.tag[l] : tg;
-        st.x[l] = nx; st.y[l] = ny; st.tag[l] = nt;
-    }
-    st.U = vmax(st.U, gm);
-}
-
-// Work of block g: row block rb and the vocabulary tiles col, col + gw, col + 2 gw, ...
-// Blocks are dealt round-robin to the 8 XCDs, so blocks g and g + 8 share an L2: they get the same
-// vocabulary tiles and different row blocks, and so read each tile of M from HBM once.
-struct HeadGrid { int n_rb, gw, n_vt; };
 
 template <class C, bool F16, bool XROW, int L>
 __global__ __launch_bounds__(C::THREADS, 1) void head_mfma_kernel(
@@ -353,11 +298,11 @@ hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, i
 
 hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_pad, int r,
                               float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
-                              hipStream_t st)
+                              bool as_bf16, hipStream_t st)
 {
     dim3 grid(rows_pad / 64 + 1, 2 * ((r + 63) / 64));
     down_finish_kernel<<<grid, 256, 0, st>>>(part, slices, rows, rows_pad, r, t32,
-                                             static_cast<uint4 *>(t16), stat, B, V, brms);
+                                             static_cast<uint4 *>(t16), stat, B, V, brms, as_bf16 ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -70,10 +70,12 @@ constexpr int kStreamListPlan = 3;       // must equal kStreamList (launch.hpp)
 constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
 
 int mfma_rows_per_tile(int rows);
+bool head_tile_enabled();
 int mfma_streams_per_block(int rows);
 
 struct MfmaPlan {
     int rows = 0, rows_pad = 0, rt = 0, n_rb = 0, gw = 0, nsr = 0, n_vt = 0;
+    bool tile = false;                   // direct-to-LDS kernel: 128-row tiles, two blocks per CU
     int slices = 0, kslice = 0;          // down-projection split of d
     size_t off_down_part = 0;            // fp32 [slices, r, rows_pad]
     size_t off_t32 = 0;                  // fp32 [rows_pad, r]
@@ -88,16 +90,17 @@ struct MfmaPlan {
 inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
     MfmaPlan p;
     p.rows = rows;
-    p.rt = mfma_rows_per_tile(rows);
+    p.tile = head_tile_enabled() && kind == HeadKind::LowRank;
+    p.rt = p.tile ? 128 : mfma_rows_per_tile(rows);
     p.n_rb = (rows + p.rt - 1) / p.rt;
     p.rows_pad = p.n_rb * p.rt;
     p.n_vt = (V + 255) / 256;
-    int colgroups = kPlanSlotsPerXcd / p.n_rb;
+    int colgroups = (p.tile ? 2 : 1) * kPlanSlotsPerXcd / p.n_rb;
     if (colgroups < 1) colgroups = 1;
     const int need = (p.n_vt + 7) / 8;
     if (colgroups > need) colgroups = need;
     p.gw = 8 * colgroups;
-    p.nsr = p.gw * mfma_streams_per_block(rows);
+    p.nsr = p.gw * (p.tile ? 4 : mfma_streams_per_block(rows));
     size_t off = 0;
     if (kind == HeadKind::LowRank) {
         const int tiles = ((r + 255) / 256) * ((rows + 63) / 64);
@@ -116,7 +119,7 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
     p.bytes = off;
     return p;
 }
-inline int mfma_max_rows_per_launch(int rows) { return kPlanSlotsPerXcd * mfma_rows_per_tile(rows); }
+inline int mfma_max_rows_per_launch(int rows) { return kPlanSlotsPerXcd * mfma_rows_per_tile(rows); }   // <= 32 * 128 = 64 * 64
 size_t merge_streams_lds_bytes(int nsr, int k);
 
 }  // namespace slimspec

@@ -77,14 +77,15 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             float *brms = reinterpret_cast<float *>(ws + p.off_brms);
             e = launch_down_gemm(hrow, static_cast<const uint16_t *>(A), down_part, rows, p.rows_pad, d, r, p.slices, p.kslice, s);
             if (e != hipSuccess) return fail_hip(e);
-            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, s);
+            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, p.tile, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-            e = launch_head_mfma(static_cast<const uint16_t *>(t16), false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
+            if (p.tile) e = launch_head_tile(t16, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
+            else e = launch_head_mfma(static_cast<const uint16_t *>(t16), false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
-                                     out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.tile ? 2 : n_wv, p.tile ? 4 : tv, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
+                                     p.tile, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
@@ -92,7 +93,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
-                                     out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+                                     false, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         }
     }
@@ -172,6 +173,13 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
 }
 
 }  // namespace
+
+namespace slimspec {
+bool head_tile_enabled() {
+    static const bool on = getenv("SLIMSPEC_HEAD_TILE") != nullptr;
+    return on;
+}
+}  // namespace slimspec
 
 extern "C" {
 
