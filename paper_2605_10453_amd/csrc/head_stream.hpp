@@ -71,6 +71,52 @@ __device__ __forceinline__ void stream_group(Stream<L> &st, const float (&v)[16]
     st.U = vmax(st.U, gm);
 }
 
+__device__ __forceinline__ float vmax3(float a, float b, float c) { float d; asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c)); return d; }
+
+// Largest and second largest of 16 values in 20 instructions: five triples (max3 / med3), then
+// "top two of three pairs" = (max3 of the maxima, max(med3 of the maxima, the seconds)).
+__device__ __forceinline__ void top2_of_16(const float (&p)[16], float &hi, float &lo) {
+    float h[5], l[5];
+#pragma unroll
+    for (int t = 0; t < 5; ++t) { h[t] = vmax3(p[3 * t], p[3 * t + 1], p[3 * t + 2]); l[t] = vmed3(p[3 * t], p[3 * t + 1], p[3 * t + 2]); }
+    const float ha = vmax3(h[0], h[1], h[2]);
+    const float la = vmax(vmax3(vmed3(h[0], h[1], h[2]), l[0], l[1]), l[2]);
+    const float hb = vmax3(h[3], h[4], p[15]);
+    const float lb = vmax3(vmed3(h[3], h[4], p[15]), l[3], l[4]);
+    hi = vmax(ha, hb);
+    lo = vmed3(ha, hb, vmax(la, lb));
+}
+
+// Fold one group into the stream when the 16 values are base-2 logits RELATIVE to `ref` (the accumulators
+// were started at -ref): the sum of 2^v needs no subtraction; the group's top two go back to absolute
+// values for the list.  The caller rescales st.s and moves st.mc once per tile (see tile_max).
+template <int L>
+__device__ __forceinline__ void stream_group_rel(Stream<L> &st, const float (&v)[16], float ref, float &tile_max, int tag)
+{
+    float p[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) p[i] = __uint_as_float((__float_as_uint(v[i]) & 0xfffffff0u) | (uint32_t)i);
+    float gr, g2r;
+    top2_of_16(p, gr, g2r);
+    float sum = st.s;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(v[i]);
+    st.s = sum;
+    float gm = __uint_as_float((__float_as_uint(gr + ref) & 0xfffffff0u) | (__float_as_uint(gr) & 15u));
+    float g2 = g2r + ref;
+    tile_max = vmax(tile_max, gm);
+    int tg = tag;
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        const bool c = gm > st.x[l];
+        const float nx = c ? gm : st.x[l], ny = c ? g2 : st.y[l];
+        const int nt = c ? tg : st.tag[l];
+        gm = c ? st.x[l] : gm; g2 = c ? st.y[l] : g2; tg = c ? st.tag[l] : tg;
+        st.x[l] = nx; st.y[l] = ny; st.tag[l] = nt;
+    }
+    st.U = vmax(st.U, gm);
+}
+
 // Work of block g: row block rb and the vocabulary tiles col, col + gw, col + 2 gw, ...
 // Blocks are dealt round-robin to the 8 XCDs, so blocks g and g + 8 share an L2: they get the same
 // vocabulary tiles and different row blocks, and so read each tile of M from HBM once.

@@ -56,6 +56,6 @@ hipError_t launch_head_tile(const void *X, const uint16_t *M, float *part, int r
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                bool contiguous_tiles, int32_t *out_ids, float *out_logprobs, hipStream_t st);
+                                bool contiguous_tiles, float unit, int32_t *out_ids, float *out_logprobs, hipStream_t st);
 
 }  // namespace slimspec

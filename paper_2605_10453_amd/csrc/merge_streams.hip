@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ brms,
-    int k, int contig, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+    int k, int contig, float unit, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
 #pragma unroll
         for (int l = 0; l < L; ++l) {
             const float x = f[3 + 3 * l];
-            keys[sidx * L + l] = (x > kNoValue) ? make_key(mask4(x), (uint32_t)(sidx * L + l)) : kNoKey;
+            keys[sidx * L + l] = (x > kNoValue) ? make_key(mask4(x) * unit, (uint32_t)(sidx * L + l)) : kNoKey;
         }
     }
     for (int e = n + tid; e < ngroups * 64; e += NT) keys[e] = kNoKey;
@@ -228,10 +228,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 const float x = r[3 + 3 * l], y = r[4 + 3 * l];
                 const int tag = __float_as_int(r[5 + 3 * l]);
                 listed[l] = (x > kNoValue) ? tag : -1;
-                if (!(x > kNoValue) || !(mask4(x) >= theta)) continue;
+                if (!(x > kNoValue) || !(mask4(x) * unit >= theta)) continue;
                 const int imax = (int)(__float_as_uint(x) & 15u);
-                push(id_of(tag, imax, half), mask4(x), 0);
-                if (y > kNoValue && mask4(y) >= theta) {
+                push(id_of(tag, imax, half), mask4(x) * unit, 0);
+                if (y > kNoValue && mask4(y) * unit >= theta) {
                     for (int i = 0; i < 16; ++i) {
                         const int id = id_of(tag, i, half);
                         if (i != imax && id < V) push(id, 0.f, 1);
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 }
             }
             const float U = r[2];
-            if (U > kNoValue && mask4(U) >= theta) {
+            if (U > kNoValue && mask4(U) * unit >= theta) {
                 const int wv = (sidx >> 1) % n_wv, col = (sidx >> 1) / n_wv;
                 for (int vt = col; vt < n_vt; vt += gw)
                     for (int j = wv * tv; j < wv * tv + tv; ++j) {
@@ -409,14 +409,14 @@ size_t merge_streams_lds_bytes(int nsr, int k) {
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                bool contiguous_tiles, int32_t *out_ids, float *out_logprobs, hipStream_t st)
+                                bool contiguous_tiles, float unit, int32_t *out_ids, float *out_logprobs, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_wv, tv, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, brms, k, contiguous_tiles ? 1 : 0, out_ids, out_logprobs);
+                                                           M, K, V, stat, n_stat, rows_pad, brms, k, contiguous_tiles ? 1 : 0, unit, out_ids, out_logprobs);
     return hipGetLastError();
 }
 

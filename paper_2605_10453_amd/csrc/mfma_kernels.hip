@@ -135,9 +135,10 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
             uint32_t hb[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t u = __float_as_uint(v[e]);
+                // the direct-to-LDS head kernel works in base-2 units: it takes t log2(e)
+                const uint32_t u = __float_as_uint(v[e] * kLog2e);
                 hb[e] = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;            // round to nearest even
-                const float dlt = v[e] - __uint_as_float(hb[e] << 16);
+                const float dlt = v[e] - __uint_as_float(hb[e] << 16) * kLn2;
                 a += dlt * dlt;
                 b += v[e] * v[e];
             }

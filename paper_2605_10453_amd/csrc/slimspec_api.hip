@@ -85,7 +85,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.tile ? 2 : n_wv, p.tile ? 4 : tv, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
-                                     p.tile, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+                                     p.tile, p.tile ? 0.6931471805599453f : 1.0f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
@@ -93,7 +93,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
-                                     false, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+                                     false, 1.0f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         }
     }
