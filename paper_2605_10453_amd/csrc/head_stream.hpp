@@ -98,6 +98,7 @@ __device__ __forceinline__ void stream_group_rel(Stream<L> &st, const float (&v)
     for (int i = 0; i < 16; ++i) p[i] = __uint_as_float((__float_as_uint(v[i]) & 0xfffffff0u) | (uint32_t)i);
     float gr, g2r;
     top2_of_16(p, gr, g2r);
+    __builtin_amdgcn_sched_barrier(0);          // the tagged copies are dead before the exponentials start
     float sum = st.s;
 #pragma unroll
     for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(v[i]);
@@ -115,6 +116,31 @@ __device__ __forceinline__ void stream_group_rel(Stream<L> &st, const float (&v)
         st.x[l] = nx; st.y[l] = ny; st.tag[l] = nt;
     }
     st.U = vmax(st.U, gm);
+}
+
+// Fold stream b into stream a (both cover different logits of the same row): log-sum-exp in base 2, the L
+// largest group maxima of the union, U = the largest maximum that is not listed.
+template <int L>
+__device__ __forceinline__ void stream_combine(Stream<L> &a, const Stream<L> &b)
+{
+    const float m = fmaxf(a.mc, b.mc);
+    a.s = a.s * __builtin_amdgcn_exp2f(a.mc - m) + b.s * __builtin_amdgcn_exp2f(b.mc - m);
+    a.mc = m;
+    a.U = fmaxf(a.U, b.U);
+#pragma unroll
+    for (int e = 0; e < L; ++e) {
+        float gm = b.x[e], g2 = b.y[e];
+        int tg = b.tag[e];
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            const bool c = gm > a.x[l];
+            const float nx = c ? gm : a.x[l], ny = c ? g2 : a.y[l];
+            const int nt = c ? tg : a.tag[l];
+            gm = c ? a.x[l] : gm; g2 = c ? a.y[l] : g2; tg = c ? a.tag[l] : tg;
+            a.x[l] = nx; a.y[l] = ny; a.tag[l] = nt;
+        }
+        a.U = fmaxf(a.U, gm);
+    }
 }
 
 // Work of block g: row block rb and the vocabulary tiles col, col + gw, col + 2 gw, ...

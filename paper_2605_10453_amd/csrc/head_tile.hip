@@ -2,26 +2,30 @@
 // (paper section 4.1: logits = t B, never written to memory), for calls with many rows.
 //
 // Shape of the kernel
-//   * One block = 4 wavefronts = a 128-row x 256-column tile of logits; two blocks share a CU (two
-//     wavefronts per SIMD, from different blocks and therefore at different phases: one block's
-//     epilogue overlaps the other block's matrix instructions).  A wavefront owns 64 rows x 128
-//     columns = 2 x 4 MFMA tiles of 32 x 32 (v_mfma_f32_32x32x16_bf16, accumulators in VGPRs).
+//   * A wavefront owns 64 rows x 128 columns of logits = 2 x 4 MFMA tiles of 32 x 32
+//     (v_mfma_f32_32x32x16_bf16, accumulators in VGPRs), two wavefronts per SIMD.
+//     WR = 4: one block of 8 wavefronts = 256 rows x 256 columns per CU (least traffic per MFMA);
+//     WR = 2: blocks of 4 wavefronts = 128 rows x 256 columns, two per CU (calls with few rows).
 //   * The transposed product z^T = M^T x^T is computed, so that the 16 values an MFMA tile gives a
 //     lane belong to ONE row: running max, sum of exp and candidate bookkeeping stay inside the lane.
 //   * Stages of 32 contraction elements travel global memory -> LDS without passing registers
 //     (global_load_lds_dwordx4): the M tile row-major as it lies in memory, the X tile as 16-byte
-//     vectors of 8 consecutive contraction elements.  Three stage buffers; loads are issued two
-//     stages ahead.  MFMA operands come from LDS with ds_read_b64_tr_b16 (M: transposes the
-//     row-major tile into 4 consecutive contraction elements per lane) and ds_read_b128 (X).
+//     vectors of 8 consecutive contraction elements.  NBUF stage buffers; loads are issued
+//     NBUF - 1 stages ahead.  MFMA operands come from LDS with ds_read_b64_tr_b16 (M: transposes
+//     the row-major tile into 4 consecutive contraction elements per lane) and ds_read_b128 (X).
 //   * 16-byte pieces of an M row are stored XOR-swizzled by (k mod 4) so that the four rows a
 //     transposing read touches fall into different banks.
+//   * X arrives multiplied by log2(e) and the accumulators of a tile start at minus the row's
+//     running maximum, so that the epilogue's 2^v needs no multiply or subtract.
 //
 // Waits: the compiler does not see the direct-to-LDS loads (inline asm), so the kernel counts them
-// itself: every wavefront issues exactly 6 per stage, vector memory returns in order, hence
-// s_waitcnt vmcnt(6) = "everything but the stage issued last has landed".  No other vector memory
-// instruction may sit inside the main loop (the kernel must not spill).
+// itself: every wavefront issues exactly LPS per stage, vector memory returns in order, hence
+// s_waitcnt vmcnt((NBUF - 2) LPS) = "the stage needed next has landed".  No other vector memory
+// instruction may sit inside the main loop: the kernel must not spill.
 #include "head_stream.hpp"
 #include "launch.hpp"
+#include <cstdlib>
+#include <type_traits>
 
 namespace slimspec {
 
@@ -29,15 +33,22 @@ namespace {
 
 constexpr int kTKB = 32;                                   // contraction elements per stage
 constexpr int kTNT = 256;                                  // vocabulary columns per tile
-constexpr int kTRT = 128;                                  // rows per block
-constexpr int kTStages = 3;
-constexpr int kTMBytes = kTKB * kTNT * 2;                  // 16 KB
-constexpr int kTXBytes = (kTKB / 8) * kTRT * 16;           //  8 KB
-constexpr int kTStageBytes = kTMBytes + kTXBytes;
-constexpr int kTLdsBytes = kTStages * kTStageBytes;        // 72 KB: two blocks per CU
+constexpr int kTMBytes = kTKB * kTNT * 2;                  // 16 KB of M per stage
+
+template <int WR>
+struct TileShape {
+    static constexpr int NW = 2 * WR;                      // wavefronts per block
+    static constexpr int RT = 64 * WR;                     // rows per block
+    static constexpr int XBYTES = (kTKB / 8) * RT * 16;
+    static constexpr int STAGE = kTMBytes + XBYTES;
+    static constexpr int NBUF = WR == 4 ? 4 : 3;
+    static constexpr int LDS = NBUF * STAGE;               // WR 4: 128 KB (one block per CU); WR 2: 72 KB (two)
+    static constexpr int MPW = 16 / NW;                    // M loads per wavefront and stage (2 rows each)
+    static constexpr int LPS = MPW + 2;                    // loads per wavefront and stage
+    static constexpr int WAIT = (NBUF - 2) * LPS;
+};
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
-typedef short v8i16 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -49,18 +60,28 @@ __device__ __forceinline__ void dma16(uint32_t buf, uint32_t voff, const void *b
     asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(buf), "v"(voff), "s"(base), "n"(OFF) : "memory", "scc");
 }
+// the lane number, recomputed wherever it is used (volatile: not hoisted into a long-lived register)
+__device__ __forceinline__ uint32_t lane_id_now() {
+    uint32_t l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 }  // namespace
 
 // X: [8 ceil(K / 64)][rows_pad] 16-byte vectors: 8 consecutive contraction elements of one row, bf16, times
-//    log2(e), zero beyond K
+//    log2(e), zero beyond K; rows_pad a multiple of 64 WR
 // M: [K][V] bf16 row-major, V and K multiples of 8
-// part: [rows][nsr][3 + 3 L] stream records (values in base-2 units), nsr = 4 gw
-template <int L>
-__global__ __launch_bounds__(256, 2) void head_tile_kernel(
+// part: [rows][gw][3 + 3 L] stream records (values in base-2 units): one per row and block
+// DBG != 0: timing experiments (1 no epilogue, 2 loads only, 3 no loads); results are meaningless
+template <int L, int WR, int DBG>
+__global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
     const uint4 *__restrict__ X, const uint16_t *__restrict__ M, float *__restrict__ part,
     int rows, int rows_pad, int K, int V, HeadGrid hg)
 {
+    using S = TileShape<WR>;
     extern __shared__ __align__(1024) unsigned char lds_raw[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)lds_raw);
     const int tid = threadIdx.x, lane = tid & 63;
@@ -69,53 +90,63 @@ __global__ __launch_bounds__(256, 2) void head_tile_kernel(
     const int half = lane >> 5, l32 = lane & 31, g1 = (lane >> 4) & 1, j16 = lane & 15;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int rb = slot % hg.n_rb, col = (slot / hg.n_rb) * 8 + xcd;
-    const int row0 = rb * kTRT;
+    const int row0 = rb * S::RT;
     const int nkb = (K + kTKB - 1) / kTKB;
     const int njobs = (col < hg.n_vt) ? (hg.n_vt - col + hg.gw - 1) / hg.gw : 0;
     const int total = njobs * nkb;
     const bool ktail = (K & (kTKB - 1)) != 0;
 
-    // ---- direct-to-LDS loads of one stage: 4 of M, 2 of X per wavefront.
-    // M load uu of this wavefront covers stage rows 8 wave + 2 uu + (lane >> 5); lane -> stored piece lane & 31,
-    // which holds source piece (lane & 31) ^ ((row & 3) << 2).
-    const uint32_t kp = lane >> 5, pp = lane & 31;
-    const uint32_t mcol_e = (pp ^ (kp << 2)) * 16u;            // source byte column when (row & 3) = kp
-    const uint32_t mcol_o = (pp ^ ((2u + kp) << 2)) * 16u;     // ... when (row & 3) = 2 + kp
+    // ---- direct-to-LDS loads of one stage.
+    // M load uu of this wavefront covers stage rows 2 MPW wave + 2 uu + (lane >> 5); lane -> stored piece
+    // lane & 31, which holds source piece (lane & 31) ^ ((row & 3) << 2).
     const uint32_t rowb = (uint32_t)V * 2u;                    // bytes per row of M
     uint32_t mv[2];                                            // lane offsets from the row pair's first row (even / odd pair)
     const auto set_tile = [&](int vt) {
+        // once per tile: recomputed from the lane number rather than kept in registers through the main loop
+        const uint32_t ln = lane_id_now();
+        const uint32_t kp = ln >> 5, pp = ln & 31;
+        const uint32_t mcol_e = (pp ^ (kp << 2)) * 16u;        // source byte column when (row & 3) = kp
+        const uint32_t mcol_o = (pp ^ ((2u + kp) << 2)) * 16u; // ... when (row & 3) = 2 + kp
         const uint32_t climit = (uint32_t)(V - vt * kTNT - 8) * 2u;      // last 16-byte piece of the row that exists
-        const uint32_t ce = min(mcol_e, climit), co = min(mcol_o, climit);
-        mv[0] = kp * rowb + ce;
-        mv[1] = (kp + 2u) * rowb + co;
+        mv[0] = kp * rowb + min(mcol_e, climit);
+        mv[1] = (kp + 2u) * rowb + min(mcol_o, climit);
     };
     const uint32_t xv0 = (uint32_t)lane * 16u;
-    const unsigned char *const m_wave = reinterpret_cast<const unsigned char *>(M) + (size_t)(8 * wave) * rowb;
-    const unsigned char *const x_wave = reinterpret_cast<const unsigned char *>(X + (size_t)wave * rows_pad + row0);
+    constexpr int RPW = 2 * S::MPW;                            // stage rows of M per wavefront
+    const int xi = 2 * wave;                                   // X loads xi, xi + 1: k-group xi / WR, rows 64 (xi % WR) ...
+    const unsigned char *const m_wave = reinterpret_cast<const unsigned char *>(M) + (size_t)(RPW * wave) * rowb;
+    const unsigned char *const x_wave =
+        reinterpret_cast<const unsigned char *>(X + (size_t)(xi / WR) * rows_pad + row0 + 64 * (xi % WR));
     const size_t m_step = (size_t)kTKB * rowb, x_step = (size_t)4 * rows_pad * 16;
+    const uint32_t m_lds = (uint32_t)(wave * RPW * 512);
+    const uint32_t x_lds = (uint32_t)(kTMBytes + ((xi / WR) * S::RT + 64 * (xi % WR)) * 16);
 
     // position of the stage whose loads are issued next
     int a_vt = col, a_kb = 0;
     const unsigned char *mptr = m_wave + (size_t)col * kTNT * 2, *xptr = x_wave;
     const auto issue_stage = [&](uint32_t buf) {
+        const uint32_t mb = buf + m_lds;
         if (ktail && a_kb == nkb - 1) {
-            // last, partial k-block: rows beyond K are read from row K - 2 / K - 1 (they meet zeros of X)
-            const uint32_t ce = mv[0] - kp * rowb, co = mv[1] - (kp + 2u) * rowb;
+            // last, partial k-block: rows beyond K are read from rows K - 2, K - 1 (they meet zeros of X)
+            const uint32_t ce = mv[0], co = mv[1] - 2u * rowb;
             const unsigned char *tile0 = reinterpret_cast<const unsigned char *>(M) + (size_t)a_vt * kTNT * 2;
-#define SLIMSPEC_TAIL_LOAD(UU)                                                                            \
-            { const int krow = min(a_kb * kTKB + 8 * wave + 2 * UU, K - 2);                                 \
-              dma16<(UU) * 1024>(buf + (uint32_t)(wave * 4096), kp * rowb + ((UU & 1) ? co : ce), tile0 + (size_t)krow * rowb); }
-            SLIMSPEC_TAIL_LOAD(0) SLIMSPEC_TAIL_LOAD(1) SLIMSPEC_TAIL_LOAD(2) SLIMSPEC_TAIL_LOAD(3)
-#undef SLIMSPEC_TAIL_LOAD
+            const int k0 = a_kb * kTKB + RPW * wave;
+            dma16<0>(mb, ce, tile0 + (size_t)min(k0, K - 2) * rowb);
+            dma16<1024>(mb, co, tile0 + (size_t)min(k0 + 2, K - 2) * rowb);
+            if (S::MPW == 4) {
+                dma16<2048>(mb, ce, tile0 + (size_t)min(k0 + 4, K - 2) * rowb);
+                dma16<3072>(mb, co, tile0 + (size_t)min(k0 + 6, K - 2) * rowb);
+            }
         } else {
-            const uint32_t mb = buf + (uint32_t)(wave * 4096);
-            const unsigned char *mptr4 = mptr + 4 * (size_t)rowb;
             dma16<0>(mb, mv[0], mptr);
             dma16<1024>(mb, mv[1], mptr);
-            dma16<2048>(mb, mv[0], mptr4);
-            dma16<3072>(mb, mv[1], mptr4);
+            if (S::MPW == 4) {
+                const unsigned char *mptr4 = mptr + 4 * (size_t)rowb;
+                dma16<2048>(mb, mv[0], mptr4);
+                dma16<3072>(mb, mv[1], mptr4);
+            }
         }
-        const uint32_t xb = buf + (uint32_t)(kTMBytes + wave * kTRT * 16);
+        const uint32_t xb = buf + x_lds;
         dma16<0>(xb, xv0, xptr);
         dma16<1024>(xb, xv0, xptr + 1024);
     };
@@ -128,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void head_tile_kernel(
     };
 
     // ---- operand addresses inside a stage
-    const uint32_t xa = (uint32_t)(kTMBytes + (half * kTRT + wr * 64 + l32) * 16);
+    const uint32_t xa = (uint32_t)(kTMBytes + (half * S::RT + wr * 64 + l32) * 16);
     // M fragment of MFMA tile jj: ma0 ^ (jj << 6) (the swizzle exchanges 64-byte groups; stage buffers are 1 KB aligned)
     const uint32_t ma0 = (uint32_t)((8 * half + (j16 >> 2)) * 512
                                     + (wv * 16 + 4 * (j16 >> 2) + 2 * g1 + ((j16 & 3) >> 1)) * 16 + (j16 & 1) * 8);
@@ -144,44 +175,73 @@ __global__ __launch_bounds__(256, 2) void head_tile_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[rt][jj][i] = 0.f;
 
+    const long long dbg_t0 = DBG ? clock64() : 0, dbg_w0 = DBG ? wall_clock64() : 0;
     if (total > 0) {
         int c_vt = col, c_kb = 0;                                         // stage being multiplied
         uint32_t buf_cur = lds0, buf_ahead = lds0;
-        const auto next_buf = [&](uint32_t b) { return (b + kTStageBytes == lds0 + kTLdsBytes) ? lds0 : b + kTStageBytes; };
+        const auto next_buf = [&](uint32_t b) { return (b + S::STAGE == lds0 + S::LDS) ? lds0 : b + S::STAGE; };
         set_tile(col);
         issue_stage(buf_ahead);                                           // stage 0
-        if (total > 1) advance_ahead();
-        buf_ahead = next_buf(buf_ahead);
-        issue_stage(buf_ahead);                                           // stage 1 (or stage 0 once more)
-        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-
-        for (int q = 0; q < total; ++q) {
-            if (q + 2 < total) advance_ahead();                           // past the end: the last stage once more
+#pragma unroll
+        for (int pre = 1; pre < S::NBUF - 1; ++pre) {                     // stages 1 .. NBUF - 2 (past the end: the last stage once more)
+            if (pre < total) advance_ahead();
             buf_ahead = next_buf(buf_ahead);
             issue_stage(buf_ahead);
+        }
+        wait_loads<S::WAIT>();
+        __builtin_amdgcn_s_barrier();
 
+        // Operand reads run one k-step (8 MFMAs) ahead of their use, also across stages: the barrier that
+        // publishes the next stage sits between the two k-steps of the current one.
+        bf16x8 xf[2][2], mf[2][4];                                        // [k-step][tile]
+        const auto read_operands = [&](uint32_t buf, auto ks_tag) {
+            constexpr int ks = decltype(ks_tag)::value;
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                bf16x8 xf[2], mf[4];
+            for (int rt = 0; rt < 2; ++rt)
+                xf[ks][rt] = __builtin_bit_cast(bf16x8, *LDS_PTR(u32x4, buf + xa + ks * (2 * S::RT * 16) + rt * 512));
 #pragma unroll
-                for (int rt = 0; rt < 2; ++rt)
-                    xf[rt] = __builtin_bit_cast(bf16x8, *LDS_PTR(u32x4, buf_cur + xa + ks * 4096 + rt * 512));
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const uint32_t mj = (buf_cur + ma0) ^ (uint32_t)(jj << 6);
-                    const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4i16, mj + ks * 8192));
-                    const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4i16, mj + ks * 8192 + 2048));
-                    mf[jj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                }
-#pragma unroll
-                for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-                        acc[rt][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mf[jj], xf[rt], acc[rt][jj], 0, 0, 0);
+            for (int jj = 0; jj < 4; ++jj) {
+                const uint32_t mj = (buf + ma0) ^ (uint32_t)(jj << 6);
+                const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4i16, mj + ks * 8192));
+                const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4i16, mj + ks * 8192 + 2048));
+                mf[ks][jj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
+        };
+        const auto multiply = [&](auto ks_tag) {
+            constexpr int ks = decltype(ks_tag)::value;
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    acc[rt][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mf[ks][jj], xf[ks][rt], acc[rt][jj], 0, 0, 0);
+        };
+        using KS0 = std::integral_constant<int, 0>;
+        using KS1 = std::integral_constant<int, 1>;
+        if (DBG != 2) read_operands(buf_cur, KS0{});
 
-            if (c_kb == nkb - 1) {
+        for (int q = 0; q < total; ++q) {
+            const bool last_kb = c_kb == nkb - 1;
+            const uint32_t buf_next = next_buf(buf_cur);
+            if (DBG != 2) read_operands(buf_cur, KS1{});
+            if (q + S::NBUF - 1 < total) advance_ahead();
+            buf_ahead = next_buf(buf_ahead);
+            if (DBG != 3) issue_stage(buf_ahead);
+            if (DBG != 2) multiply(KS0{});
+            // every read of this stage has returned (its buffer is reloaded after the barrier); the next stage has landed
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            wait_loads<S::WAIT>();
+            __builtin_amdgcn_s_barrier();
+            if (DBG != 2 && !last_kb && q + 1 < total) read_operands(buf_next, KS0{});
+            if (DBG != 2) multiply(KS1{});
+            __builtin_amdgcn_sched_barrier(0);
+
+            if (DBG != 0 && last_kb) {
+#pragma unroll
+                for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) { st[rt].s += acc[rt][jj][0] + acc[rt][jj][7]; acc[rt][jj][0] = 0.f; }
+            }
+            if (DBG == 0 && last_kb) {
                 // The accumulators hold base-2 logits minus the row's reference (its running maximum when the
                 // tile began; the first tile finds its own maximum first).
                 const int n0 = c_vt * kTNT;
@@ -192,7 +252,7 @@ __global__ __launch_bounds__(256, 2) void head_tile_kernel(
                     if (tail) {
 #pragma unroll
                         for (int jj = 0; jj < 4; ++jj) {
-                            const int cbase = n0 + 32 * (4 * wv + jj) + 4 * half;
+                            const int cbase = n0 + 32 * (4 * wv + jj) + 4 * (int)(lane_id_now() >> 5);
 #pragma unroll
                             for (int i = 0; i < 16; ++i)
                                 if (cbase + 8 * (i >> 2) + (i & 3) >= V) acc[rt][jj][i] = kNegBig;
@@ -224,8 +284,10 @@ __global__ __launch_bounds__(256, 2) void head_tile_kernel(
                         stream_group_rel<L>(st[rt], v, ref, tile_max, c_vt * 8 + 4 * wv + jj);
                         __builtin_amdgcn_sched_barrier(0);
                     }
-                    const float mc_new = first ? tile_max : vmax(ref, tile_max);
-                    st[rt].s *= __builtin_amdgcn_exp2f(ref - mc_new);
+                    // the first tile's reference is its own maximum (-1e30 and an empty sum if every column was
+                    // masked: the vocabulary's last tile); later tiles move the reference up when they exceed it
+                    const float mc_new = first ? ref : vmax(ref, tile_max);
+                    if (!first) st[rt].s *= __builtin_amdgcn_exp2f(ref - mc_new);
                     st[rt].mc = mc_new;
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj)
@@ -233,42 +295,97 @@ __global__ __launch_bounds__(256, 2) void head_tile_kernel(
                         for (int i = 0; i < 16; ++i) acc[rt][jj][i] = -mc_new;
                 }
             }
-            asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            buf_cur = next_buf(buf_cur);
+            __builtin_amdgcn_sched_barrier(0);
+            if (DBG != 2 && last_kb && q + 1 < total) read_operands(buf_next, KS0{});      // kept out of the epilogue's registers
+            buf_cur = buf_next;
             if (q + 1 < total && ++c_kb == nkb) { c_kb = 0; c_vt += hg.gw; }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                  // the surplus loads of the last stages
+        wait_loads<0>();                                                  // the surplus loads of the last stages
     }
 
-    // one partial per (row, stream): stream = (col * 2 + wv) * 2 + half
-    const int nsr = hg.gw * 4;
-    const int sidx = (col * 2 + wv) * 2 + half;
+    if (DBG) {                                         // timing experiments: cycles and 100 MHz ticks of this block
+        if (tid == 0 && blockIdx.x < 8) {
+            reinterpret_cast<long long *>(part)[2 * blockIdx.x] = clock64() - dbg_t0;
+            reinterpret_cast<long long *>(part)[2 * blockIdx.x + 1] = wall_clock64() - dbg_w0;
+        }
+        return;
+    }
+
+    // ---- one record per (row, block): the four streams of a row (two half-wavefronts x two column halves)
+    // are folded into one, in a fixed order.  From here on a tag also names the half: tag * 2 + half.
     constexpr int REC = 3 + 3 * L;
+    float *xchg = reinterpret_cast<float *>(lds_raw);                      // [RT][REC + 1], free after the last barrier
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
-        const int row = row0 + (wr * 2 + rt) * 32 + l32;
-        if (row >= rows) continue;
-        float *o = part + ((size_t)row * nsr + sidx) * REC;
-        o[0] = st[rt].mc; o[1] = st[rt].s; o[2] = st[rt].U;
+        Stream<L> &a = st[rt];
 #pragma unroll
-        for (int l = 0; l < L; ++l) {
-            o[3 + 3 * l] = st[rt].x[l];
-            o[4 + 3 * l] = st[rt].y[l];
-            o[5 + 3 * l] = __int_as_float(st[rt].tag[l]);
+        for (int l = 0; l < L; ++l) a.tag[l] = a.tag[l] * 2 + half;
+        Stream<L> o;
+        o.mc = __shfl_xor(a.mc, 32); o.s = __shfl_xor(a.s, 32); o.U = __shfl_xor(a.U, 32);
+#pragma unroll
+        for (int l = 0; l < L; ++l) { o.x[l] = __shfl_xor(a.x[l], 32); o.y[l] = __shfl_xor(a.y[l], 32); o.tag[l] = __shfl_xor(a.tag[l], 32); }
+        if (half == 0) stream_combine(a, o);                                // lanes 0..31 now hold both halves
+    }
+    __syncthreads();                                                        // every wavefront is past its last operand read
+    if (wv == 1 && half == 0) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            float *o = xchg + ((wr * 2 + rt) * 32 + l32) * (REC + 1);
+            o[0] = st[rt].mc; o[1] = st[rt].s; o[2] = st[rt].U;
+#pragma unroll
+            for (int l = 0; l < L; ++l) { o[3 + 3 * l] = st[rt].x[l]; o[4 + 3 * l] = st[rt].y[l]; o[5 + 3 * l] = __int_as_float(st[rt].tag[l]); }
         }
     }
+    __syncthreads();
+    if (wv == 0 && half == 0) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            const int row = row0 + (wr * 2 + rt) * 32 + l32;
+            const float *i = xchg + ((wr * 2 + rt) * 32 + l32) * (REC + 1);
+            Stream<L> o;
+            o.mc = i[0]; o.s = i[1]; o.U = i[2];
+#pragma unroll
+            for (int l = 0; l < L; ++l) { o.x[l] = i[3 + 3 * l]; o.y[l] = i[4 + 3 * l]; o.tag[l] = __float_as_int(i[5 + 3 * l]); }
+            stream_combine(st[rt], o);
+            if (row >= rows) continue;
+            float *w = part + ((size_t)row * hg.gw + col) * REC;
+            w[0] = st[rt].mc; w[1] = st[rt].s; w[2] = st[rt].U;
+#pragma unroll
+            for (int l = 0; l < L; ++l) { w[3 + 3 * l] = st[rt].x[l]; w[4 + 3 * l] = st[rt].y[l]; w[5 + 3 * l] = __int_as_float(st[rt].tag[l]); }
+        }
+    }
+}
+
+int head_tile_rows_per_block(int rows) {
+    static const bool small = getenv("SLIMSPEC_TILE128") != nullptr;      // experiment switch
+    return (rows > 128 && !small) ? 256 : 128;
+}
+
+template <int WR, int DBG>
+static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part, int rows, int rows_pad,
+                                  int K, int V, int n_rb, int gw, hipStream_t st)
+{
+    using S = TileShape<WR>;
+    auto fn = head_tile_kernel<kStreamList, WR, DBG>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
+    if (e != hipSuccess) return e;
+    HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT};
+    fn<<<n_rb * gw, 64 * S::NW, S::LDS, st>>>(static_cast<const uint4 *>(X), M, part, rows, rows_pad, K, V, hg);
+    return hipGetLastError();
 }
 
 hipError_t launch_head_tile(const void *X, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st)
 {
-    auto fn = head_tile_kernel<kStreamList>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, kTLdsBytes);
-    if (e != hipSuccess) return e;
-    HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT};
-    fn<<<n_rb * gw, 256, kTLdsBytes, st>>>(static_cast<const uint4 *>(X), M, part, rows, rows_pad, K, V, hg);
-    return hipGetLastError();
+    static const int dbg = getenv("SLIMSPEC_DBG") ? atoi(getenv("SLIMSPEC_DBG")) : 0;
+    const bool big = head_tile_rows_per_block(rows) == 256;
+#define SLIMSPEC_TILE(DBG) (big ? launch_tile_cfg<4, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st) \
+                                : launch_tile_cfg<2, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
+    if (dbg == 1) return SLIMSPEC_TILE(1);
+    if (dbg == 2) return SLIMSPEC_TILE(2);
+    if (dbg == 3) return SLIMSPEC_TILE(3);
+    return SLIMSPEC_TILE(0);
+#undef SLIMSPEC_TILE
 }
 
 }  // namespace slimspec

@@ -221,13 +221,15 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         for (int sidx = tid; sidx < nsr; sidx += NT) {
             float r[REC];
             load_rec(sidx, r);
-            const int half = sidx & 1;
             int listed[L];
 #pragma unroll
             for (int l = 0; l < L; ++l) {
                 const float x = r[3 + 3 * l], y = r[4 + 3 * l];
-                const int tag = __float_as_int(r[5 + 3 * l]);
-                listed[l] = (x > kNoValue) ? tag : -1;
+                const int rawtag = __float_as_int(r[5 + 3 * l]);
+                // direct-to-LDS kernel: one stream per block, the tag's lowest bit names the half-wavefront
+                const int half = contig ? (rawtag & 1) : (sidx & 1);
+                const int tag = contig ? (rawtag >> 1) : rawtag;
+                listed[l] = (x > kNoValue) ? rawtag : -1;
                 if (!(x > kNoValue) || !(mask4(x) * unit >= theta)) continue;
                 const int imax = (int)(__float_as_uint(x) & 15u);
                 push(id_of(tag, imax, half), mask4(x) * unit, 0);
@@ -240,19 +242,24 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             }
             const float U = r[2];
             if (U > kNoValue && mask4(U) * unit >= theta) {
-                const int wv = (sidx >> 1) % n_wv, col = (sidx >> 1) / n_wv;
+                // every unlisted group of the stream
+                const int wv = contig ? 0 : (sidx >> 1) % n_wv, col = contig ? sidx : (sidx >> 1) / n_wv;
+                const int j0 = contig ? 0 : wv * tv, j1 = contig ? 8 : wv * tv + tv;
+                const int h0 = contig ? 0 : (sidx & 1), h1 = contig ? 2 : (sidx & 1) + 1;
                 for (int vt = col; vt < n_vt; vt += gw)
-                    for (int j = wv * tv; j < wv * tv + tv; ++j) {
-                        const int tag = vt * 8 + j;
-                        bool is_listed = false;
+                    for (int j = j0; j < j1; ++j)
+                        for (int half = h0; half < h1; ++half) {
+                            const int tag = vt * 8 + j;
+                            const int rawtag = contig ? tag * 2 + half : tag;
+                            bool is_listed = false;
 #pragma unroll
-                        for (int l = 0; l < L; ++l) is_listed |= (listed[l] == tag);
-                        if (is_listed) continue;
-                        for (int i = 0; i < 16; ++i) {
-                            const int id = id_of(tag, i, half);
-                            if (id < V) push(id, 0.f, 1);
+                            for (int l = 0; l < L; ++l) is_listed |= (listed[l] == rawtag);
+                            if (is_listed) continue;
+                            for (int i = 0; i < 16; ++i) {
+                                const int id = id_of(tag, i, half);
+                                if (id < V) push(id, 0.f, 1);
+                            }
                         }
-                    }
             }
         }
     }
@@ -296,7 +303,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             const int item = entry & (kListedBit - 1);
             const int id = w_id[item];
             float acc = 0.f;
-#pragma unroll 8
+#pragma unroll 16
             for (int j = wave * 4 + jsub; j < K; j += 4 * NWAVES)
                 acc = fmaf(xrow[j], bf16_to_float(M[(size_t)j * V + id]), acc);
             uint32_t a, b;

@@ -71,6 +71,7 @@ constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
 
 int mfma_rows_per_tile(int rows);
 bool head_tile_enabled();
+int head_tile_rows_per_block(int rows);
 int mfma_streams_per_block(int rows);
 
 struct MfmaPlan {
@@ -91,16 +92,16 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
     MfmaPlan p;
     p.rows = rows;
     p.tile = head_tile_enabled() && kind == HeadKind::LowRank;
-    p.rt = p.tile ? 128 : mfma_rows_per_tile(rows);
+    p.rt = p.tile ? head_tile_rows_per_block(rows) : mfma_rows_per_tile(rows);
     p.n_rb = (rows + p.rt - 1) / p.rt;
     p.rows_pad = p.n_rb * p.rt;
     p.n_vt = (V + 255) / 256;
-    int colgroups = (p.tile ? 2 : 1) * kPlanSlotsPerXcd / p.n_rb;
+    int colgroups = ((p.tile && p.rt == 128) ? 2 : 1) * kPlanSlotsPerXcd / p.n_rb;      // 128-row blocks: two per CU
     if (colgroups < 1) colgroups = 1;
     const int need = (p.n_vt + 7) / 8;
     if (colgroups > need) colgroups = need;
     p.gw = 8 * colgroups;
-    p.nsr = p.gw * (p.tile ? 4 : mfma_streams_per_block(rows));
+    p.nsr = p.gw * (p.tile ? 1 : mfma_streams_per_block(rows));      // the direct-to-LDS kernel folds a block's streams of a row into one
     size_t off = 0;
     if (kind == HeadKind::LowRank) {
         const int tiles = ((r + 255) / 256) * ((rows + 63) / 64);
