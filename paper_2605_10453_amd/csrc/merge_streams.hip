@@ -303,9 +303,21 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             const int item = entry & (kListedBit - 1);
             const int id = w_id[item];
             float acc = 0.f;
-#pragma unroll 16
-            for (int j = wave * 4 + jsub; j < K; j += 4 * NWAVES)
-                acc = fmaf(xrow[j], bf16_to_float(M[(size_t)j * V + id]), acc);
+            // all loads of a pass are independent: 32 in flight per lane
+            const uint16_t *mcol = M + id;
+            for (int j0 = wave * 4 + jsub; j0 < K; j0 += 32 * 4 * NWAVES) {
+                uint16_t w[32];
+#pragma unroll
+                for (int e = 0; e < 32; ++e) {
+                    const int j = min(j0 + e * 4 * NWAVES, K - 1);
+                    w[e] = mcol[(size_t)j * V];
+                }
+#pragma unroll
+                for (int e = 0; e < 32; ++e) {
+                    const int j = j0 + e * 4 * NWAVES;
+                    acc = fmaf(j < K ? xrow[j] : 0.f, bf16_to_float(w[e]), acc);
+                }
+            }
             uint32_t a, b;
             swap_pair<16>(__float_as_uint(acc), a, b);
             acc = __uint_as_float(a) + __uint_as_float(b);

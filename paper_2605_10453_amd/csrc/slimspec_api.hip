@@ -176,7 +176,8 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
 
 namespace slimspec {
 bool head_tile_enabled() {
-    static const bool on = getenv("SLIMSPEC_HEAD_TILE") != nullptr;
+    // diagnostic switch: SLIMSPEC_HEAD_TILE=0 runs the low-rank head's many-row path on the register-staged kernel
+    static const bool on = !(getenv("SLIMSPEC_HEAD_TILE") && getenv("SLIMSPEC_HEAD_TILE")[0] == '0');
     return on;
 }
 }  // namespace slimspec

@@ -77,6 +77,8 @@ SMALL = [
     (9, 96, 24, 2056, 7),           # one row more than a row group
     (17, 128, 32, 4104, 12),        # three row groups
     (40, 256, 32, 1032, 3),
+    (130, 64, 40, 2056, 5),         # two 128-row halves of a 256-row block, contraction tail, column tail
+    (300, 128, 64, 5000, 10),       # two 256-row blocks, the second mostly padding
 ]
 
 
@@ -92,6 +94,28 @@ def test_full_head_small(gpu, oracle_mod, rows, d, r, V, k, w_f32):
     x = synth.make_inputs(synth.small_config(rows, d, r, V, k), seed=77 + rows, with_full_head=True)
     W = synth.bf16_bits_to_f32(x.W) if w_f32 else x.W
     check_full(gpu, oracle_mod, x.h, W, k)
+
+
+@pytest.mark.parametrize("rows,d,r,V,k", SMALL[9:13])
+def test_full_head_small_many_rows(gpu, oracle_mod, rows, d, r, V, k):
+    """More than 8 rows and bf16 weights: the full head runs on the matrix cores."""
+    x = synth.make_inputs(synth.small_config(rows, d, r, V, k, peaked_every=4), seed=177 + rows, with_full_head=True)
+    check_full(gpu, oracle_mod, x.h, x.W, k)
+
+
+@pytest.mark.parametrize("rows,k", [(20, 17), (140, 40)])
+def test_many_rows_large_k(gpu, oracle_mod, rows, k):
+    """k above the matrix-core path's limit: the call takes the streaming path in row groups."""
+    x = synth.make_inputs(synth.small_config(rows, 128, 32, 3080, k, peaked_every=3), seed=900 + rows)
+    check_low_rank(gpu, oracle_mod, x, k)
+
+
+def test_zero_rows_inside_a_many_row_batch(gpu, oracle_mod):
+    """Padded batch slots (all-zero hidden states) among ordinary rows on the matrix-core path."""
+    x = synth.make_inputs(synth.small_config(33, 128, 32, 3080, 6), seed=4242)
+    x.h[5] = 0
+    x.h[32] = 0
+    check_low_rank(gpu, oracle_mod, x, 6)
 
 
 def test_config1_both_heads_agree(gpu, oracle_mod):
