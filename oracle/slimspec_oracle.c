@@ -28,7 +28,8 @@
  * rank(AB) <= r, sum exp(logprob) = 1, shift invariance, permutation
  * equivariance, k = 1 = argmax, k = V = sorted log-softmax, numpy/scipy
  * cross-checks.  Numerical values on random inputs are pinned only through
- * those library cross-checks (the paper prints no worked logits).
+ * those library cross-checks (the paper prints no worked logits): beyond the
+ * pins above, parity on random inputs is "parity unpinned" by any paper value.
  */
 #include <math.h>
 #include <stdint.h>
