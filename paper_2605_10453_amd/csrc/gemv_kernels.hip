@@ -187,14 +187,14 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
 
 template <int R>
 static hipError_t launch_down(const uint16_t *h, const uint16_t *A, float *tpart,
-                              int rows_here, int d, int r, const FusedPlan &fp, hipStream_t st)
+                              int rows_here, int d, int r, const DownPlan &fp, hipStream_t st)
 {
     down_items_kernel<R><<<fp.n_items, kDownThreads, 0, st>>>(h, A, tpart, rows_here, d, r, fp.n_cb, fp.slice);
     return hipGetLastError();
 }
 
 hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *tpart,
-                                  int rows_here, int d, int r, const FusedPlan &fp, hipStream_t st)
+                                  int rows_here, int d, int r, const DownPlan &fp, hipStream_t st)
 {
     if (rows_here <= 1) return launch_down<1>(h, A, tpart, rows_here, d, r, fp, st);
     if (rows_here <= 2) return launch_down<2>(h, A, tpart, rows_here, d, r, fp, st);

@@ -8,7 +8,7 @@ namespace slimspec {
 
 // slices of t = h A (fp32, [nds][R][r] with R = 1, 2, 4 or 8 >= rows_here) for up to kGemvMaxRows rows
 hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *tpart,
-                                  int rows_here, int d, int r, const FusedPlan &fp, hipStream_t st);
+                                  int rows_here, int d, int r, const DownPlan &dp, hipStream_t st);
 
 // x = float(h) for the full head.
 hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st);
@@ -22,12 +22,6 @@ hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_
 // Combine the partials of every row into the final ids and log-probabilities.
 hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int *part_id,
                         int rows, int chunks, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st);
-
-// whole head for up to kGemvMaxRows rows in one launch (down-projection, streaming, merge)
-hipError_t launch_fused_head(bool low_rank, const uint16_t *h, const uint16_t *A, const void *M, bool m_is_f32,
-                             float *tpart, uint32_t *flags, uint32_t *ticket, float2 *ms, float *pv, int *pi,
-                             int rows_here, int d, int K, int V, int chunks, int k, const FusedPlan &fp,
-                             int32_t *out_ids, float *out_lp, hipStream_t st);
 
 // ---- matrix-core path (rows > kGemvMaxRows, bf16 weights) ----
 constexpr int kStreamList = 3;          // groups kept per lane stream

@@ -15,10 +15,24 @@ constexpr size_t kAlign = 256;
 
 enum class HeadKind { LowRank, Full };
 
-// Single-launch streaming path: how the down-projection is shared out among the blocks.
-struct FusedPlan { int n_items = 0, n_cb = 0, nds = 0, slice = 0; };
-FusedPlan make_fused_plan(bool low_rank, int d, int r);
-bool fused_head_fits(int rows_here, int chunks, int k);
+// How the few-row down-projection is shared out: n_cb column blocks of 64 columns of A x nds slices of d.
+struct DownPlan { int n_items = 0, n_cb = 0, nds = 0, slice = 0; };
+inline DownPlan make_down_plan(bool low_rank, int d, int r) {
+    DownPlan p;
+    if (low_rank) {
+        p.n_cb = (r + 63) / 64;
+        // about 240 items in all (one round of blocks on 256 CUs), at most 32 slices, slices a multiple of 8 rows
+        int want = 240 / p.n_cb;
+        if (want > 32) want = 32;
+        if (want < 1) want = 1;
+        int slice = ((d + want - 1) / want + 7) / 8 * 8;
+        if (slice < 64) slice = 64;
+        p.slice = slice;
+        p.nds = (d + slice - 1) / slice;
+        p.n_items = p.n_cb * p.nds;
+    }
+    return p;
+}
 
 struct Plan {
     bool ok = false;
@@ -27,8 +41,7 @@ struct Plan {
     int chunks = 0;            // partials per row
     // byte offsets into the workspace
     size_t off_x = 0;          // fp32 [kGemvMaxRows, K]: t (low-rank) or widened h (full)
-    size_t off_tpart = 0;      // fp32 [nds, kGemvMaxRows, r]  slices of t (single-launch path)
-    size_t off_flags = 0;      // uint32 [n_items + 1]         item flags, then the ticket
+    size_t off_tpart = 0;      // fp32 [nds, kGemvMaxRows, r]  slices of t
     size_t off_part_ms = 0;    // float2 [rows, chunks]      running max, sum of exp
     size_t off_part_val = 0;   // float  [rows, chunks, k]   per-chunk top-k logits
     size_t off_part_id = 0;    // int32  [rows, chunks, k]   per-chunk top-k ids
@@ -45,9 +58,8 @@ inline Plan make_plan(HeadKind kind, int rows, int d, int r, int V, int k) {
     size_t off = 0;
     p.off_x = off;          off = align_up(off + sizeof(float) * kGemvMaxRows * (size_t)p.K);
     {
-        const FusedPlan fp = make_fused_plan(kind == HeadKind::LowRank, d, r);
-        p.off_tpart = off;  off = align_up(off + sizeof(float) * (size_t)fp.nds * kGemvMaxRows * (size_t)r);
-        p.off_flags = off;  off = align_up(off + sizeof(uint32_t) * ((size_t)fp.n_items + 2));
+        const DownPlan dp = make_down_plan(kind == HeadKind::LowRank, d, r);
+        p.off_tpart = off;  off = align_up(off + sizeof(float) * (size_t)dp.nds * kGemvMaxRows * (size_t)r);
     }
     p.off_part_ms = off;    off = align_up(off + 2 * sizeof(float) * (size_t)rows * p.chunks);
     p.off_part_val = off;   off = align_up(off + sizeof(float) * (size_t)rows * p.chunks * k);

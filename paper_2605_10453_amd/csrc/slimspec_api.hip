@@ -41,6 +41,7 @@ int check_shape(HeadKind kind, const slimspec_shape *s, int32_t k)
 }
 
 constexpr int kMfmaMaxK = 16;      // the lane streams keep 3 groups: enough for k <= 16 (larger k: streaming path)
+constexpr int kMfmaMinRows = 5;    // from here on the matrix-core path is faster than streaming rows in lock step (measured at C2's shape)
 
 size_t mfma_workspace_bytes(HeadKind kind, const slimspec_shape *s)
 {
@@ -112,7 +113,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         return SLIMSPEC_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(out_ids) & 3u) || (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
         return SLIMSPEC_UNSUPPORTED;
-    const bool use_mfma = shape->rows > kGemvMaxRows && !m_is_f32 && k <= kMfmaMaxK;
+    const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK;
     if (use_mfma)
         return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
     const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
@@ -126,29 +127,9 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     int *part_id = reinterpret_cast<int *>(ws + p.off_part_id);
     const uint16_t *hb = static_cast<const uint16_t *>(h);
 
-    // Rows are processed in groups of kGemvMaxRows by the streaming kernels; the groups reuse the
-    // small scratch in stream order.  A group normally takes ONE launch (down-projection, streaming
-    // and merge fused); when the merge scratch does not fit that kernel (large k) it takes three.
-    const bool fused = fused_head_fits(kGemvMaxRows, p.chunks, k) && getenv("SLIMSPEC_FUSED");
-    if (fused) {
-        const FusedPlan fp = make_fused_plan(kind == HeadKind::LowRank, p.d, p.r);
-        float *tpart = reinterpret_cast<float *>(ws + p.off_tpart);
-        uint32_t *flags = reinterpret_cast<uint32_t *>(ws + p.off_flags);
-        uint32_t *ticket = flags + fp.n_items + 1;
-        for (int row0 = 0; row0 < p.rows; row0 += kGemvMaxRows) {
-            const int rows_here = (p.rows - row0 < kGemvMaxRows) ? p.rows - row0 : kGemvMaxRows;
-            hipError_t e;
-            const bool timed = g_ev_start && row0 == 0;
-            if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-            e = launch_fused_head(kind == HeadKind::LowRank, hb + (size_t)row0 * p.d, static_cast<const uint16_t *>(A), M, m_is_f32,
-                                  tpart, flags, ticket, part_ms, part_val, part_id, rows_here, p.d, p.K, p.V, p.chunks, k, fp,
-                                  out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
-            if (e != hipSuccess) return fail_hip(e);
-            if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-        }
-        return SLIMSPEC_OK;
-    }
-    const FusedPlan dp = make_fused_plan(kind == HeadKind::LowRank, p.d, p.r);
+    // Rows are processed in groups of kGemvMaxRows by the streaming kernels; the groups reuse the small
+    // scratch in stream order; one merge launch serves all rows.
+    const DownPlan dp = make_down_plan(kind == HeadKind::LowRank, p.d, p.r);
     float *tpart = reinterpret_cast<float *>(ws + p.off_tpart);
     for (int row0 = 0; row0 < p.rows; row0 += kGemvMaxRows) {
         const int rows_here = (p.rows - row0 < kGemvMaxRows) ? p.rows - row0 : kGemvMaxRows;
@@ -193,7 +174,7 @@ size_t slimspec_workspace_bytes(const slimspec_shape *shape, int32_t k)
     // the larger of: streaming path (also serves fp32 W and large k), matrix-core path, for both heads
     if (check_shape(HeadKind::Full, shape, k) == SLIMSPEC_OK) {
         need = make_plan(HeadKind::Full, shape->rows, shape->d, shape->r, shape->V, k).bytes;
-        if (shape->rows > kGemvMaxRows) {
+        if (shape->rows >= kMfmaMinRows) {
             size_t m = mfma_workspace_bytes(HeadKind::Full, shape);
             if (m > need) need = m;
         }
@@ -201,7 +182,7 @@ size_t slimspec_workspace_bytes(const slimspec_shape *shape, int32_t k)
     if (check_shape(HeadKind::LowRank, shape, k) == SLIMSPEC_OK) {
         size_t lo = make_plan(HeadKind::LowRank, shape->rows, shape->d, shape->r, shape->V, k).bytes;
         if (lo > need) need = lo;
-        if (shape->rows > kGemvMaxRows) {
+        if (shape->rows >= kMfmaMinRows) {
             size_t m = mfma_workspace_bytes(HeadKind::LowRank, shape);
             if (m > need) need = m;
         }
