@@ -74,10 +74,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int n = nsr * L;
-    const int ngroups = (n + 63) / 64;
-    uint64_t *keys = reinterpret_cast<uint64_t *>(lds_raw);            // [ngroups * 64] listed maxima, padded with kNoKey
-    uint64_t *surv = keys + (size_t)ngroups * 64;                       // [ngroups * k]  best k of every 64
-    uint64_t *work = surv + (size_t)ngroups * k;                        // [kWorkCap]     final keys / fallback buffer
+    const int ngroups = (nsr + 63) / 64;                                // groups of 64 stream heads
+    uint64_t *keys = reinterpret_cast<uint64_t *>(lds_raw);            // [n]            every listed maximum
+    uint64_t *hkeys = keys + n;                                         // [ngroups * 64] the streams' largest maxima, padded with kNoKey
+    uint64_t *surv = hkeys + (size_t)ngroups * 64;                      // [max(ngroups, 3) * k]  best k of every 64 heads; then the candidates for tau
+    uint64_t *work = surv + (size_t)(ngroups > 3 ? ngroups : 3) * k;    // [kWorkCap]     final keys / fallback buffer
     int *w_id = reinterpret_cast<int *>(work + kWorkCap);               // [kWorkCap]
     float *w_val = reinterpret_cast<float *>(w_id + kWorkCap);          // [kWorkCap]
     int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]     0 no, 1 / 2 yes; later: list of items to evaluate
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             keys[sidx * L + l] = (x > kNoValue) ? make_key(mask4(x) * unit, (uint32_t)(sidx * L + l)) : kNoKey;
         }
     }
-    for (int e = n + tid; e < ngroups * 64; e += NT) keys[e] = kNoKey;
+    for (int sidx = tid; sidx < ngroups * 64; sidx += NT) hkeys[sidx] = (sidx < nsr) ? keys[sidx * L] : kNoKey;   // own writes
     __syncthreads();
     float Mx = red_m[0], X2 = 0.f;
 #pragma unroll
@@ -173,11 +174,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     }
 
     TRACE2(2);
-    // ---- tau: the k-th largest listed maximum (best k of every 64 keys, then all pairs)
-    for (int e = tid; e < n; e += NT) {
-        const uint64_t mine = keys[e];
+    // ---- tau: the k-th largest listed maximum.  The lists are sorted, so first T = the k-th largest of the
+    // streams' heads (best k of every 64 heads, then all pairs); every listed maximum >= T (at most 3 k of them,
+    // all of them if there are fewer than k heads) is a candidate, and tau is the k-th largest candidate.
+    for (int e = tid; e < nsr; e += NT) {
+        const uint64_t mine = hkeys[e];
         if (mine == kNoKey) continue;
-        const uint4 *grp = reinterpret_cast<const uint4 *>(keys + (e & ~63));       // 64 keys, two per 16-byte read
+        const uint4 *grp = reinterpret_cast<const uint4 *>(hkeys + (e & ~63));      // 64 keys, two per 16-byte read
         int rank = 0;
 #pragma unroll
         for (int q = 0; q < 32; ++q) {
@@ -189,7 +192,20 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __syncthreads();
     TRACE2(3);
     const int n_surv = (int)cnt_surv;
-    rank_all_pairs(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
+    __shared__ uint64_t head_bound;
+    __shared__ uint32_t cnt_cand;
+    if (tid == 0) { head_bound = kNoKey; cnt_cand = 0u; }
+    __syncthreads();
+    rank_all_pairs(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) head_bound = key; });
+    __syncthreads();
+    const uint64_t T = head_bound;                                       // kNoKey (smallest): fewer than k heads
+    __syncthreads();                                                     // surv is reused below
+    for (int e = tid; e < n; e += NT) {
+        const uint64_t mine = keys[e];
+        if (mine != kNoKey && mine >= T) surv[atomicAdd(&cnt_cand, 1u)] = mine;
+    }
+    __syncthreads();
+    rank_all_pairs(surv, (int)cnt_cand, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
     __syncthreads();
     TRACE2(4);
     const bool have_tau = tau_key != kNoKey;
@@ -421,8 +437,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
 
 size_t merge_streams_lds_bytes(int nsr, int k) {
     const size_t n = (size_t)nsr * kStreamList;
-    const size_t ngroups = (n + 63) / 64;
-    return sizeof(uint64_t) * (ngroups * 64 + ngroups * k + kWorkCap) + 16u * kWorkCap;
+    const size_t ngroups = ((size_t)nsr + 63) / 64;
+    return sizeof(uint64_t) * (n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k + kWorkCap) + 16u * kWorkCap;
 }
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
