@@ -25,12 +25,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16 matrix peak
-GEMV_MAX_ROWS = 8              # rows up to which the library streams (above: matrix cores)
+GEMV_MAX_ROWS = 4              # rows up to which the library streams (from 5 rows on: matrix cores)
 
 # HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/ (each scaled by the same counter's reading for a plain copy kernel of
 # known size); None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C2": 131977480, "C4": 142534173}
+MEASURED_TRAFFIC_BYTES = {"C2": 131977480, "C4": 147272027}
 
 
 def log(*a):
@@ -172,7 +172,7 @@ def main():
                    "frac": ach / HBM_PEAK_GBS}
         out.update({"traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                     "kernel": "vocabulary projection + running log-sum-exp / top-k "
-                              + ("(head_mfma_kernel)" if cfg.rows > GEMV_MAX_ROWS else "(stream_topk_kernel)"),
+                              + ("(head_tile_kernel)" if cfg.rows > GEMV_MAX_ROWS else "(stream_topk_kernel)"),
                     "kernel_us": kern_ms * 1e3,
                     "kernel_us_minus_empty_event_pair": (kern_ms - null_ms) * 1e3,
                     "empty_event_pair_us": null_ms * 1e3,
