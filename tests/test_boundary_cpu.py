@@ -103,3 +103,25 @@ def test_product_path_does_not_touch_the_checker():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2605_10453_amd" not in text and "libslimspec" not in text
+
+
+def test_direct_to_lds_kernel_does_not_spill():
+    """head_tile_kernel counts its own vector-memory loads (s_waitcnt vmcnt(N)); a register spill would add
+    loads the count does not know about.  The compiler must report no scratch for every instance of it."""
+    import shutil
+    import subprocess
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    from paper_2605_10453_amd import build as build_mod
+    src = os.path.join(build_mod.CSRC, "head_tile.hip")
+    flags = [f for f in build_mod.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    out = subprocess.run([hipcc, *flags, "--cuda-device-only", "-c", src, "-o", os.devnull,
+                          "-Rpass-analysis=kernel-resource-usage"], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr[-2000:]
+    text = out.stderr
+    names = re.findall(r"Function Name: (\S+)", text)
+    scratch = re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", text)
+    tiles = [(n, int(sz)) for n, sz in zip(names, scratch) if "head_tile_kernel" in n]
+    assert len(tiles) >= 2, text[-2000:]
+    assert all(sz == 0 for _, sz in tiles), tiles

@@ -79,7 +79,17 @@ SMALL = [
     (40, 256, 32, 1032, 3),
     (130, 64, 40, 2056, 5),         # two 128-row halves of a 256-row block, contraction tail, column tail
     (300, 128, 64, 5000, 10),       # two 256-row blocks, the second mostly padding
+    (20, 64, 8, 1032, 4),           # a single, partial stage of the contraction
+    (12, 64, 24, 2056, 16),         # the largest k of the matrix-core path
+    (5, 128, 32, 4104, 10),         # the smallest row count of the matrix-core path
 ]
+
+
+def test_more_rows_than_one_launch(gpu, oracle_mod):
+    """More rows than one launch of the matrix-core kernels takes (4096): the call loops over launches."""
+    x = synth.make_inputs(synth.small_config(4100, 64, 32, 1032, 5, peaked_every=7), seed=4100)
+    check_low_rank(gpu, oracle_mod, x, 5)
+
 
 
 @pytest.mark.parametrize("rows,d,r,V,k", SMALL)
