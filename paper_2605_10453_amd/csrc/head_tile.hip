@@ -227,6 +227,7 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
             buf_ahead = next_buf(buf_ahead);
             if (DBG != 3) issue_stage(buf_ahead);
             if (DBG != 2) multiply(KS0{});
+            __builtin_amdgcn_sched_barrier(0);                            // the waits below stay behind the first k-step's MFMAs
             // every read of this stage has returned (its buffer is reloaded after the barrier); the next stage has landed
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             wait_loads<S::WAIT>();
@@ -308,6 +309,7 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
             reinterpret_cast<long long *>(part)[2 * blockIdx.x] = clock64() - dbg_t0;
             reinterpret_cast<long long *>(part)[2 * blockIdx.x + 1] = wall_clock64() - dbg_w0;
         }
+        part[64 + (size_t)blockIdx.x * blockDim.x + tid] = st[0].s + st[1].s;      // keeps the arithmetic alive
         return;
     }
 
