@@ -5,14 +5,16 @@
 
 namespace slimspec {
 
-__global__ __launch_bounds__(kMergeThreads) void merge_kernel(
+constexpr int kRowMergeThreads = 1024;   // one block per row: the more threads, the shorter the load and rank phases
+
+__global__ __launch_bounds__(kRowMergeThreads) void merge_kernel(
     const float2 *__restrict__ part_ms, const float *__restrict__ part_val, const int *__restrict__ part_id,
     int chunks, int k, int cache_ids, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     __shared__ MergeSmall small;
     const int row = blockIdx.x;
-    merge_row<kMergeThreads>(lds_raw, cache_ids != 0, small, threadIdx.x, part_ms + (size_t)row * chunks,
+    merge_row<kRowMergeThreads>(lds_raw, cache_ids != 0, small, threadIdx.x, part_ms + (size_t)row * chunks,
                              part_val + (size_t)row * chunks * k, part_id + (size_t)row * chunks * k,
                              chunks, k, out_ids + (size_t)row * k, out_logprobs + (size_t)row * k);
 }
@@ -27,7 +29,7 @@ hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int 
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    merge_kernel<<<rows, kMergeThreads, lds, st>>>(part_ms, part_val, part_id, chunks, k, cache_ids ? 1 : 0, out_ids, out_logprobs);
+    merge_kernel<<<rows, kRowMergeThreads, lds, st>>>(part_ms, part_val, part_id, chunks, k, cache_ids ? 1 : 0, out_ids, out_logprobs);
     return hipGetLastError();
 }
 

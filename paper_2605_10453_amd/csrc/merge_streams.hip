@@ -319,18 +319,16 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             const int item = entry & (kListedBit - 1);
             const int id = w_id[item];
             float acc = 0.f;
-            // all loads of a pass are independent: 32 in flight per lane
+            // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 8 independent loads per lane
             const uint16_t *mcol = M + id;
-            for (int j0 = wave * 4 + jsub; j0 < K; j0 += 32 * 4 * NWAVES) {
-                uint16_t w[32];
+            constexpr int RSTEP = 4 * NWAVES;
+            for (int j0 = wave * 4 + jsub; j0 < K; j0 += 8 * RSTEP) {
+                uint16_t w[8];
 #pragma unroll
-                for (int e = 0; e < 32; ++e) {
-                    const int j = min(j0 + e * 4 * NWAVES, K - 1);
-                    w[e] = mcol[(size_t)j * V];
-                }
+                for (int e = 0; e < 8; ++e) w[e] = mcol[(size_t)min(j0 + e * RSTEP, K - 1) * V];
 #pragma unroll
-                for (int e = 0; e < 32; ++e) {
-                    const int j = j0 + e * 4 * NWAVES;
+                for (int e = 0; e < 8; ++e) {
+                    const int j = j0 + e * RSTEP;
                     acc = fmaf(j < K ? xrow[j] : 0.f, bf16_to_float(w[e]), acc);
                 }
             }

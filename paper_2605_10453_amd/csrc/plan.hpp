@@ -9,7 +9,7 @@ namespace slimspec {
 
 constexpr int kChunkCols = 512;      // vocabulary columns per partial: one wavefront x 8 columns per lane
 constexpr int kGemvMaxRows = 8;      // rows handled by one pass of the streaming (lane-owns-columns) path
-constexpr int kMergeThreads = 256;    // threads of the merge block of one row
+constexpr int kMergeThreads = 512;    // threads of the stream-merge block of one row
 constexpr int SLIMSPEC_KMAX_INTERNAL = 64;
 constexpr size_t kAlign = 256;
 
