@@ -50,6 +50,8 @@ struct TileShape {
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #define LDS_PTR(T, byte_addr) ((__attribute__((address_space(3))) T *)(uintptr_t)(byte_addr))
@@ -66,6 +68,14 @@ __device__ __forceinline__ uint32_t lane_id_now() {
     asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
     return l;
 }
+// Two bf16 values -> the same two values in f16 (exact for magnitudes in [2^-14, 65504]; smaller ones become
+// f16 subnormals with an absolute error below 2^-25, larger ones infinities, which the merge answers with its
+// exhaustive exact pass).  Plain 32-bit VALU instructions: packed 16-bit arithmetic does not overlap with MFMAs.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t b) {
+    typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+    const f16x2_t h = __builtin_bit_cast(f16x2_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(b << 16), __uint_as_float(b & 0xffff0000u)));
+    return __builtin_bit_cast(uint32_t, h);
+}
 template <int N>
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
@@ -76,7 +86,7 @@ __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)
 // M: [K][V] bf16 row-major, V and K multiples of 8
 // part: [rows][gw][3 + 3 L] stream records (values in base-2 units): one per row and block
 // DBG != 0: timing experiments (1 no epilogue, 2 loads only, 3 no loads); results are meaningless
-template <int L, int WR, int DBG>
+template <int L, int WR, bool F16, int DBG>
 __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
     const uint4 *__restrict__ X, const uint16_t *__restrict__ M, float *__restrict__ part,
     int rows, int rows_pad, int K, int V, HeadGrid hg)
@@ -189,22 +199,44 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
             issue_stage(buf_ahead);
         }
         wait_loads<S::WAIT>();
+        // F16: every wavefront turns the part of the M tile that it loaded itself (so no barrier is needed before)
+        // from bf16 into f16, in place; the barrier that publishes the stage comes after.
+        const uint32_t own_m = m_lds + (uint32_t)lane * 16u;
+        u32x4 raw[S::MPW];
+        const auto read_own = [&](uint32_t buf) {
+#pragma unroll
+            for (int u = 0; u < S::MPW; ++u) raw[u] = *LDS_PTR(u32x4, buf + own_m + u * 1024);
+        };
+        const auto convert_own = [&](uint32_t buf) {
+#pragma unroll
+            for (int u = 0; u < S::MPW; ++u) {
+                u32x4 c;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) c[e] = bf16x2_to_f16x2(raw[u][e]);
+                *LDS_PTR(u32x4, buf + own_m + u * 1024) = c;
+            }
+        };
+        if (F16) {
+            read_own(buf_cur);
+            convert_own(buf_cur);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
         __builtin_amdgcn_s_barrier();
 
         // Operand reads run one k-step (8 MFMAs) ahead of their use, also across stages: the barrier that
         // publishes the next stage sits between the two k-steps of the current one.
-        bf16x8 xf[2][2], mf[2][4];                                        // [k-step][tile]
+        u32x4 xf[2][2], mf[2][4];                                         // [k-step][tile], 8 16-bit values each
         const auto read_operands = [&](uint32_t buf, auto ks_tag) {
             constexpr int ks = decltype(ks_tag)::value;
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt)
-                xf[ks][rt] = __builtin_bit_cast(bf16x8, *LDS_PTR(u32x4, buf + xa + ks * (2 * S::RT * 16) + rt * 512));
+                xf[ks][rt] = *LDS_PTR(u32x4, buf + xa + ks * (2 * S::RT * 16) + rt * 512);
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
                 const uint32_t mj = (buf + ma0) ^ (uint32_t)(jj << 6);
                 const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4i16, mj + ks * 8192));
                 const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(v4i16, mj + ks * 8192 + 2048));
-                mf[ks][jj] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                mf[ks][jj] = __builtin_bit_cast(u32x4, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
         };
         const auto multiply = [&](auto ks_tag) {
@@ -213,7 +245,15 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
             for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj)
-                    acc[rt][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(mf[ks][jj], xf[ks][rt], acc[rt][jj], 0, 0, 0);
+                    acc[rt][jj] = F16 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, mf[ks][jj]), __builtin_bit_cast(f16x8, xf[ks][rt]), acc[rt][jj], 0, 0, 0)
+                                      : __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, mf[ks][jj]), __builtin_bit_cast(bf16x8, xf[ks][rt]), acc[rt][jj], 0, 0, 0);
+        };
+        const auto multiply_rows = [&](auto ks_tag, auto rt_tag) {        // one row tile of a k-step: 4 MFMAs
+            constexpr int ks = decltype(ks_tag)::value, rt = decltype(rt_tag)::value;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                acc[rt][jj] = F16 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, mf[ks][jj]), __builtin_bit_cast(f16x8, xf[ks][rt]), acc[rt][jj], 0, 0, 0)
+                                  : __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, mf[ks][jj]), __builtin_bit_cast(bf16x8, xf[ks][rt]), acc[rt][jj], 0, 0, 0);
         };
         using KS0 = std::integral_constant<int, 0>;
         using KS1 = std::integral_constant<int, 1>;
@@ -222,18 +262,41 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
         for (int q = 0; q < total; ++q) {
             const bool last_kb = c_kb == nkb - 1;
             const uint32_t buf_next = next_buf(buf_cur);
+            if (F16) {
+                // own part of the next stage: landed (before this iteration's loads are issued: one stage fewer may
+                // be outstanding) -> registers; converted while the first k-step multiplies; back to LDS
+                wait_loads<(S::NBUF - 3) * S::LPS>();
+                read_own(buf_next);
+            }
             if (DBG != 2) read_operands(buf_cur, KS1{});
             if (q + S::NBUF - 1 < total) advance_ahead();
             buf_ahead = next_buf(buf_ahead);
             if (DBG != 3) issue_stage(buf_ahead);
-            if (DBG != 2) multiply(KS0{});
-            __builtin_amdgcn_sched_barrier(0);                            // the waits below stay behind the first k-step's MFMAs
+            if (F16) {
+                if (DBG != 2) multiply(KS0{});
+                convert_own(buf_next);
+                // issue order: an MFMA first (its operands are in registers), then three conversion instructions
+                // behind every MFMA, the LDS writes last
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 3 * S::MPW / 2, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x200, S::MPW, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                // half of the second k-step before the barrier: the LDS writes above land behind its MFMAs
+                if (DBG != 2) multiply_rows(KS1{}, KS0{});
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                if (DBG != 2) multiply(KS0{});
+                __builtin_amdgcn_sched_barrier(0);                        // the waits below stay behind the first k-step's MFMAs
+            }
             // every read of this stage has returned (its buffer is reloaded after the barrier); the next stage has landed
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            wait_loads<S::WAIT>();
+            if (!F16) wait_loads<S::WAIT>();
             __builtin_amdgcn_s_barrier();
             if (DBG != 2 && !last_kb && q + 1 < total) read_operands(buf_next, KS0{});
-            if (DBG != 2) multiply(KS1{});
+            if (DBG != 2) { if (F16) multiply_rows(KS1{}, KS1{}); else multiply(KS1{}); }
             __builtin_amdgcn_sched_barrier(0);
 
             if (DBG != 0 && last_kb) {
@@ -363,12 +426,12 @@ int head_tile_rows_per_block(int rows) {
     return (rows > 128 && !small) ? 256 : 128;
 }
 
-template <int WR, int DBG>
+template <int WR, bool F16, int DBG>
 static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part, int rows, int rows_pad,
                                   int K, int V, int n_rb, int gw, hipStream_t st)
 {
     using S = TileShape<WR>;
-    auto fn = head_tile_kernel<kStreamList, WR, DBG>;
+    auto fn = head_tile_kernel<kStreamList, WR, F16, DBG>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
     if (e != hipSuccess) return e;
     HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT};
@@ -376,18 +439,20 @@ static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part,
     return hipGetLastError();
 }
 
-hipError_t launch_head_tile(const void *X, const uint16_t *M, float *part, int rows, int rows_pad,
+hipError_t launch_head_tile(const void *X, bool x_is_f16, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st)
 {
     static const int dbg = getenv("SLIMSPEC_DBG") ? atoi(getenv("SLIMSPEC_DBG")) : 0;
     const bool big = head_tile_rows_per_block(rows) == 256;
-#define SLIMSPEC_TILE(DBG) (big ? launch_tile_cfg<4, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st) \
-                                : launch_tile_cfg<2, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
+#define SLIMSPEC_TILE_F(F16, DBG) (big ? launch_tile_cfg<4, F16, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st) \
+                                       : launch_tile_cfg<2, F16, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
+#define SLIMSPEC_TILE(DBG) (x_is_f16 ? SLIMSPEC_TILE_F(true, DBG) : SLIMSPEC_TILE_F(false, DBG))
     if (dbg == 1) return SLIMSPEC_TILE(1);
     if (dbg == 2) return SLIMSPEC_TILE(2);
     if (dbg == 3) return SLIMSPEC_TILE(3);
     return SLIMSPEC_TILE(0);
 #undef SLIMSPEC_TILE
+#undef SLIMSPEC_TILE_F
 }
 
 }  // namespace slimspec

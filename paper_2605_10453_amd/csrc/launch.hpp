@@ -35,7 +35,7 @@ hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, i
 // slices -> fp32 t, f16 t (k-grouped), per-row rounding statistics, rms estimate of B
 hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_pad, int r,
                               float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
-                              bool as_bf16, hipStream_t st);
+                              int xmode, hipStream_t st);   // xmode 0: f16 t; 1: bf16 t log2(e); 2: f16 t log2(e)
 // vocabulary projection with the fused epilogue; X is f16 k-grouped (x_row_major = false, M converted to
 // f16 on the fly) or bf16 row-major [rows, K] (x_row_major = true, bf16 MFMA)
 hipError_t launch_head_mfma(const uint16_t *X, bool x_row_major, const uint16_t *M, float *part,
@@ -43,13 +43,15 @@ hipError_t launch_head_mfma(const uint16_t *X, bool x_row_major, const uint16_t 
 
 // the same projection from stages loaded straight into LDS; X is bf16 in 16-byte vectors of 8 contraction
 // elements, [ceil(K / 64) * 8][rows_pad], rows_pad a multiple of 128; columns of an MFMA tile are contiguous
-hipError_t launch_head_tile(const void *X, const uint16_t *M, float *part, int rows, int rows_pad,
+// x_is_f16: X holds f16 t log2(e) and the kernel turns the M tiles into f16 inside LDS (an 8 times
+// finer operand than bf16); otherwise X holds bf16 t log2(e)
+hipError_t launch_head_tile(const void *X, bool x_is_f16, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st);
 
 // stream partials -> final ids / log-probabilities, with exact fp32 re-evaluation of uncertain ranks
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                bool contiguous_tiles, float unit, int32_t *out_ids, float *out_logprobs, hipStream_t st);
+                                bool contiguous_tiles, float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, hipStream_t st);
 
 }  // namespace slimspec

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ brms,
-    int k, int contig, float unit, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+    int k, int contig, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     };
 
     // ---- log-sum-exp of the streams, and the squared norm of the row's contraction input
-    float m_t = kNegInf, s_t = 0.f, x2 = 0.f;
+    float m_t = kNegInf, s_t = 0.f, x2 = 0.f, x1 = 0.f;
     for (int sidx = tid; sidx < nsr; sidx += NT) {
         float f[REC];
         load_rec(sidx, f);
@@ -129,16 +129,18 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             m_t = m_new;
         }
     }
-    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; }
+    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
     __shared__ float stat_sh[64];
     if (stat != nullptr && tid < n_stat && tid < 64) stat_sh[tid] = stat[(size_t)tid * rows_pad + row].x;
     const float m_w = wave_max(m_t);
     float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
     s_w = wave_sum(s_w);
     x2 = wave_sum(x2);
+    x1 = wave_sum(x1);
     if (lane == 0) { red_m[wave] = m_w; red_s[wave] = s_w; }
     __shared__ float red_x[NWAVES];
-    if (lane == 0) red_x[wave] = x2;
+    __shared__ float red_x1[NWAVES];
+    if (lane == 0) { red_x[wave] = x2; red_x1[wave] = x1; }
 
     TRACE2(1);
     // ---- keys of the listed maxima
@@ -153,7 +155,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     }
     for (int sidx = tid; sidx < ngroups * 64; sidx += NT) hkeys[sidx] = (sidx < nsr) ? keys[sidx * L] : kNoKey;   // own writes
     __syncthreads();
-    float Mx = red_m[0], X2 = 0.f;
+    float Mx = red_m[0], X2 = 0.f, X1 = 0.f;
 #pragma unroll
     for (int w = 1; w < NWAVES; ++w) Mx = fmaxf(Mx, red_m[w]);
     float S = 0.f;
@@ -161,6 +163,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     for (int w = 0; w < NWAVES; ++w) {
         S += (red_m[w] == kNegInf) ? 0.f : red_s[w] * __builtin_amdgcn_exp2f(red_m[w] - Mx);
         X2 += red_x[w];
+        X1 += red_x1[w];
     }
     const float lse = (Mx + __builtin_amdgcn_logf(S)) * kLn2;
 
@@ -214,7 +217,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     if (stat != nullptr) {
         float dt2 = 0.f;                                     // squared norm of t - f16(t), summed in a fixed order
         for (int q = 0; q < n_stat; ++q) dt2 += (q < 64) ? stat_sh[q] : stat[(size_t)q * rows_pad + row].x;
-        eps = kEpsSigmas * sqrtf(dt2) * brms[0] + fabsf(tau) * 1.2e-5f + 1e-30f;
+        // + weights the kernel flushed to zero (magnitude below tiny_w) times the 1-norm of the contraction input
+        eps = kEpsSigmas * sqrtf(dt2) * brms[0] + fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
     }
     else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
     const float theta = have_tau ? tau - 2.f * eps : kNegInf;
@@ -442,14 +446,14 @@ size_t merge_streams_lds_bytes(int nsr, int k) {
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                bool contiguous_tiles, float unit, int32_t *out_ids, float *out_logprobs, hipStream_t st)
+                                bool contiguous_tiles, float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_wv, tv, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, brms, k, contiguous_tiles ? 1 : 0, unit, out_ids, out_logprobs);
+                                                           M, K, V, stat, n_stat, rows_pad, brms, k, contiguous_tiles ? 1 : 0, unit, tiny_w, out_ids, out_logprobs);
     return hipGetLastError();
 }
 

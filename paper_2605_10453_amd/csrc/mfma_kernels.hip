@@ -131,11 +131,11 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
         float4 *o = reinterpret_cast<float4 *>(t32 + (size_t)row * r + kg * 8);
         o[0] = make_float4(v[0], v[1], v[2], v[3]);
         o[1] = make_float4(v[4], v[5], v[6], v[7]);
-        if (as_bf16) {
+        if (as_bf16 == 1) {
             uint32_t hb[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                // the direct-to-LDS head kernel works in base-2 units: it takes t log2(e)
+                // bf16 operand of the direct-to-LDS head kernel, in base-2 units: t log2(e)
                 const uint32_t u = __float_as_uint(v[e] * kLog2e);
                 hb[e] = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;            // round to nearest even
                 const float dlt = v[e] - __uint_as_float(hb[e] << 16) * kLn2;
@@ -145,11 +145,14 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
             t16[(size_t)kg * rows_pad + row] = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16),
                                                           hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
         } else {
+            // f16 operand: t itself (register-staged kernel) or t log2(e) (direct-to-LDS kernel: base-2 units)
+            const float scale = (as_bf16 == 2) ? kLog2e : 1.0f;
+            const float back = (as_bf16 == 2) ? kLn2 : 1.0f;
             f16x8 hv;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                hv[e] = (_Float16)v[e];
-                const float dlt = v[e] - (float)hv[e];
+                hv[e] = (_Float16)(v[e] * scale);
+                const float dlt = v[e] - (float)hv[e] * back;
                 a += dlt * dlt;
                 b += v[e] * v[e];
             }
@@ -299,11 +302,11 @@ hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, i
 
 hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_pad, int r,
                               float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
-                              bool as_bf16, hipStream_t st)
+                              int xmode, hipStream_t st)
 {
     dim3 grid(rows_pad / 64 + 1, 2 * ((r + 63) / 64));
     down_finish_kernel<<<grid, 256, 0, st>>>(part, slices, rows, rows_pad, r, t32,
-                                             static_cast<uint4 *>(t16), stat, B, V, brms, as_bf16 ? 1 : 0);
+                                             static_cast<uint4 *>(t16), stat, B, V, brms, xmode);
     return hipGetLastError();
 }
 

@@ -7,6 +7,7 @@
 #include <stdlib.h>
 
 using namespace slimspec;
+namespace slimspec { bool head_tile_f16(int k); }
 
 namespace {
 
@@ -78,15 +79,16 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             float *brms = reinterpret_cast<float *>(ws + p.off_brms);
             e = launch_down_gemm(hrow, static_cast<const uint16_t *>(A), down_part, rows, p.rows_pad, d, r, p.slices, p.kslice, s);
             if (e != hipSuccess) return fail_hip(e);
-            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, p.tile, s);
+            const bool tile_f16 = p.tile && head_tile_f16(k);
+            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, p.tile ? (tile_f16 ? 2 : 1) : 0, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-            if (p.tile) e = launch_head_tile(t16, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
+            if (p.tile) e = launch_head_tile(t16, tile_f16, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             else e = launch_head_mfma(static_cast<const uint16_t *>(t16), false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.tile ? 2 : n_wv, p.tile ? 4 : tv, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
-                                     p.tile, p.tile ? 0.6931471805599453f : 1.0f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+                                     p.tile, p.tile ? 0.6931471805599453f : 1.0f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
@@ -94,7 +96,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
-                                     false, 1.0f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+                                     false, 1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         }
     }
@@ -156,6 +158,16 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
 }  // namespace
 
 namespace slimspec {
+bool head_tile_f16(int k) {
+    // The direct-to-LDS kernel takes bf16 operands as they are, or turns the weight tiles into f16 inside LDS and
+    // takes an f16 t (8 times finer).  The conversion costs the projection kernel about 12 %; the finer operand
+    // saves most of the merge's exact re-evaluations, which grow with k: measured break-even at k = 10, 5-9 % of
+    // the call in favour of f16 at k = 16.  Diagnostic override: SLIMSPEC_TILE_OPERAND=bf16|f16.
+    static const char *force = getenv("SLIMSPEC_TILE_OPERAND");
+    if (force && force[0] == 'b') return false;
+    if (force && force[0] == 'f') return true;
+    return k > 12;
+}
 bool head_tile_enabled() {
     // diagnostic switch: SLIMSPEC_HEAD_TILE=0 runs the low-rank head's many-row path on the register-staged kernel
     static const bool on = !(getenv("SLIMSPEC_HEAD_TILE") && getenv("SLIMSPEC_HEAD_TILE")[0] == '0');

@@ -86,7 +86,7 @@ SMALL = [
 
 
 def test_more_rows_than_one_launch(gpu, oracle_mod):
-    """More rows than one launch of the matrix-core kernels takes (4096): the call loops over launches."""
+    """More rows than one launch of the matrix-core kernels takes (512): the call loops over launches; the last has 4 rows."""
     x = synth.make_inputs(synth.small_config(4100, 64, 32, 1032, 5, peaked_every=7), seed=4100)
     check_low_rank(gpu, oracle_mod, x, 5)
 
