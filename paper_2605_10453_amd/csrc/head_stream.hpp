@@ -1,4 +1,4 @@
-// Per-lane stream bookkeeping shared by the matrix-core head kernels: every lane keeps, for each
+// Per-lane stream bookkeeping of the matrix-core head kernel: every lane keeps, for each
 // row it owns, a running max / sum of exp and the L largest "group maxima" of its share of the
 // vocabulary (a group = the 16 logits of one row that one 32x32 MFMA tile gives a lane).
 #pragma once
@@ -29,48 +29,6 @@ __device__ __forceinline__ void stream_init(Stream<L> &st) {
     for (int l = 0; l < L; ++l) { st.x[l] = kNegBig; st.y[l] = kNegBig; st.tag[l] = 0; }
 }
 
-// Fold one group (16 logits of one row) into the stream.
-template <int L>
-__device__ __forceinline__ void stream_group(Stream<L> &st, const float (&v)[16], int tag)
-{
-    float p[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) p[i] = __uint_as_float((__float_as_uint(v[i]) & 0xfffffff0u) | (uint32_t)i);
-    // largest and second largest of the 16 tagged values
-    float a[8], b[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) { a[q] = vmax(p[2 * q], p[2 * q + 1]); b[q] = vmin(p[2 * q], p[2 * q + 1]); }
-#pragma unroll
-    for (int w = 4; w >= 1; w >>= 1)
-#pragma unroll
-        for (int q = 0; q < w; ++q) {
-            float hi = vmax(a[2 * q], a[2 * q + 1]);
-            float lo = vmed3(a[2 * q], a[2 * q + 1], vmax(b[2 * q], b[2 * q + 1]));
-            a[q] = hi; b[q] = lo;
-        }
-    float gm = a[0], g2 = b[0];
-
-    // running log-sum-exp (base 2 inside)
-    const float mc_new = vmax(st.mc, gm * kLog2e);
-    float sum = st.s * __builtin_amdgcn_exp2f(st.mc - mc_new);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(v[i], kLog2e, -mc_new));
-    st.s = sum;
-    st.mc = mc_new;
-
-    // keep the L groups with the largest maxima
-    int tg = tag;
-#pragma unroll
-    for (int l = 0; l < L; ++l) {
-        const bool c = gm > st.x[l];
-        const float nx = c ? gm : st.x[l], ny = c ? g2 : st.y[l];
-        const int nt = c ? tg : st.tag[l];
-        gm = c ? st.x[l] : gm; g2 = c ? st.y[l] : g2; tg = c ? st.tag[l] : tg;
-        st.x[l] = nx; st.y[l] = ny; st.tag[l] = nt;
-    }
-    st.U = vmax(st.U, gm);
-}
-
 __device__ __forceinline__ float vmax3(float a, float b, float c) { float d; asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c)); return d; }
 
 // Largest and second largest of 16 values in 20 instructions: five triples (max3 / med3), then
@@ -90,7 +48,8 @@ __device__ __forceinline__ void top2_of_16(const float (&p)[16], float &hi, floa
 // Fold one group into the stream when the 16 values are base-2 logits RELATIVE to `ref` (the accumulators
 // were started at -ref): the sum of 2^v needs no subtraction; the group's top two go back to absolute
 // values for the list.  The caller rescales st.s and moves st.mc once per tile (see tile_max).
-template <int L>
+// NAT: the values are natural-log logits (the operand was not pre-multiplied by log2 e): one multiply more.
+template <int L, bool NAT>
 __device__ __forceinline__ void stream_group_rel(Stream<L> &st, const float (&v)[16], float ref, float &tile_max, int tag)
 {
     float p[16];
@@ -101,7 +60,7 @@ __device__ __forceinline__ void stream_group_rel(Stream<L> &st, const float (&v)
     __builtin_amdgcn_sched_barrier(0);          // the tagged copies are dead before the exponentials start
     float sum = st.s;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(v[i]);
+    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(NAT ? v[i] * kLog2e : v[i]);
     st.s = sum;
     float gm = __uint_as_float((__float_as_uint(gr + ref) & 0xfffffff0u) | (__float_as_uint(gr) & 15u));
     float g2 = g2r + ref;

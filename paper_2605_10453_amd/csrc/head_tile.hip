@@ -81,12 +81,13 @@ __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)
 
 }  // namespace
 
-// X: [8 ceil(K / 64)][rows_pad] 16-byte vectors: 8 consecutive contraction elements of one row, bf16, times
-//    log2(e), zero beyond K; rows_pad a multiple of 64 WR
+// X: [8 ceil(K / 64)][rows_pad] 16-byte vectors: 8 consecutive contraction elements of one row, zero beyond K and
+//    beyond the last row; rows_pad a multiple of 64 WR.  NAT = false: the contraction input times log2(e), bf16
+//    (F16: f16): logits come out in base-2 units.  NAT = true: the bf16 input itself (full head): natural units.
 // M: [K][V] bf16 row-major, V and K multiples of 8
 // part: [rows][gw][3 + 3 L] stream records (values in base-2 units): one per row and block
 // DBG != 0: timing experiments (1 no epilogue, 2 loads only, 3 no loads); results are meaningless
-template <int L, int WR, bool F16, int DBG>
+template <int L, int WR, bool F16, bool NAT, int DBG>
 __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
     const uint4 *__restrict__ X, const uint16_t *__restrict__ M, float *__restrict__ part,
     int rows, int rows_pad, int K, int V, HeadGrid hg)
@@ -345,13 +346,13 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
                         float v[16];
 #pragma unroll
                         for (int i = 0; i < 16; ++i) v[i] = acc[rt][jj][i];
-                        stream_group_rel<L>(st[rt], v, ref, tile_max, c_vt * 8 + 4 * wv + jj);
+                        stream_group_rel<L, NAT>(st[rt], v, ref, tile_max, c_vt * 8 + 4 * wv + jj);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     // the first tile's reference is its own maximum (-1e30 and an empty sum if every column was
                     // masked: the vocabulary's last tile); later tiles move the reference up when they exceed it
                     const float mc_new = first ? ref : vmax(ref, tile_max);
-                    if (!first) st[rt].s *= __builtin_amdgcn_exp2f(ref - mc_new);
+                    if (!first) st[rt].s *= __builtin_amdgcn_exp2f(NAT ? (ref - mc_new) * kLog2e : ref - mc_new);
                     st[rt].mc = mc_new;
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj)
@@ -383,6 +384,7 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
         Stream<L> &a = st[rt];
+        if (NAT) a.mc *= kLog2e;                                        // records carry the running maximum in base-2 units
 #pragma unroll
         for (int l = 0; l < L; ++l) a.tag[l] = a.tag[l] * 2 + half;
         Stream<L> o;
@@ -421,17 +423,35 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
     }
 }
 
+// Row-major bf16 rows [rows, K] -> the X layout of head_tile_kernel (zero beyond K and beyond the last row).
+// grid = (rows_pad / 64, 8 ceil(K / 64)); one thread per 16-byte vector.
+__global__ __launch_bounds__(64) void regroup_rows_kernel(const uint16_t *__restrict__ h, uint4 *__restrict__ X,
+                                                          int rows, int rows_pad, int K)
+{
+    const int row = blockIdx.x * 64 + threadIdx.x, kg = blockIdx.y;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (row < rows && kg * 8 < K) v = *reinterpret_cast<const uint4 *>(h + (size_t)row * K + kg * 8);       // K is a multiple of 8
+    X[(size_t)kg * rows_pad + row] = v;
+}
+
+hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pad, int K, hipStream_t st)
+{
+    dim3 grid(rows_pad / 64, 8 * ((K + 63) / 64));
+    regroup_rows_kernel<<<grid, 64, 0, st>>>(h, static_cast<uint4 *>(X), rows, rows_pad, K);
+    return hipGetLastError();
+}
+
 int head_tile_rows_per_block(int rows) {
     static const bool small = getenv("SLIMSPEC_TILE128") != nullptr;      // experiment switch
     return (rows > 128 && !small) ? 256 : 128;
 }
 
-template <int WR, bool F16, int DBG>
+template <int WR, bool F16, bool NAT, int DBG>
 static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part, int rows, int rows_pad,
                                   int K, int V, int n_rb, int gw, hipStream_t st)
 {
     using S = TileShape<WR>;
-    auto fn = head_tile_kernel<kStreamList, WR, F16, DBG>;
+    auto fn = head_tile_kernel<kStreamList, WR, F16, NAT, DBG>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
     if (e != hipSuccess) return e;
     HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT};
@@ -439,14 +459,15 @@ static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part,
     return hipGetLastError();
 }
 
-hipError_t launch_head_tile(const void *X, bool x_is_f16, const uint16_t *M, float *part, int rows, int rows_pad,
+hipError_t launch_head_tile(const void *X, bool x_is_f16, bool natural_units, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st)
 {
     static const int dbg = getenv("SLIMSPEC_DBG") ? atoi(getenv("SLIMSPEC_DBG")) : 0;
     const bool big = head_tile_rows_per_block(rows) == 256;
-#define SLIMSPEC_TILE_F(F16, DBG) (big ? launch_tile_cfg<4, F16, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st) \
-                                       : launch_tile_cfg<2, F16, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
-#define SLIMSPEC_TILE(DBG) (x_is_f16 ? SLIMSPEC_TILE_F(true, DBG) : SLIMSPEC_TILE_F(false, DBG))
+#define SLIMSPEC_TILE_F(F16, NAT, DBG) (big ? launch_tile_cfg<4, F16, NAT, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st) \
+                                            : launch_tile_cfg<2, F16, NAT, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
+#define SLIMSPEC_TILE(DBG) (natural_units ? SLIMSPEC_TILE_F(false, true, DBG) \
+                                          : (x_is_f16 ? SLIMSPEC_TILE_F(true, false, DBG) : SLIMSPEC_TILE_F(false, false, DBG)))
     if (dbg == 1) return SLIMSPEC_TILE(1);
     if (dbg == 2) return SLIMSPEC_TILE(2);
     if (dbg == 3) return SLIMSPEC_TILE(3);

@@ -27,31 +27,31 @@ hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int 
 constexpr int kStreamList = 3;          // groups kept per lane stream
 constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial
 
-int mfma_cols_per_wave(int rows);       // MFMA tiles (of the 8 in a 256-wide tile) owned by one wavefront
-
 // partial sums of t = h A over `slices` slices of d (kslice entries each, a multiple of 64)
 hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int rows_pad, int d, int r,
                             int slices, int kslice, hipStream_t st);
-// slices -> fp32 t, f16 t (k-grouped), per-row rounding statistics, rms estimate of B
+// slices -> fp32 t, the 16-bit operand t log2(e) (bf16, or f16 when as_f16) in the k-grouped layout of
+// head_tile_kernel, per-row rounding statistics, rms estimate of B
 hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_pad, int r,
                               float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *brms,
-                              int xmode, hipStream_t st);   // xmode 0: f16 t; 1: bf16 t log2(e); 2: f16 t log2(e)
-// vocabulary projection with the fused epilogue; X is f16 k-grouped (x_row_major = false, M converted to
-// f16 on the fly) or bf16 row-major [rows, K] (x_row_major = true, bf16 MFMA)
-hipError_t launch_head_mfma(const uint16_t *X, bool x_row_major, const uint16_t *M, float *part,
-                            int rows, int rows_pad, int K, int V, int n_rb, int gw, hipStream_t st);
+                              bool as_f16, hipStream_t st);
 
-// the same projection from stages loaded straight into LDS; X is bf16 in 16-byte vectors of 8 contraction
+// vocabulary projection with the fused epilogue, stages loaded straight into LDS; X is 16-byte vectors of 8 contraction
 // elements, [ceil(K / 64) * 8][rows_pad], rows_pad a multiple of 128; columns of an MFMA tile are contiguous
 // x_is_f16: X holds f16 t log2(e) and the kernel turns the M tiles into f16 inside LDS (an 8 times
 // finer operand than bf16); otherwise X holds bf16 t log2(e)
-hipError_t launch_head_tile(const void *X, bool x_is_f16, const uint16_t *M, float *part, int rows, int rows_pad,
+// natural_units: X holds the bf16 contraction input itself (full head) and the records carry natural-log values
+hipError_t launch_head_tile(const void *X, bool x_is_f16, bool natural_units, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st);
+// bf16 rows [rows, K] -> that X layout ([8 ceil(K / 64)][rows_pad] 16-byte vectors, zero padded)
+hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pad, int K, hipStream_t st);
 
 // stream partials -> final ids / log-probabilities, with exact fp32 re-evaluation of uncertain ranks
-hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
+// nsr records per row (= gw, the number of vocabulary-tile columns of the head kernel's grid); unit: factor from the
+// records' values to natural-log logits; tiny_w: magnitude below which the kernel flushed weights to zero
+hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                bool contiguous_tiles, float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, hipStream_t st);
+                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, hipStream_t st);
 
 }  // namespace slimspec

@@ -1,5 +1,5 @@
-// Merge for the matrix-core path: one block per row turns the row's lane-stream partials
-// (see mfma_kernels.hip) into the final top-k ids and log-probabilities.
+// Merge for the matrix-core path: one block per row turns the row's stream records (one per block of
+// head_tile_kernel that worked on the row, see head_tile.hip) into the final top-k ids and log-probabilities.
 //
 // What a stream tells about its share of the row's logits (all values as computed by the
 // matrix cores, i.e. with a 16-bit contraction input in the low-rank head):
@@ -65,11 +65,11 @@ __device__ __forceinline__ void rank_all_pairs(const uint64_t *keys, int n, int 
 }  // namespace
 
 __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
-    const float *__restrict__ part, int nsr, int gw, int n_wv, int tv, int n_vt,
+    const float *__restrict__ part, int nsr, int gw, int n_vt,
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ brms,
-    int k, int contig, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+    int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -232,10 +232,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         if (slot < (uint32_t)kWorkCap) { w_id[slot] = id; w_val[slot] = val; w_need[slot] = need; w_apx[slot] = 0.f; }
         if (need) atomicAdd(&cnt_hidden, 1u);
     };
-    // column of member i of a group: an MFMA tile covers 32 adjacent columns (contig) or every eighth column
+    // column of member i of a group: MFMA tile (tag & 7) of vocabulary tile (tag >> 3) covers 32 adjacent columns
     auto id_of = [&](int tag, int i, int half) {
         const int pos = 8 * (i >> 2) + 4 * half + (i & 3);
-        return (tag >> 3) * 256 + (contig ? 32 * (tag & 7) + pos : 8 * pos + (tag & 7));
+        return (tag >> 3) * 256 + 32 * (tag & 7) + pos;
     };
     if (!exhaustive) {
         for (int sidx = tid; sidx < nsr; sidx += NT) {
@@ -246,9 +246,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             for (int l = 0; l < L; ++l) {
                 const float x = r[3 + 3 * l], y = r[4 + 3 * l];
                 const int rawtag = __float_as_int(r[5 + 3 * l]);
-                // direct-to-LDS kernel: one stream per block, the tag's lowest bit names the half-wavefront
-                const int half = contig ? (rawtag & 1) : (sidx & 1);
-                const int tag = contig ? (rawtag >> 1) : rawtag;
+                // the tag's lowest bit names the half-wavefront that held the group
+                const int half = rawtag & 1, tag = rawtag >> 1;
                 listed[l] = (x > kNoValue) ? rawtag : -1;
                 if (!(x > kNoValue) || !(mask4(x) * unit >= theta)) continue;
                 const int imax = (int)(__float_as_uint(x) & 15u);
@@ -262,15 +261,12 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             }
             const float U = r[2];
             if (U > kNoValue && mask4(U) * unit >= theta) {
-                // every unlisted group of the stream
-                const int wv = contig ? 0 : (sidx >> 1) % n_wv, col = contig ? sidx : (sidx >> 1) / n_wv;
-                const int j0 = contig ? 0 : wv * tv, j1 = contig ? 8 : wv * tv + tv;
-                const int h0 = contig ? 0 : (sidx & 1), h1 = contig ? 2 : (sidx & 1) + 1;
-                for (int vt = col; vt < n_vt; vt += gw)
-                    for (int j = j0; j < j1; ++j)
-                        for (int half = h0; half < h1; ++half) {
+                // every unlisted group of the stream: record sidx covers vocabulary tiles sidx, sidx + gw, ...
+                for (int vt = sidx; vt < n_vt; vt += gw)
+                    for (int j = 0; j < 8; ++j)
+                        for (int half = 0; half < 2; ++half) {
                             const int tag = vt * 8 + j;
-                            const int rawtag = contig ? tag * 2 + half : tag;
+                            const int rawtag = tag * 2 + half;
                             bool is_listed = false;
 #pragma unroll
                             for (int l = 0; l < L; ++l) is_listed |= (listed[l] == rawtag);
@@ -443,17 +439,17 @@ size_t merge_streams_lds_bytes(int nsr, int k) {
     return sizeof(uint64_t) * (n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k + kWorkCap) + 16u * kWorkCap;
 }
 
-hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_wv, int tv, int n_vt,
+hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                bool contiguous_tiles, float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, hipStream_t st)
+                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_wv, tv, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, brms, k, contiguous_tiles ? 1 : 0, unit, tiny_w, out_ids, out_logprobs);
+    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
+                                                           M, K, V, stat, n_stat, rows_pad, brms, k, unit, tiny_w, out_ids, out_logprobs);
     return hipGetLastError();
 }
 

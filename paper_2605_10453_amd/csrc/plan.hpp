@@ -81,18 +81,14 @@ constexpr int kPlanSlotsPerXcd = 32;     // blocks per XCD of the persistent ker
 constexpr int kStreamListPlan = 3;       // must equal kStreamList (launch.hpp)
 constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
 
-int mfma_rows_per_tile(int rows);
-bool head_tile_enabled();
 int head_tile_rows_per_block(int rows);
-int mfma_streams_per_block(int rows);
 
 struct MfmaPlan {
     int rows = 0, rows_pad = 0, rt = 0, n_rb = 0, gw = 0, nsr = 0, n_vt = 0;
-    bool tile = false;                   // direct-to-LDS kernel: 128-row tiles, two blocks per CU
     int slices = 0, kslice = 0;          // down-projection split of d
     size_t off_down_part = 0;            // fp32 [slices, r, rows_pad]
     size_t off_t32 = 0;                  // fp32 [rows_pad, r]
-    size_t off_t16 = 0;                  // 16-byte vectors [8 ceil(r / 64), rows_pad]
+    size_t off_t16 = 0;                  // 16-byte vectors [8 ceil(K / 64), rows_pad]: the head kernel's row operand
     size_t off_stat = 0;                 // float2 [2 ceil(r / 64), rows_pad]
     size_t off_brms = 0;                 // float
     size_t off_streams = 0;              // fp32 [rows, nsr, kStreamRec]
@@ -103,17 +99,16 @@ struct MfmaPlan {
 inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
     MfmaPlan p;
     p.rows = rows;
-    p.tile = head_tile_enabled() && kind == HeadKind::LowRank;
-    p.rt = p.tile ? head_tile_rows_per_block(rows) : mfma_rows_per_tile(rows);
+    p.rt = head_tile_rows_per_block(rows);
     p.n_rb = (rows + p.rt - 1) / p.rt;
     p.rows_pad = p.n_rb * p.rt;
     p.n_vt = (V + 255) / 256;
-    int colgroups = ((p.tile && p.rt == 128) ? 2 : 1) * kPlanSlotsPerXcd / p.n_rb;      // 128-row blocks: two per CU
+    int colgroups = (p.rt == 128 ? 2 : 1) * kPlanSlotsPerXcd / p.n_rb;      // 128-row blocks: two per CU
     if (colgroups < 1) colgroups = 1;
     const int need = (p.n_vt + 7) / 8;
     if (colgroups > need) colgroups = need;
     p.gw = 8 * colgroups;
-    p.nsr = p.gw * (p.tile ? 1 : mfma_streams_per_block(rows));      // the direct-to-LDS kernel folds a block's streams of a row into one
+    p.nsr = p.gw;          // the head kernel folds a block's streams of a row into one record
     size_t off = 0;
     if (kind == HeadKind::LowRank) {
         const int tiles = ((r + 255) / 256) * ((rows + 63) / 64);
@@ -127,6 +122,8 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
         p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((r + 63) / 64 * 64));
         p.off_stat = off;      off = align_up(off + 2 * sizeof(float) * (size_t)p.rows_pad * 2 * ((r + 63) / 64));
         p.off_brms = off;      off = align_up(off + sizeof(float));
+    } else {
+        p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((d + 63) / 64 * 64));      // h regrouped for the kernel
     }
     p.off_streams = off;       off = align_up(off + sizeof(float) * (size_t)rows * p.nsr * kStreamRecPlan);
     p.bytes = off;

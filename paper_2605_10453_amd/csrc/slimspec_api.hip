@@ -68,7 +68,6 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
         const MfmaPlan p = make_mfma_plan(kind, rows, d, r, V);
         float *streams = reinterpret_cast<float *>(ws + p.off_streams);
         const uint16_t *hrow = hb + (size_t)row0 * d;
-        const int n_wv = mfma_streams_per_block(rows) / 2, tv = mfma_cols_per_wave(rows);
         hipError_t e;
         const bool timed = g_ev_start && row0 == 0;
         if (kind == HeadKind::LowRank) {
@@ -79,24 +78,27 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             float *brms = reinterpret_cast<float *>(ws + p.off_brms);
             e = launch_down_gemm(hrow, static_cast<const uint16_t *>(A), down_part, rows, p.rows_pad, d, r, p.slices, p.kslice, s);
             if (e != hipSuccess) return fail_hip(e);
-            const bool tile_f16 = p.tile && head_tile_f16(k);
-            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, p.tile ? (tile_f16 ? 2 : 1) : 0, s);
+            const bool tile_f16 = head_tile_f16(k);
+            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, tile_f16, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-            if (p.tile) e = launch_head_tile(t16, tile_f16, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
-            else e = launch_head_mfma(static_cast<const uint16_t *>(t16), false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
+            e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.tile ? 2 : n_wv, p.tile ? 4 : tv, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
-                                     p.tile, p.tile ? 0.6931471805599453f : 1.0f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+            // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
+                                     0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
+            // the full head runs the same kernel on h itself (bf16 exact, natural units): no rounding statistics
+            void *hx = ws + p.off_t16;
+            if ((e = launch_regroup_rows(hrow, hx, rows, p.rows_pad, d, s)) != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-            e = launch_head_mfma(hrow, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, s);
+            e = launch_head_tile(hx, false, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, n_wv, tv, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
-                                     false, 1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
+                                     1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, s);
             if (e != hipSuccess) return fail_hip(e);
         }
     }
@@ -167,11 +169,6 @@ bool head_tile_f16(int k) {
     if (force && force[0] == 'b') return false;
     if (force && force[0] == 'f') return true;
     return k > 12;
-}
-bool head_tile_enabled() {
-    // diagnostic switch: SLIMSPEC_HEAD_TILE=0 runs the low-rank head's many-row path on the register-staged kernel
-    static const bool on = !(getenv("SLIMSPEC_HEAD_TILE") && getenv("SLIMSPEC_HEAD_TILE")[0] == '0');
-    return on;
 }
 }  // namespace slimspec
 
