@@ -85,15 +85,26 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
     if ((int)blockIdx.x * 64 >= rows_pad) {
         if (blockIdx.y != 0) return;
         // sample: 8 adjacent entries of every row of B at a few column positions spread over V
+        // (the sample is cold in HBM: eight independent loads per thread at a time, not one after the other)
         float a = 0.f;
-        for (int q = tid; q < r * kBrmsPositions; q += 256) {
-            const int j = q / kBrmsPositions, pos = q % kBrmsPositions;
-            const int col = (int)(((long long)pos * (V / 8)) / kBrmsPositions) * 8;
-            const uint4 w = *reinterpret_cast<const uint4 *>(B + (size_t)j * V + col);
-            const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
-                                bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+        const int n_sample = r * kBrmsPositions;
+        for (int q0 = tid; q0 < n_sample; q0 += 8 * 256) {
+            uint4 w[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) a += f[e] * f[e];
+            for (int u = 0; u < 8; ++u) {
+                const int q = min(q0 + u * 256, n_sample - 1);
+                const int j = q / kBrmsPositions, pos = q % kBrmsPositions;
+                const int col = (int)(((long long)pos * (V / 8)) / kBrmsPositions) * 8;
+                w[u] = *reinterpret_cast<const uint4 *>(B + (size_t)j * V + col);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (q0 + u * 256 >= n_sample) continue;
+                const float f[8] = {bf16_lo(w[u].x), bf16_hi(w[u].x), bf16_lo(w[u].y), bf16_hi(w[u].y),
+                                    bf16_lo(w[u].z), bf16_hi(w[u].z), bf16_lo(w[u].w), bf16_hi(w[u].w)};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a += f[e] * f[e];
+            }
         }
         a = wave_sum(a);
         if (lane == 0) red_a[kgl][0] = a;
@@ -110,10 +121,23 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = 0.f;
         if (row < rows) {
-            for (int s = 0; s < slices; ++s) {                // fixed order
-                const float *src = part + ((size_t)s * r + kg * 8) * rows_pad + row;
+            // fixed order of the adds; the loads of 16 slices are in flight together (they come from the
+            // memory-side cache: a round trip per slice would cost more than the sums)
+            constexpr int SB = 16;
+            for (int s0 = 0; s0 < slices; s0 += SB) {
+                float w[SB][8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] += src[(size_t)e * rows_pad];
+                for (int u = 0; u < SB; ++u) {
+                    const float *src = part + ((size_t)min(s0 + u, slices - 1) * r + kg * 8) * rows_pad + row;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) w[u][e] = src[(size_t)e * rows_pad];
+                }
+#pragma unroll
+                for (int u = 0; u < SB; ++u)
+                    if (s0 + u < slices) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] += w[u][e];
+                    }
             }
         }
         float4 *o = reinterpret_cast<float4 *>(t32 + (size_t)row * r + kg * 8);
