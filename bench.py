@@ -257,6 +257,7 @@ def main():
                               "paper_relative_head_time_r_d8": 0.21,
                               "paper_hardware": "NVIDIA H200, vLLM 0.17.1 (context only; the paper's head time "
                                                 "excludes softmax / top-k)"}
+        w_bits = xf.W
         del xf
         torch.cuda.empty_cache()
         # six head calls (the paper's six draft steps, section 5.1) captured in one HIP graph: no host launch jitter
@@ -303,6 +304,17 @@ def main():
             extra["C4_512_rows"] = {"us_per_call": ms4 * 1e3, "rows_per_s": c4.rows / (ms4 * 1e-3),
                                     "mfma_frac_call": fl4 / (ms4 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
                                     "roofline": r4}
+            if c4.d == cfg.d and c4.V == cfg.V:
+                # the full head on the same 512 rows (same kernel, contraction length d): the comparison of section 4.1
+                import types
+                log("[bench] full head, 512 rows")
+                sf = 12
+                fdt4, fk4 = time_full(c4, types.SimpleNamespace(h=x4.h, W=w_bits), sf, 3, 2)
+                fms4 = fdt4 / sf * 1e3
+                rf4 = roofline_of(c4, c4.d, fk4, null_ms)
+                extra["C4_512_rows"]["full_head"] = {"us_per_call": fms4 * 1e3, "projection_kernel_us": fk4 * 1e3,
+                                                     "roofline_frac_kernel": rf4["frac"], "bound": rf4["bound"],
+                                                     "low_rank_speedup": fms4 / ms4}
         out["extra"] = extra
 
     print(json.dumps(out), flush=True)

@@ -102,15 +102,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
 
     // a stream record as three 16-byte loads; the thread's first stream stays in registers
     static_assert(REC == 12, "three float4 per record");
-    float4 mine_rec[3];
-    {
-        const float4 *src = reinterpret_cast<const float4 *>(rec + (size_t)min(tid, nsr - 1) * REC);
-        mine_rec[0] = src[0]; mine_rec[1] = src[1]; mine_rec[2] = src[2];
-    }
+    typedef float f32x4 __attribute__((ext_vector_type(4)));      // native vectors stay in registers (a float4 array did not)
+    const f32x4 *mine_src = reinterpret_cast<const f32x4 *>(rec + (size_t)min(tid, nsr - 1) * REC);
+    const f32x4 mine0 = mine_src[0], mine1 = mine_src[1], mine2 = mine_src[2];
     auto load_rec = [&](int sidx, float (&f)[REC]) {
-        float4 a = mine_rec[0], b = mine_rec[1], c = mine_rec[2];
+        f32x4 a = mine0, b = mine1, c = mine2;
         if (sidx != tid) {
-            const float4 *src = reinterpret_cast<const float4 *>(rec + (size_t)sidx * REC);
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(rec + (size_t)sidx * REC);
             a = src[0]; b = src[1]; c = src[2];
         }
         f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
@@ -298,15 +296,17 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         __syncthreads();
         TRACE2(6);
         // list the items to evaluate (any order: every result goes back to its own slot)
-        int my_need[(kWorkCap + NT - 1) / NT];
-        int n_mine = 0;
-        for (int c = tid; c < n_work; c += NT) my_need[n_mine++] = w_need[c] ? (c | (w_need[c] == 2 ? kListedBit : 0)) : -1;
-        __syncthreads();
-        n_mine = 0;
-        for (int c = tid; c < n_work; c += NT) {
-            const int item = my_need[n_mine++];
-            if (item >= 0) w_need[atomicAdd(&cnt_need, 1u)] = item;
+        constexpr int PER = (kWorkCap + NT - 1) / NT;       // fixed trip count: the array stays in registers
+        int my_need[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT;
+            my_need[i] = (c < n_work && w_need[c]) ? (c | (w_need[c] == 2 ? kListedBit : 0)) : -1;
         }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (my_need[i] >= 0) w_need[atomicAdd(&cnt_need, 1u)] = my_need[i];
         __syncthreads();
         // exact fp32 logits, 16 columns at a time: a lane owns (column lane % 16, row phase lane / 16), the
         // four wavefronts interleave rows, so one load instruction touches 4 rows of M x 16 columns and the

@@ -105,16 +105,18 @@ def test_product_path_does_not_touch_the_checker():
             assert "paper_2605_10453_amd" not in text and "libslimspec" not in text
 
 
-def test_direct_to_lds_kernel_does_not_spill():
+@pytest.mark.parametrize("source,kernel", [("head_tile.hip", "head_tile_kernel"), ("merge_streams.hip", "merge_streams_kernel")])
+def test_kernels_use_no_scratch_memory(source, kernel):
     """head_tile_kernel counts its own vector-memory loads (s_waitcnt vmcnt(N)); a register spill would add
-    loads the count does not know about.  The compiler must report no scratch for every instance of it."""
+    loads the count does not know about.  merge_streams_kernel once kept a small array in scratch memory, which
+    cost 12 MB of writes per 512-row call.  The compiler must report no scratch for every instance of either."""
     import shutil
     import subprocess
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     if not (os.path.exists(hipcc) or shutil.which(hipcc)):
         pytest.skip("hipcc not available")
     from paper_2605_10453_amd import build as build_mod
-    src = os.path.join(build_mod.CSRC, "head_tile.hip")
+    src = os.path.join(build_mod.CSRC, source)
     flags = [f for f in build_mod.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
     out = subprocess.run([hipcc, *flags, "--cuda-device-only", "-c", src, "-o", os.devnull,
                           "-Rpass-analysis=kernel-resource-usage"], capture_output=True, text=True)
@@ -122,6 +124,6 @@ def test_direct_to_lds_kernel_does_not_spill():
     text = out.stderr
     names = re.findall(r"Function Name: (\S+)", text)
     scratch = re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", text)
-    tiles = [(n, int(sz)) for n, sz in zip(names, scratch) if "head_tile_kernel" in n]
-    assert len(tiles) >= 2, text[-2000:]
-    assert all(sz == 0 for _, sz in tiles), tiles
+    found = [(n, int(sz)) for n, sz in zip(names, scratch) if kernel in n]
+    assert len(found) >= 1, text[-2000:]
+    assert all(sz == 0 for _, sz in found), found
