@@ -308,8 +308,8 @@ def main():
                 # the full head on the same 512 rows (same kernel, contraction length d): the comparison of section 4.1
                 import types
                 log("[bench] full head, 512 rows")
-                sf = 12
-                fdt4, fk4 = time_full(c4, types.SimpleNamespace(h=x4.h, W=w_bits), sf, 3, 2)
+                sf = 40          # (the first calls after idle run at lower clocks: ten warm-up calls)
+                fdt4, fk4 = time_full(c4, types.SimpleNamespace(h=x4.h, W=w_bits), sf, 10, 2)
                 fms4 = fdt4 / sf * 1e3
                 rf4 = roofline_of(c4, c4.d, fk4, null_ms)
                 extra["C4_512_rows"]["full_head"] = {"us_per_call": fms4 * 1e3, "projection_kernel_us": fk4 * 1e3,

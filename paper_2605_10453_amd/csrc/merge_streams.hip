@@ -39,6 +39,32 @@ constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evalua
 constexpr float kEpsSigmas = 4.0f;      // eps = this many standard deviations of the rounding error of t
                                         // (values are re-evaluated when within 2 eps = 5.6 sigma of their difference)
 
+// Deferred exact evaluation (long contractions, i.e. the full head).  A column of M is one 2-byte element per row,
+// every row in a cache line and mostly a page of its own; one block (one CU) gets through only about 160 such lines
+// per microsecond, so a row that has to re-evaluate 16 columns over K = 4096 would hold the whole launch up for
+// 25 us per batch.  With a deferral buffer the merge kernel instead parks such a row (its collected set and the
+// list of columns to evaluate), exact_cols_kernel spreads the row's gathers over kDeferSlices blocks, and a second
+// launch of the merge kernel (resume = 1) picks the parked rows up after the evaluation.  Rows whose lists do not
+// fit the buffer are evaluated in place as before.
+constexpr int kDeferNeed = 256;         // columns to evaluate per parked row, at most
+constexpr int kDeferWork = 512;         // collected logits per parked row, at most
+constexpr int kDeferSlices = 16;        // blocks that share one row's gathers (slices of the contraction)
+constexpr int kDeferHeader = 16;        // ints: [0] n_need (0: not parked), [1] n_work, [2] S, [3] Mx, [4] lse (floats)
+constexpr size_t kDeferRowInts = kDeferHeader + kDeferNeed + 2 * kDeferWork + (size_t)kDeferSlices * kDeferNeed;
+
+struct ParkedRow { int *hdr, *need, *id; float *val, *part; };     // part: [kDeferSlices][kDeferNeed]
+__device__ __forceinline__ ParkedRow parked_row(int *defer, int row) {
+    ParkedRow p{nullptr, nullptr, nullptr, nullptr, nullptr};
+    if (defer) {
+        p.hdr = defer + (size_t)row * kDeferRowInts;
+        p.need = p.hdr + kDeferHeader;
+        p.id = p.need + kDeferNeed;
+        p.val = reinterpret_cast<float *>(p.id + kDeferWork);
+        p.part = p.val + kDeferWork;
+    }
+    return p;
+}
+
 __device__ __forceinline__ float mask4(float v) { return __uint_as_float(__float_as_uint(v) & 0xfffffff0u); }
 
 struct RowCtx {
@@ -69,7 +95,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ brms,
-    int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+    int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
+    int *__restrict__ defer, int resume)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -98,7 +125,61 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     ctx.x_is_bf16 = x_is_bf16; ctx.M = M; ctx.K = K; ctx.V = V;
 
     TRACE2(0);
-    if (tid == 0) { tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; cnt_need = 0u; }
+    const ParkedRow pk = parked_row(defer, row);
+    int *const park = pk.hdr, *const park_need = pk.need, *const park_id = pk.id;
+    float *const park_val = pk.val, *const park_part = pk.part;
+
+    // The tail of the row's merge once every collected logit has its final value: rank the collected set, correct
+    // the sum of exp by the changes of the re-evaluated terms (summed in rank order: a fixed order), write.
+    const auto finish = [&](int n_work, float S, float Mx, float lse) {
+        for (int c = tid; c < n_work; c += NT) work[c] = make_key(w_val[c], (uint32_t)w_id[c]);
+        __syncthreads();
+        float *by_rank = reinterpret_cast<float *>(w_need);
+        rank_all_pairs(work, n_work, tid, NT, [&](int c, uint64_t, int rank) {
+            if (rank < k) winners[rank] = (uint32_t)c;
+            by_rank[rank] = w_apx[c];
+        });
+        __syncthreads();
+        TRACE2(8);
+        float corr = 0.f;
+        for (int q = 0; q < n_work; ++q) corr += by_rank[q];
+        const float s_fixed = S + corr;
+        const float lse_fixed = (s_fixed > 0.f) ? (Mx + __builtin_amdgcn_logf(s_fixed)) * kLn2 : lse;
+        if (tid < k) {
+            const uint32_t c = winners[tid];
+            out_ids[(size_t)row * k + tid] = w_id[c];
+            out_logprobs[(size_t)row * k + tid] = w_val[c] - lse_fixed;
+        }
+    };
+    // A listed maximum had its computed value in the streams' sum of exp: remember by how much its term changes.
+    const auto take_exact = [&](int entry, float z, float Mx) {
+        const int item = entry & (kListedBit - 1);
+        if (entry & kListedBit) w_apx[item] = __builtin_amdgcn_exp2f(z * kLog2e - Mx) - __builtin_amdgcn_exp2f(w_val[item] * kLog2e - Mx);
+        w_val[item] = z;
+    };
+
+    if (resume) {
+        // second launch: only rows parked by the first one; their columns have been evaluated in between
+        const int n_need = park[0];
+        if (n_need == 0) return;
+        const int n_work = park[1];
+        const float S = __int_as_float(park[2]), Mx = __int_as_float(park[3]), lse = __int_as_float(park[4]);
+        for (int c = tid; c < n_work; c += NT) { w_id[c] = park_id[c]; w_val[c] = park_val[c]; w_apx[c] = 0.f; }
+        __syncthreads();
+        for (int i = tid; i < n_need; i += NT) {           // every entry names its own item: no two threads share a slot
+            float z = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < kDeferSlices; ++ks) z += park_part[ks * kDeferNeed + i];      // fixed order
+            take_exact(park_need[i], z, Mx);
+        }
+        __syncthreads();
+        finish(n_work, S, Mx, lse);
+        return;
+    }
+    if (tid == 0) {
+        tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; cnt_need = 0u;
+        if (park) park[0] = 0;                              // not parked, unless decided otherwise below
+    }
 
     // a stream record as three 16-byte loads; the thread's first stream stays in registers
     static_assert(REC == 12, "three float4 per record");
@@ -308,6 +389,17 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         for (int i = 0; i < PER; ++i)
             if (my_need[i] >= 0) w_need[atomicAdd(&cnt_need, 1u)] = my_need[i];
         __syncthreads();
+        if (park && cnt_need != 0u && cnt_need <= (uint32_t)kDeferNeed && n_work <= kDeferWork) {
+            // park the row: collected set, list of columns, the streams' log-sum-exp
+            const int n_need = (int)cnt_need;
+            for (int c = tid; c < n_work; c += NT) { park_id[c] = w_id[c]; park_val[c] = w_val[c]; }
+            for (int c = tid; c < n_need; c += NT) park_need[c] = w_need[c];
+            if (tid == 0) {
+                park[0] = n_need; park[1] = n_work;
+                park[2] = __float_as_int(S); park[3] = __float_as_int(Mx); park[4] = __float_as_int(lse);
+            }
+            return;
+        }
         // exact fp32 logits, 16 columns at a time: a lane owns (column lane % 16, row phase lane / 16), the
         // four wavefronts interleave rows, so one load instruction touches 4 rows of M x 16 columns and the
         // whole block has 16 rows in flight per step; partial sums are combined in a fixed order
@@ -343,34 +435,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 float z = red_ex[0][tid];
 #pragma unroll
                 for (int w = 1; w < NWAVES; ++w) z += red_ex[w][tid];
-                // tid < 16: u == tid, so `item` is this column's slot.  A listed maximum had its computed value
-                // in the streams' sum of exp: remember by how much its term changes
-                if (entry & kListedBit) w_apx[item] = __builtin_amdgcn_exp2f(z * kLog2e - Mx) - __builtin_amdgcn_exp2f(w_val[item] * kLog2e - Mx);
-                w_val[item] = z;
+                take_exact(entry, z, Mx);                 // tid < 16: u == tid, so `entry` is this column's
             }
             __syncthreads();
         }
         __syncthreads();
         TRACE2(7);
-        for (int c = tid; c < n_work; c += NT) work[c] = make_key(w_val[c], (uint32_t)w_id[c]);
-        __syncthreads();
-        // the changes of the re-evaluated terms of the sum of exp, ordered by rank so that their sum has a fixed order
-        float *by_rank = reinterpret_cast<float *>(w_need);
-        rank_all_pairs(work, n_work, tid, NT, [&](int c, uint64_t, int rank) {
-            if (rank < k) winners[rank] = (uint32_t)c;
-            by_rank[rank] = w_apx[c];
-        });
-        __syncthreads();
-        TRACE2(8);
-        float corr = 0.f;
-        for (int q = 0; q < n_work; ++q) corr += by_rank[q];
-        const float s_fixed = S + corr;
-        const float lse_fixed = (s_fixed > 0.f) ? (Mx + __builtin_amdgcn_logf(s_fixed)) * kLn2 : lse;
-        if (tid < k) {
-            const uint32_t c = winners[tid];
-            out_ids[(size_t)row * k + tid] = w_id[c];
-            out_logprobs[(size_t)row * k + tid] = w_val[c] - lse_fixed;
-        }
+        finish(n_work, S, Mx, lse);
         return;
     }
 
@@ -433,6 +504,57 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     }
 }
 
+// Partial exact logits of the parked rows: block (ks, row) covers slice ks of the contraction for every column on
+// the row's list, 16 columns at a time (lane = column lane % 16, row phase lane / 16; the four wavefronts interleave
+// rows), and leaves part[ks][i]; the resumed merge adds the slices in order.  Rows that are not parked cost a block
+// one load.
+__global__ __launch_bounds__(256) void exact_cols_kernel(
+    int *__restrict__ defer, const void *__restrict__ xexact, int x_is_bf16, int ldx,
+    const uint16_t *__restrict__ M, int K, int V)
+{
+    const int ks = blockIdx.x, row = blockIdx.y;
+    const ParkedRow pk = parked_row(defer, row);
+    const int n_need = pk.hdr[0];
+    if (n_need == 0) return;
+    RowCtx ctx;
+    ctx.x = x_is_bf16 ? static_cast<const void *>(static_cast<const uint16_t *>(xexact) + (size_t)row * ldx)
+                      : static_cast<const void *>(static_cast<const float *>(xexact) + (size_t)row * ldx);
+    ctx.x_is_bf16 = x_is_bf16; ctx.M = M; ctx.K = K; ctx.V = V;
+    const int per = ((K + kDeferSlices - 1) / kDeferSlices + 15) & ~15;
+    const int kb = min(K, ks * per), ke = min(K, kb + per);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int u = lane & 15, jsub = lane >> 4;
+    __shared__ float red[4][16];
+    for (int g0 = 0; g0 < n_need; g0 += 16) {
+        const int entry = pk.need[min(g0 + u, n_need - 1)];
+        const uint16_t *mcol = M + pk.id[entry & (kListedBit - 1)];
+        float acc = 0.f;
+        constexpr int NB = 16, RSTEP = 16;                 // 16 loads in flight per lane, 16 rows per load instruction of the block
+        for (int j0 = kb + wave * 4 + jsub; j0 < ke; j0 += NB * RSTEP) {
+            uint16_t w[NB];
+#pragma unroll
+            for (int e = 0; e < NB; ++e) w[e] = mcol[(size_t)min(j0 + e * RSTEP, ke - 1) * V];
+#pragma unroll
+            for (int e = 0; e < NB; ++e) {
+                const int j = j0 + e * RSTEP;
+                acc = fmaf(j < ke ? x_at(ctx, j) : 0.f, bf16_to_float(w[e]), acc);
+            }
+        }
+        uint32_t a, b;
+        swap_pair<16>(__float_as_uint(acc), a, b);
+        acc = __uint_as_float(a) + __uint_as_float(b);
+        swap_pair<32>(__float_as_uint(acc), a, b);
+        acc = __uint_as_float(a) + __uint_as_float(b);
+        if (lane < 16) red[wave][lane] = acc;
+        __syncthreads();
+        if (tid < 16 && g0 + tid < n_need)
+            pk.part[ks * kDeferNeed + g0 + tid] = ((red[0][tid] + red[1][tid]) + red[2][tid]) + red[3][tid];
+        __syncthreads();
+    }
+}
+
+size_t merge_defer_bytes(int rows) { return sizeof(int) * kDeferRowInts * (size_t)rows; }
+
 size_t merge_streams_lds_bytes(int nsr, int k) {
     const size_t n = (size_t)nsr * kStreamList;
     const size_t ngroups = ((size_t)nsr + 63) / 64;
@@ -442,14 +564,23 @@ size_t merge_streams_lds_bytes(int nsr, int k) {
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
-                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, hipStream_t st)
+                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, void *defer_buf, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    int *defer = static_cast<int *>(defer_buf);
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, brms, k, unit, tiny_w, out_ids, out_logprobs);
+                                                           M, K, V, stat, n_stat, rows_pad, brms, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           defer, 0);
+    if ((e = hipGetLastError()) != hipSuccess || !defer) return e;
+    // parked rows: their exact columns on many CUs, then the rest of their merge
+    exact_cols_kernel<<<dim3(kDeferSlices, rows), 256, 0, st>>>(defer, xexact, x_is_bf16 ? 1 : 0, ldx, M, K, V);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
+                                                           M, K, V, stat, n_stat, rows_pad, brms, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           defer, 1);
     return hipGetLastError();
 }
 

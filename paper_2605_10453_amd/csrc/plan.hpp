@@ -82,6 +82,8 @@ constexpr int kStreamListPlan = 3;       // must equal kStreamList (launch.hpp)
 constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
 
 int head_tile_rows_per_block(int rows);
+size_t merge_defer_bytes(int rows);
+constexpr int kDeferMinK = 2048;
 
 struct MfmaPlan {
     int rows = 0, rows_pad = 0, rt = 0, n_rb = 0, gw = 0, nsr = 0, n_vt = 0;
@@ -92,6 +94,8 @@ struct MfmaPlan {
     size_t off_stat = 0;                 // float2 [2 ceil(r / 64), rows_pad]
     size_t off_brms = 0;                 // float
     size_t off_streams = 0;              // fp32 [rows, nsr, kStreamRec]
+    size_t off_defer = 0;                // parked rows of the merge (long contractions only; bytes 0 otherwise)
+    bool defer = false;
     size_t bytes = 0;
 };
 
@@ -126,6 +130,9 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
         p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((d + 63) / 64 * 64));      // h regrouped for the kernel
     }
     p.off_streams = off;       off = align_up(off + sizeof(float) * (size_t)rows * p.nsr * kStreamRecPlan);
+    // exact re-evaluations are column gathers of K scattered lines each: from K = 2048 on they go to their own kernel
+    p.defer = (kind == HeadKind::Full ? d : r) >= kDeferMinK;
+    if (p.defer) { p.off_defer = off; off = align_up(off + merge_defer_bytes(rows)); }
     p.bytes = off;
     return p;
 }

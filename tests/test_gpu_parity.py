@@ -113,6 +113,26 @@ def test_full_head_small_many_rows(gpu, oracle_mod, rows, d, r, V, k):
     check_full(gpu, oracle_mod, x.h, x.W, k)
 
 
+@pytest.mark.parametrize("n_tied", [2, 40, 600])
+def test_full_head_long_contraction_exact_reevaluation(gpu, oracle_mod, n_tied):
+    """Full head with d >= 2048 and many rows: rows that need exact re-evaluations are parked by the merge and
+    finished by two more launches.  Exactly tied top columns force the re-evaluation for row 0 (2 and 40 tied
+    columns fit a parked row's list; 600 leave about 400 outside the duplicated block, more than a parked row
+    holds, and are evaluated in place); a duplicated block of columns makes
+    every other row tie at some ranks too."""
+    cfg = synth.small_config(rows=12, d=2048, r=8, V=4104, k=8)
+    x = synth.make_inputs(cfg, 5, with_full_head=True)
+    V = cfg.V
+    x.W[:, 2048:2048 + 1024] = x.W[:, :1024]                    # every row: its best column below 1024 has a twin
+    h0 = synth.bf16_bits_to_f64(x.h[0])
+    cols = sorted(set(int(c) for c in np.linspace(1030, V - 1, n_tied).astype(np.int64)) - set(range(2048, 3072)))
+    synth.plant_identical_columns(x.W, 0.35 * h0 / math.sqrt(cfg.d), cols)
+    g_ids, g_lp, ora = check_full(gpu, oracle_mod, x.h, x.W, cfg.k)
+    n_top = min(len(cols), cfg.k)
+    assert g_ids[0, :n_top].tolist() == cols[:n_top]
+    assert np.array_equal(g_ids, ora.ids)                       # exact values, ties by id: nothing left to the tolerance
+
+
 @pytest.mark.parametrize("rows,k", [(20, 17), (140, 40)])
 def test_many_rows_large_k(gpu, oracle_mod, rows, k):
     """k above the matrix-core path's limit: the call takes the streaming path in row groups."""
