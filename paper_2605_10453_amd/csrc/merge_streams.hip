@@ -46,8 +46,9 @@ constexpr float kEpsSigmas = 4.0f;      // eps = this many standard deviations o
 // list of columns to evaluate), exact_cols_kernel spreads the row's gathers over kDeferSlices blocks, and a second
 // launch of the merge kernel (resume = 1) picks the parked rows up after the evaluation.  Rows whose lists do not
 // fit the buffer are evaluated in place as before.
-constexpr int kDeferNeed = 256;         // columns to evaluate per parked row, at most
-constexpr int kDeferWork = 512;         // collected logits per parked row, at most
+constexpr int kDeferNeed = 1280;        // columns to evaluate per parked row, at most (a whole stream's unlisted groups
+                                        // at the 512-row shape: about 1000)
+constexpr int kDeferWork = 1536;        // collected logits per parked row, at most
 constexpr int kDeferSlices = 16;        // blocks that share one row's gathers (slices of the contraction)
 constexpr int kDeferHeader = 16;        // ints: [0] n_need (0: not parked), [1] n_work, [2] S, [3] Mx, [4] lse (floats)
 constexpr size_t kDeferRowInts = kDeferHeader + kDeferNeed + 2 * kDeferWork + (size_t)kDeferSlices * kDeferNeed;

@@ -113,12 +113,12 @@ def test_full_head_small_many_rows(gpu, oracle_mod, rows, d, r, V, k):
     check_full(gpu, oracle_mod, x.h, x.W, k)
 
 
-@pytest.mark.parametrize("n_tied", [2, 40, 600])
+@pytest.mark.parametrize("n_tied", [2, 40, 600, 2400])
 def test_full_head_long_contraction_exact_reevaluation(gpu, oracle_mod, n_tied):
     """Full head with d >= 2048 and many rows: rows that need exact re-evaluations are parked by the merge and
     finished by two more launches.  Exactly tied top columns force the re-evaluation for row 0 (2 and 40 tied
-    columns fit a parked row's list; 600 leave about 400 outside the duplicated block, more than a parked row
-    holds, and are evaluated in place); a duplicated block of columns makes
+    columns and the about 400 that 600 leave outside the duplicated block fit a parked row's list; 2400 leave
+    about 1600, more than a parked row holds, and are evaluated in place); a duplicated block of columns makes
     every other row tie at some ranks too."""
     cfg = synth.small_config(rows=12, d=2048, r=8, V=4104, k=8)
     x = synth.make_inputs(cfg, 5, with_full_head=True)
