@@ -211,6 +211,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     }
     for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
     __shared__ float stat_sh[64];
+    const float b_rms = (stat != nullptr) ? brms[0] : 0.f;      // asked for early: by the time eps needs it, it has arrived
     if (stat != nullptr && tid < n_stat && tid < 64) stat_sh[tid] = stat[(size_t)tid * rows_pad + row].x;
     const float m_w = wave_max(m_t);
     float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
@@ -298,7 +299,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         float dt2 = 0.f;                                     // squared norm of t - f16(t), summed in a fixed order
         for (int q = 0; q < n_stat; ++q) dt2 += (q < 64) ? stat_sh[q] : stat[(size_t)q * rows_pad + row].x;
         // + weights the kernel flushed to zero (magnitude below tiny_w) times the 1-norm of the contraction input
-        eps = kEpsSigmas * sqrtf(dt2) * brms[0] + fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
+        eps = kEpsSigmas * sqrtf(dt2) * b_rms + fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
     }
     else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
     const float theta = have_tau ? tau - 2.f * eps : kNegInf;
