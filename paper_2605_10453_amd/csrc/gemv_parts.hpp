@@ -210,17 +210,38 @@ __device__ __forceinline__ void merge_row(unsigned char *dyn, bool cache_ids, Me
     const int lane = tid & 63, wave = tid >> 6;
 
     const int n = chunks * k;
-    for (int e = tid; e < n; e += NT) {
-        vals[e] = pv[e];
-        if (cache_ids) ids[e] = pi[e];                  // when they fit: no dependent load at the end
+    // The partials were written by other CUs: every load is a trip to the memory side.  All loads of a thread are
+    // therefore issued before the first of them is used (four list entries per thread and trip, and the first
+    // chunk's head and (max, sum) with them), instead of one trip per loop iteration.
+    const bool own_chunk = tid < chunks;
+    const float head0 = own_chunk ? pv[(size_t)tid * k] : 0.f;
+    const float2 ms0 = own_chunk ? ms[tid] : make_float2(kNegInf, 0.f);
+    for (int e0 = tid; e0 < n; e0 += 4 * NT) {
+        float v[4];
+        int id[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = min(e0 + u * NT, n - 1);
+            v[u] = pv[e];
+            id[u] = cache_ids ? pi[e] : 0;              // when they fit: no dependent load at the end
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * NT;
+            if (e < n) {
+                vals[e] = v[u];
+                if (cache_ids) ids[e] = id[u];
+            }
+        }
     }
     if (tid == 0) { S.bound = kNoKey; S.cnt = 0u; }
 
     // log-sum-exp: every thread folds its chunks in increasing order, then the block combines
     float m_t = kNegInf, s_t = 0.f;
     for (int c = tid; c < chunks; c += NT) {
-        heads[c] = make_key(pv[(size_t)c * k], (uint32_t)(c * k));
-        float2 p = ms[c];
+        const bool first = c == tid;
+        heads[c] = make_key(first ? head0 : pv[(size_t)c * k], (uint32_t)(c * k));
+        float2 p = first ? ms0 : ms[c];
         float m_new = fmaxf(m_t, p.x);
         s_t = s_t * fast_exp(m_t - m_new) + p.y * fast_exp(p.x - m_new);
         m_t = m_new;
@@ -238,13 +259,20 @@ __device__ __forceinline__ void merge_row(unsigned char *dyn, bool cache_ids, Me
     for (int w = 0; w < NWAVES; ++w) Ssum += (S.red_m[w] == kNegInf) ? 0.f : S.red_s[w] * fast_exp(S.red_m[w] - M);
     const float lse = M + fast_log(Ssum);
 
-    // (1) the k-th largest head
-    for (int c = tid; c < chunks; c += NT) {
-        const uint64_t mine = heads[c];
-        int rank = 0;
+    // (1) the k-th largest head: four adjacent lanes share one head, each counts a quarter of the others
+    {
+        const int quarter = (chunks + 3) / 4;
+        const int q0 = (tid & 3) * quarter, q1 = min(chunks, q0 + quarter);
+        for (int c0 = 0; c0 < chunks; c0 += NT / 4) {              // trip count uniform over the block
+            const int c = c0 + (tid >> 2);
+            const uint64_t mine = heads[min(c, chunks - 1)];
+            int rank = 0;
 #pragma unroll 8
-        for (int q = 0; q < chunks; ++q) rank += (heads[q] > mine) ? 1 : 0;
-        if (rank == k - 1) S.bound = mine;              // keys are unique: one writer at most
+            for (int q = q0; q < q1; ++q) rank += (heads[q] > mine) ? 1 : 0;
+            rank += __shfl_xor(rank, 1);
+            rank += __shfl_xor(rank, 2);
+            if (c < chunks && (tid & 3) == 0 && rank == k - 1) S.bound = mine;      // keys are unique: one writer at most
+        }
     }
     __syncthreads();
     const uint64_t bound = S.bound;                     // kNoKey when there are fewer than k lists: keep everything
