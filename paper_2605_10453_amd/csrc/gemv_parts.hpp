@@ -91,21 +91,18 @@ template <int R, int NW>
 struct ChunkLds {
     static constexpr int EW = (R < NW) ? R : NW;
     float red[NW][R][kChunkCols];
-    uint64_t sel_keys[EW][64];
     uint64_t sel_cand[EW][kChunkCols];
-    uint64_t sel_bound[EW];
-    uint32_t sel_cnt[EW];
 };
 
 // Row i of the chunk: fixed-order sum of the NW partial sums, then (max, sum of exp, top-k) of its
 // 512 logits, written as the partial of (row, chunk).  One wavefront; all 64 lanes must call.
 //
-// Top-k in three steps whose cost does not grow with k: the k-th largest of the 64 lane maxima
-// (by all-pairs counting) bounds the answer from below; the few elements that reach the bound
-// are gathered in shared memory; they are ranked among themselves by (logit desc, id asc),
-// again by counting.  Lanes own increasing columns, so ordering lane maxima by (value, lane) is
-// consistent with ordering elements by (value, id): an element below the bound is preceded by
-// k lane maxima.
+// Top-k in three steps whose cost does not grow with k, and which stay inside the wavefront (this is the tail of
+// every block, after its last weight row has arrived: nothing overlaps it).  (1) T = the k-th largest of the 64
+// lane maxima, found bit by bit from the top with one ballot and one population count per bit: an element below
+// T is preceded by k lane maxima, so it cannot be in the top-k.  (2) The elements >= T (k or a few more; all of
+// them when values tie) are compacted into shared memory through ballots and lane prefix counts.  (3) They are
+// ranked among themselves by (logit desc, id asc) by counting.
 template <int R, int NW>
 __device__ __forceinline__ void chunk_row_epilogue(ChunkLds<R, NW> &L, int i, int wave, int lane, bool active,
                                                    int col, int k, size_t slot,
@@ -134,29 +131,26 @@ __device__ __forceinline__ void chunk_row_epilogue(ChunkLds<R, NW> &L, int i, in
     for (int e = 0; e < 8; ++e) s += fast_exp(z[e] - m);     // exp(-inf) = 0 for padding lanes
     s = wave_sum(s);
 
-    // (1) bound: the k-th largest of the 64 lane maxima, as keys (value, lane)
-    uint64_t *lane_keys = L.sel_keys[wave];
+    // (1) T: the largest 32-bit pattern with at least k lane maxima at or above it (0 if fewer than k lanes hold columns)
     uint64_t *cand = L.sel_cand[wave];
-    const uint64_t my_lane_key = active ? make_key(lm, (uint32_t)lane) : kNoKey;
-    lane_keys[lane] = my_lane_key;
-    if (lane == 0) { L.sel_cnt[wave] = 0u; L.sel_bound[wave] = kNoKey; }
-    lds_wave_sync();
-    int rank = 0;
-#pragma unroll 8
-    for (int q = 0; q < 64; ++q) rank += (lane_keys[q] > my_lane_key) ? 1 : 0;
-    if (rank == k - 1 && my_lane_key != kNoKey) L.sel_bound[wave] = my_lane_key;   // keys are unique: one lane at most
-    lds_wave_sync();
-    const uint64_t bound = L.sel_bound[wave];          // kNoKey when fewer than k lanes hold columns: keep everything
-    // (2) every element whose (value, lane) key reaches the bound is a candidate
+    const uint32_t lane_bits = active ? float_order_bits(lm) : 0u;
+    uint32_t T = 0u;
+#pragma unroll
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t trial = T | (1u << bit);
+        if (__popcll(__ballot(lane_bits >= trial)) >= k) T = trial;
+    }
+    // (2) every element at or above T is a candidate; slot = number of candidates before it (element-major, then lane)
+    int n_cand = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        if (active && make_key(z[e], (uint32_t)lane) >= bound) {
-            uint32_t pos = atomicAdd(&L.sel_cnt[wave], 1u);
-            cand[pos] = make_key(z[e], (uint32_t)(col + e));
-        }
+        const bool take = active && float_order_bits(z[e]) >= T;
+        const uint64_t mask = __ballot(take);
+        const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (take) cand[n_cand + before] = make_key(z[e], (uint32_t)(col + e));
+        n_cand += __popcll(mask);
     }
     lds_wave_sync();
-    const int n_cand = (int)L.sel_cnt[wave];
     // (3) rank the candidates among themselves by (value desc, id asc); ranks below k are the answer
     for (int c0 = 0; c0 < n_cand; c0 += 64) {
         const int c = c0 + lane;
