@@ -47,7 +47,7 @@ template <int R, int NW, typename WT, bool SLICES>
 __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     const float *__restrict__ x, int nds, const WT *__restrict__ M,
     float2 *__restrict__ part_ms, float *__restrict__ part_val, int *__restrict__ part_id,
-    int rows_here, int row0, int K, int V, int chunks, int k)
+    int rows_here, int row0, int K, int V, int chunks, int lanes, int k)
 {
     __shared__ ChunkLds<R, NW> L;
     extern __shared__ __align__(16) unsigned char dyn[];         // SLICES: t as fp32 [R][K]
@@ -55,8 +55,8 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int chunk = blockIdx.x;
-    const int col = chunk * kChunkCols + lane * 8;
-    const bool active = col < V;          // V is a multiple of 8: all 8 columns valid or none
+    const int col = (chunk * lanes + lane) * 8;             // the chunk covers 8 * lanes adjacent columns
+    const bool active = lane < lanes && col < V;          // V is a multiple of 8: all 8 columns valid or none
 
     float acc[R][8];
 #pragma unroll
@@ -210,7 +210,7 @@ hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)
 
 template <int R, int NW, typename WT>
 static hipError_t launch_stream(const float *x, int nds, const WT *M, float2 *ms, float *pv, int *pi,
-                                int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st)
+                                int rows_here, int row0, int K, int V, int chunks, int lanes, int k, hipStream_t st)
 {
     if (nds > 0) {
         auto fn = stream_topk_kernel<R, NW, WT, true>;
@@ -219,31 +219,33 @@ static hipError_t launch_stream(const float *x, int nds, const WT *M, float2 *ms
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
             if (e != hipSuccess) return e;
         }
-        fn<<<chunks, NW * 64, dyn, st>>>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k);
+        fn<<<chunks, NW * 64, dyn, st>>>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
     } else {
-        stream_topk_kernel<R, NW, WT, false><<<chunks, NW * 64, 0, st>>>(x, 0, M, ms, pv, pi, rows_here, row0, K, V, chunks, k);
+        stream_topk_kernel<R, NW, WT, false><<<chunks, NW * 64, 0, st>>>(x, 0, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
     }
     return hipGetLastError();
 }
 
 template <typename WT>
 static hipError_t launch_stream_rows(const float *x, int nds, const WT *M, float2 *ms, float *pv, int *pi,
-                                     int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st)
+                                     int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st)
 {
-    // shared memory is NW * R * 2 KB: keep it at 32 KB
-    if (rows_here <= 1) return launch_stream<1, 16, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    if (rows_here <= 2) return launch_stream<2, 8, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    if (rows_here <= 4) return launch_stream<4, 4, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    return launch_stream<8, 2, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+#define SLIMSPEC_STREAM(R, NW) launch_stream<R, NW, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k, st)
+    // shared memory is NW * R * 2 KB: keep it at 32 KB.  One row: the block size the chunk geometry asks for.
+    if (rows_here <= 1) return nw1 == 4 ? SLIMSPEC_STREAM(1, 4) : nw1 == 8 ? SLIMSPEC_STREAM(1, 8) : SLIMSPEC_STREAM(1, 16);
+    if (rows_here <= 2) return SLIMSPEC_STREAM(2, 8);
+    if (rows_here <= 4) return SLIMSPEC_STREAM(4, 4);
+    return SLIMSPEC_STREAM(8, 2);
+#undef SLIMSPEC_STREAM
 }
 
 // nds > 0: x holds nds slices [nds][R][K] of the contraction input (R = 1, 2, 4 or 8 as chosen for rows_here)
 hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_f32, float2 *ms, float *pv, int *pi,
-                              int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st)
+                              int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st)
 {
     if (m_is_f32)
-        return launch_stream_rows<float>(x, nds, (const float *)M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
-    return launch_stream_rows<uint16_t>(x, nds, (const uint16_t *)M, ms, pv, pi, rows_here, row0, K, V, chunks, k, st);
+        return launch_stream_rows<float>(x, nds, (const float *)M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, nw1, k, st);
+    return launch_stream_rows<uint16_t>(x, nds, (const uint16_t *)M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, nw1, k, st);
 }
 
 }  // namespace slimspec

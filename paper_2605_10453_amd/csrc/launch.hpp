@@ -17,7 +17,7 @@ hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)
 // from nds slices of it (the output of launch_down_projection), and M [K, V].
 hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_f32,
                               float2 *part_ms, float *part_val, int *part_id,
-                              int rows_here, int row0, int K, int V, int chunks, int k, hipStream_t st);
+                              int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st);
 
 // Combine the partials of every row into the final ids and log-probabilities.
 hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int *part_id,

@@ -7,7 +7,7 @@
 
 namespace slimspec {
 
-constexpr int kChunkCols = 512;      // vocabulary columns per partial: one wavefront x 8 columns per lane
+constexpr int kChunkCols = 512;      // vocabulary columns per partial at most: one wavefront x 8 columns per lane
 constexpr int kGemvMaxRows = 8;      // rows handled by one pass of the streaming (lane-owns-columns) path
 constexpr int kMergeThreads = 512;    // threads of the stream-merge block of one row
 constexpr int SLIMSPEC_KMAX_INTERNAL = 64;
@@ -34,11 +34,34 @@ inline DownPlan make_down_plan(bool low_rank, int d, int r) {
     return p;
 }
 
+// Geometry of the streaming kernel: a block owns one chunk of 8 * lanes adjacent columns (lanes <= 64 lanes of every
+// wavefront hold columns) and its nw wavefronts split the contraction.  One block of 16 wavefronts fills a CU, so
+// up to 256 chunks run as one round.  A vocabulary with more 512-column chunks than that (151936 columns: 297)
+// would leave 41 CUs with two chunks and the others waiting: for a single row the chunks are instead made narrower
+// and the blocks smaller (8 wavefronts: two blocks share a CU, 512 at once; 4 wavefronts: 1024 at once) so that all
+// of them are resident together and every CU gets the same number of columns within a few per cent.
+struct ChunkGeom { int lanes = 64, nw1 = 16, chunks = 0; };
+inline ChunkGeom make_chunk_geom(int rows, int V) {
+    ChunkGeom g;
+    g.chunks = (V + kChunkCols - 1) / kChunkCols;
+    if (rows == 1 && g.chunks > 256) {
+        const int n16 = (V + 7) / 8;                         // 16-byte column groups
+        const int slots = g.chunks <= 512 ? 512 : 1024;
+        g.nw1 = g.chunks <= 512 ? 8 : 4;
+        if (g.chunks <= slots) {
+            g.lanes = (n16 + slots - 1) / slots;
+            g.chunks = (n16 + g.lanes - 1) / g.lanes;
+        }
+    }
+    return g;
+}
+
 struct Plan {
     bool ok = false;
     int rows = 0, d = 0, r = 0, V = 0, k = 0;
     int K = 0;                 // contraction length of the vocabulary projection (r or d)
     int chunks = 0;            // partials per row
+    int lanes = 64, nw1 = 16;  // see ChunkGeom
     // byte offsets into the workspace
     size_t off_x = 0;          // fp32 [kGemvMaxRows, K]: t (low-rank) or widened h (full)
     size_t off_tpart = 0;      // fp32 [nds, kGemvMaxRows, r]  slices of t
@@ -54,7 +77,8 @@ inline Plan make_plan(HeadKind kind, int rows, int d, int r, int V, int k) {
     Plan p;
     p.rows = rows; p.d = d; p.r = r; p.V = V; p.k = k;
     p.K = (kind == HeadKind::LowRank) ? r : d;
-    p.chunks = (V + kChunkCols - 1) / kChunkCols;
+    const ChunkGeom cg = make_chunk_geom(rows, V);
+    p.chunks = cg.chunks; p.lanes = cg.lanes; p.nw1 = cg.nw1;
     size_t off = 0;
     p.off_x = off;          off = align_up(off + sizeof(float) * kGemvMaxRows * (size_t)p.K);
     {

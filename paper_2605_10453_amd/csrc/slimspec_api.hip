@@ -36,7 +36,7 @@ int check_shape(HeadKind kind, const slimspec_shape *s, int32_t k)
     if (kind == HeadKind::LowRank && (s->r & 7)) return SLIMSPEC_UNSUPPORTED;
     // index arithmetic inside the kernels is 32-bit for ids and 64-bit for offsets
     if ((int64_t)s->V > (int64_t)1 << 30) return SLIMSPEC_UNSUPPORTED;
-    int chunks = (s->V + kChunkCols - 1) / kChunkCols;
+    const int chunks = make_chunk_geom(s->rows, s->V).chunks;
     if (merge_lds_bytes(chunks, k) > kMergeLdsLimit) return SLIMSPEC_UNSUPPORTED;
     return SLIMSPEC_OK;
 }
@@ -150,7 +150,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
         e = launch_stream_topk(kind == HeadKind::LowRank ? tpart : x, kind == HeadKind::LowRank ? dp.nds : 0, M, m_is_f32,
                                part_ms, part_val, part_id,
-                               rows_here, row0, p.K, p.V, p.chunks, k, s);
+                               rows_here, row0, p.K, p.V, p.chunks, p.lanes, p.nw1, k, s);
         if (e != hipSuccess) return fail_hip(e);
         if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
     }

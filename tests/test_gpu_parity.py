@@ -82,6 +82,10 @@ SMALL = [
     (20, 64, 8, 1032, 4),           # a single, partial stage of the contraction
     (12, 64, 24, 2056, 16),         # the largest k of the matrix-core path
     (5, 128, 32, 4104, 10),         # the smallest row count of the matrix-core path
+    (1, 64, 16, 140000, 10),        # one row, more than 256 chunks: narrower chunks, 8-wavefront blocks
+    (1, 64, 16, 300000, 10),        # ... more than 512: 4-wavefront blocks
+    (1, 64, 8, 600008, 5),          # ... more than 1024: full-width chunks in several rounds
+    (2, 64, 16, 140000, 10),        # two rows keep 512-column chunks
 ]
 
 
@@ -98,7 +102,7 @@ def test_low_rank_small(gpu, oracle_mod, rows, d, r, V, k):
     check_low_rank(gpu, oracle_mod, x, k)
 
 
-@pytest.mark.parametrize("rows,d,r,V,k", SMALL[:8])
+@pytest.mark.parametrize("rows,d,r,V,k", SMALL[:8] + SMALL[-4:-2])
 @pytest.mark.parametrize("w_f32", [False, True])
 def test_full_head_small(gpu, oracle_mod, rows, d, r, V, k, w_f32):
     x = synth.make_inputs(synth.small_config(rows, d, r, V, k), seed=77 + rows, with_full_head=True)
