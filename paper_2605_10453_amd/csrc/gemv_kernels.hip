@@ -49,9 +49,9 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     float2 *__restrict__ part_ms, float *__restrict__ part_val, int *__restrict__ part_id,
     int rows_here, int row0, int K, int V, int chunks, int lanes, int k)
 {
-    __shared__ ChunkLds<R, NW> L;
-    extern __shared__ __align__(16) unsigned char dyn[];         // SLICES: t as fp32 [R][K]
-    float *xs = reinterpret_cast<float *>(dyn);
+    extern __shared__ __align__(16) unsigned char dyn[];         // ChunkLds, then (SLICES) t as fp32 [R][K]
+    ChunkLds<R, NW> &L = *reinterpret_cast<ChunkLds<R, NW> *>(dyn);
+    float *xs = reinterpret_cast<float *>(dyn + sizeof(ChunkLds<R, NW>));
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int chunk = blockIdx.x;
@@ -208,21 +208,29 @@ hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)
     return hipGetLastError();
 }
 
+constexpr size_t kStreamLdsLimit = 150 * 1024;      // of the CU's 160 KB
+
+template <int R, int NW>
+constexpr size_t stream_lds_bytes(bool slices, int K) {
+    return sizeof(ChunkLds<R, NW>) + (slices ? sizeof(float) * (size_t)R * K : 0);
+}
+
 template <int R, int NW, typename WT>
 static hipError_t launch_stream(const float *x, int nds, const WT *M, float2 *ms, float *pv, int *pi,
                                 int rows_here, int row0, int K, int V, int chunks, int lanes, int k, hipStream_t st)
 {
-    if (nds > 0) {
-        auto fn = stream_topk_kernel<R, NW, WT, true>;
-        const size_t dyn = sizeof(float) * (size_t)R * K;
-        if (dyn > 16 * 1024) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
-            if (e != hipSuccess) return e;
-        }
-        fn<<<chunks, NW * 64, dyn, st>>>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
-    } else {
-        stream_topk_kernel<R, NW, WT, false><<<chunks, NW * 64, 0, st>>>(x, 0, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
+    static_assert(sizeof(ChunkLds<R, NW>) % 16 == 0, "t follows the struct in shared memory");
+    const size_t dyn = stream_lds_bytes<R, NW>(nds > 0, K);
+    const void *fn = nds > 0 ? reinterpret_cast<const void *>(stream_topk_kernel<R, NW, WT, true>)
+                             : reinterpret_cast<const void *>(stream_topk_kernel<R, NW, WT, false>);
+    if (dyn > 32 * 1024) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+        if (e != hipSuccess) return e;
     }
+    if (nds > 0)
+        stream_topk_kernel<R, NW, WT, true><<<chunks, NW * 64, dyn, st>>>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
+    else
+        stream_topk_kernel<R, NW, WT, false><<<chunks, NW * 64, dyn, st>>>(x, 0, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
     return hipGetLastError();
 }
 
@@ -231,11 +239,14 @@ static hipError_t launch_stream_rows(const float *x, int nds, const WT *M, float
                                      int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st)
 {
 #define SLIMSPEC_STREAM(R, NW) launch_stream<R, NW, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k, st)
-    // shared memory is NW * R * 2 KB: keep it at 32 KB.  One row: the block size the chunk geometry asks for.
+#define SLIMSPEC_FITS(R, NW) (stream_lds_bytes<R, NW>(nds > 0, K) <= kStreamLdsLimit)
+    // One row: the block size the chunk geometry asks for.  More rows: as many wavefronts as the shared memory of
+    // the partial sums (NW * R * 2 KB) allows; they split the contraction, and every one of them keeps loads in flight.
     if (rows_here <= 1) return nw1 == 4 ? SLIMSPEC_STREAM(1, 4) : nw1 == 8 ? SLIMSPEC_STREAM(1, 8) : SLIMSPEC_STREAM(1, 16);
-    if (rows_here <= 2) return SLIMSPEC_STREAM(2, 8);
-    if (rows_here <= 4) return SLIMSPEC_STREAM(4, 4);
-    return SLIMSPEC_STREAM(8, 2);
+    if (rows_here <= 2) return SLIMSPEC_FITS(2, 16) ? SLIMSPEC_STREAM(2, 16) : SLIMSPEC_STREAM(2, 8);
+    if (rows_here <= 4) return SLIMSPEC_FITS(4, 8) ? SLIMSPEC_STREAM(4, 8) : SLIMSPEC_STREAM(4, 4);
+    return SLIMSPEC_FITS(8, 4) ? SLIMSPEC_STREAM(8, 4) : SLIMSPEC_STREAM(8, 2);
+#undef SLIMSPEC_FITS
 #undef SLIMSPEC_STREAM
 }
 
