@@ -107,7 +107,13 @@ constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
 
 int head_tile_rows_per_block(int rows);
 size_t merge_defer_bytes(int rows);
-constexpr int kDeferMinK = 2048;
+// Rows whose exact re-evaluations are parked for exact_cols_kernel: worth two more launches when a few rows with long
+// column gathers would otherwise hold the merge up.  Always from K = 2048 (the full head: 127 -> 35 us at 512 rows);
+// from K = 1024 when the kernel ran on f16 operands, where few rows need any re-evaluation (C5: 42.7 -> 34.3 us).
+// With bf16 operands most rows re-evaluate something and the gathers are bound by the memory side's bandwidth, not by
+// one CU's latency: parked or not measures the same at K = 1024 (58 us) and worse at K = 512 (32 -> 43 us).
+constexpr int kDeferMinK = 2048, kDeferMinKFine = 1024;
+inline bool merge_parks_rows(int K, bool fine_operand) { return K >= kDeferMinK || (fine_operand && K >= kDeferMinKFine); }
 
 struct MfmaPlan {
     int rows = 0, rows_pad = 0, rt = 0, n_rb = 0, gw = 0, nsr = 0, n_vt = 0;
@@ -154,8 +160,7 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
         p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((d + 63) / 64 * 64));      // h regrouped for the kernel
     }
     p.off_streams = off;       off = align_up(off + sizeof(float) * (size_t)rows * p.nsr * kStreamRecPlan);
-    // exact re-evaluations are column gathers of K scattered lines each: from K = 2048 on they go to their own kernel
-    p.defer = (kind == HeadKind::Full ? d : r) >= kDeferMinK;
+    p.defer = (kind == HeadKind::Full ? d : r) >= kDeferMinKFine;      // room for it; the call decides (merge_parks_rows)
     if (p.defer) { p.off_defer = off; off = align_up(off + merge_defer_bytes(rows)); }
     p.bytes = off;
     return p;

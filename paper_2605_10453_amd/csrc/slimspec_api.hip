@@ -88,7 +88,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
-                                     p.defer ? ws + p.off_defer : nullptr, s);
+                                     (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
             // the full head runs the same kernel on h itself (bf16 exact, natural units): no rounding statistics
@@ -100,7 +100,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
-                                     p.defer ? ws + p.off_defer : nullptr, s);
+                                     (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);
         }
     }
