@@ -30,7 +30,7 @@ GEMV_MAX_ROWS = 4              # rows up to which the library streams (from 5 ro
 # HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/ (each scaled by the same counter's reading for a plain copy kernel of
 # known size); None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C2": 131976207, "C4": 146818716}
+MEASURED_TRAFFIC_BYTES = {"C2": 131990491, "C4": 146981121}
 
 
 def log(*a):
