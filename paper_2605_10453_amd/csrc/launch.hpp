@@ -43,6 +43,8 @@ hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_
 // natural_units: X holds the bf16 contraction input itself (full head) and the records carry natural-log values
 hipError_t launch_head_tile(const void *X, bool x_is_f16, bool natural_units, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st);
+// true when a timing-only variant of the kernel is selected (SLIMSPEC_DBG): its output must not be merged
+bool head_tile_timing_only();
 // bf16 rows [rows, K] -> that X layout ([8 ceil(K / 64)][rows_pad] 16-byte vectors, zero padded)
 hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pad, int K, hipStream_t st);
 

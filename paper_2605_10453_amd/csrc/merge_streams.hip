@@ -332,11 +332,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 listed[l] = (x > kNoValue) ? rawtag : -1;
                 if (!(x > kNoValue) || !(mask4(x) * unit >= theta)) continue;
                 const int imax = (int)(__float_as_uint(x) & 15u);
-                push(id_of(tag, imax, half), mask4(x) * unit, 0);
+                const int id_max = id_of(tag, imax, half);
+                if ((unsigned)id_max >= (unsigned)V) continue;      // cannot come from the head kernel: keeps the gathers in bounds whatever the records hold
+                push(id_max, mask4(x) * unit, 0);
                 if (y > kNoValue && mask4(y) * unit >= theta) {
                     for (int i = 0; i < 16; ++i) {
                         const int id = id_of(tag, i, half);
-                        if (i != imax && id < V) push(id, 0.f, 1);
+                        if (i != imax && (unsigned)id < (unsigned)V) push(id, 0.f, 1);
                     }
                 }
             }

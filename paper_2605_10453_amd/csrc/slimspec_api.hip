@@ -85,6 +85,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
+            if (head_tile_timing_only()) continue;          // diagnostic build of the kernel: nothing to merge, outputs stay untouched
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
@@ -98,6 +99,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             e = launch_head_tile(hx, false, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
+            if (head_tile_timing_only()) continue;
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
                                      (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, s);
