@@ -61,6 +61,31 @@ def check_full(gpu, oracle_mod, h, W, k, rows_subset=None):
     return g_ids, g_lp, ora
 
 
+# ------------------------------------------------------------------ seeded sweep of small random shapes
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        rows = int(rng.choice([1, 2, 3, 4, 5, 6, 9, 17, 33, 70, 129, 200]))
+        d = 8 * int(rng.integers(1, 65))
+        r = 8 * int(rng.integers(1, 17))
+        V = 8 * int(rng.integers(1, 1200))
+        k = int(min(V, rng.choice([1, 2, 5, 10, 16, 17, 40, 64])))
+        out.append((rows, d, r, V, k))
+    return out
+
+
+@pytest.mark.parametrize("rows,d,r,V,k", _random_shapes(24, 2024))
+def test_random_small_shapes_both_heads(gpu, oracle_mod, rows, d, r, V, k):
+    """Every dispatch branch on shapes nobody picked by hand: few / many rows, k on both sides of the matrix-core
+    limit, contraction lengths and vocabularies that are not multiples of any tile."""
+    cfg = synth.small_config(rows=rows, d=d, r=r, V=V, k=k, peaked_every=3)
+    x = synth.make_inputs(cfg, 1000 + rows + V, with_full_head=True)
+    check_low_rank(gpu, oracle_mod, x, k)
+    check_full(gpu, oracle_mod, x.h, x.W, k)
+
+
 # ------------------------------------------------------------------ small shapes, several tiles + ragged tails
 
 SMALL = [
