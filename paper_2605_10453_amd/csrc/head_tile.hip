@@ -1,5 +1,5 @@
 // Vocabulary-tiled up-projection on the matrix cores with the fused log-sum-exp / top-k epilogue
-// (paper section 4.1: logits = t B, never written to memory), for calls with many rows.
+// (paper section 4.1: logits = t B, or h W for the full head, never written to memory), for calls with many rows.
 //
 // Shape of the kernel
 //   * A wavefront owns 64 rows x 128 columns of logits = 2 x 4 MFMA tiles of 32 x 32
@@ -16,7 +16,8 @@
 //   * 16-byte pieces of an M row are stored XOR-swizzled by (k mod 4) so that the four rows a
 //     transposing read touches fall into different banks.
 //   * X arrives multiplied by log2(e) and the accumulators of a tile start at minus the row's
-//     running maximum, so that the epilogue's 2^v needs no multiply or subtract.
+//     running maximum, so that the epilogue's 2^v needs no multiply or subtract.  The full head (z = h W)
+//     runs the same kernel on h itself (NAT): natural-log units, one multiply per exponential.
 //
 // Waits: the compiler does not see the direct-to-LDS loads (inline asm), so the kernel counts them
 // itself: every wavefront issues exactly LPS per stage, vector memory returns in order, hence
