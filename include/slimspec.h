@@ -64,7 +64,8 @@ typedef enum slimspec_dtype {
 typedef enum slimspec_status {
     SLIMSPEC_OK = 0,
     SLIMSPEC_INVALID_ARGUMENT = -1,    /* null pointer, non-positive size, k < 1, k > V, bad dtype   */
-    SLIMSPEC_UNSUPPORTED = -2,         /* k > SLIMSPEC_KMAX, d/r/V not a multiple of 8, misaligned   */
+    SLIMSPEC_UNSUPPORTED = -2,         /* k > SLIMSPEC_KMAX, d/r/V not a multiple of 8, misaligned,  */
+                                       /* V > 2^28, d * r >= 2^31                                    */
     SLIMSPEC_WORKSPACE_TOO_SMALL = -3,
     SLIMSPEC_HIP_ERROR = -4            /* a launch failed; text via slimspec_last_hip_error()        */
 } slimspec_status;

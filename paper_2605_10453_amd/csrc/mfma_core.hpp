@@ -68,7 +68,7 @@ __device__ __forceinline__ void load_m_regs(MRegs<C> &r, const uint16_t *__restr
         const int kg = q >> 5, g = q & 31;
         const int n = min(n0 + g * 8, N - 8);
         const int k = min(k0 + kg * 8, K - 8);
-        const uint32_t off = (uint32_t)k * (uint32_t)N + (uint32_t)n;      // < 2^31 elements (checked on the host)
+        const uint32_t off = (uint32_t)k * (uint32_t)N + (uint32_t)n;      // < 2^31 elements (K N = d r: checked on the host)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const uint16_t *row_i = M + (size_t)i * N;                       // uniform

@@ -34,8 +34,10 @@ int check_shape(HeadKind kind, const slimspec_shape *s, int32_t k)
     if (k > SLIMSPEC_KMAX) return SLIMSPEC_UNSUPPORTED;
     if ((s->d & 7) || (s->V & 7)) return SLIMSPEC_UNSUPPORTED;
     if (kind == HeadKind::LowRank && (s->r & 7)) return SLIMSPEC_UNSUPPORTED;
-    // index arithmetic inside the kernels is 32-bit for ids and 64-bit for offsets
-    if ((int64_t)s->V > (int64_t)1 << 30) return SLIMSPEC_UNSUPPORTED;
+    // Index arithmetic inside the kernels: 32-bit ids, 64-bit base addresses, 32-bit lane offsets of a few rows of a
+    // weight matrix (up to four rows of V bf16 values) and of an element of A (d * r).
+    if ((int64_t)s->V > (int64_t)1 << 28) return SLIMSPEC_UNSUPPORTED;
+    if (kind == HeadKind::LowRank && (int64_t)s->d * s->r >= (int64_t)1 << 31) return SLIMSPEC_UNSUPPORTED;
     const int chunks = make_chunk_geom(s->rows, s->V).chunks;
     if (merge_lds_bytes(chunks, k) > kMergeLdsLimit) return SLIMSPEC_UNSUPPORTED;
     return SLIMSPEC_OK;

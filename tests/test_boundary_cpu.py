@@ -83,6 +83,8 @@ def test_argument_validation_without_gpu(lib):
     assert low(S(1, 4096, 512, 128260), 10) == b.STATUS_UNSUPPORTED         # V % 8
     assert low(S(1, 4100, 512, 128256), 10) == b.STATUS_UNSUPPORTED         # d % 8
     assert low(S(1, 4096, 516, 128256), 10) == b.STATUS_UNSUPPORTED         # r % 8
+    assert low(S(1, 4096, 512, (1 << 28) + 8), 10) == b.STATUS_UNSUPPORTED  # V beyond the 32-bit lane offsets
+    assert low(S(1, 1 << 20, 1 << 11, 128256), 10) == b.STATUS_UNSUPPORTED  # d * r beyond them
     assert low(good, 10, h=ctypes.c_void_p(0x1004)) == b.STATUS_UNSUPPORTED  # misaligned
     assert low(good, 10, wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
     assert full(good, 10, dtype=7) == b.STATUS_INVALID_ARGUMENT
