@@ -24,10 +24,15 @@
  *                                    largest logit of the row, p = 0..k-1
  *     out_logprobs [rows, k] float   its log-probability
  * Order: descending logit; equal logits: smaller id first.  Logits are accumulated in
- * fp32 from exact bf16 products; t is carried with at least 16 significant bits.
+ * fp32 from exact bf16 products.  With few rows t = h A stays in fp32 throughout.  With
+ * many rows the matrix cores take a 16-bit t (bf16, or f16 for k > 12) for the sum of
+ * exponentials and for finding the candidates; every candidate whose rank or reported
+ * value could depend on that rounding is then evaluated again from the fp32 t.
  *
  * Ownership / asynchrony: every pointer is caller-owned; the library allocates and
- * frees nothing, keeps nothing between calls, and never synchronises.  All work is
+ * frees nothing, keeps no data between calls (the only state it holds is per host
+ * thread: the text of the last HIP error and the two event handles of
+ * slimspec_set_timing_events), and never synchronises.  All work is
  * enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
  * the call returns immediately; outputs are valid once the stream has been
  * synchronised.  `workspace` is device scratch of at least
@@ -104,7 +109,8 @@ const char *slimspec_status_string(int status);
  * ("" if none).  Static/thread-local storage. */
 const char *slimspec_last_hip_error(void);
 
-/* Measurement aid (not part of the method): when both are non-NULL, every later call
+/* Measurement aid (not part of the method).  This is per-thread state that lasts until
+ * it is switched off again: when both are non-NULL, every later call
  * made by this host thread records `start_event` just before and `stop_event` just
  * after its vocabulary-projection kernel (the kernel that streams B or W; for calls
  * that run it several times, the first run) on the call's stream, so a harness can

@@ -187,7 +187,8 @@ using CfgSmall = TileCfg<1, 4, 2, 2>;    // 64 rows x 256 columns of t per block
 
 template <class C>
 static hipError_t set_lds(const void *fn) {
-    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    static LdsLimit lds_limit;
+    return lds_limit.raise(fn, C::LDS_BYTES);
 }
 
 hipError_t launch_down_gemm(const uint16_t *h, const uint16_t *A, float *part, int rows, int rows_pad, int d, int r,

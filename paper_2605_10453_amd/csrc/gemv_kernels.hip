@@ -224,7 +224,8 @@ static hipError_t launch_stream(const float *x, int nds, const WT *M, float2 *ms
     const void *fn = nds > 0 ? reinterpret_cast<const void *>(stream_topk_kernel<R, NW, WT, true>)
                              : reinterpret_cast<const void *>(stream_topk_kernel<R, NW, WT, false>);
     if (dyn > 32 * 1024) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+        static LdsLimit lds_limit[2];
+        hipError_t e = lds_limit[nds > 0 ? 1 : 0].raise(fn, (int)dyn);
         if (e != hipSuccess) return e;
     }
     if (nds > 0)

@@ -25,7 +25,6 @@
 // instruction may sit inside the main loop: the kernel must not spill.
 #include "head_stream.hpp"
 #include "launch.hpp"
-#include <cstdlib>
 #include <type_traits>
 
 namespace slimspec {
@@ -87,7 +86,8 @@ __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)
 //    (F16: f16): logits come out in base-2 units.  NAT = true: the bf16 input itself (full head): natural units.
 // M: [K][V] bf16 row-major, V and K multiples of 8
 // part: [rows][gw][3 + 3 L] stream records (values in base-2 units): one per row and block
-// DBG != 0: timing experiments (1 no epilogue, 2 loads only, 3 no loads); results are meaningless
+// DBG != 0 (experiment builds only, -DSLIMSPEC_DIAG_DBG=n): timing experiments (1 no epilogue, 2 loads only, 3 no loads);
+// their results are meaningless
 template <int L, int WR, bool F16, bool NAT, int DBG>
 __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
     const uint4 *__restrict__ X, const uint16_t *__restrict__ M, float *__restrict__ part,
@@ -243,23 +243,6 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
         };
         const auto multiply = [&](auto ks_tag) {
             constexpr int ks = decltype(ks_tag)::value;
-            if constexpr (DBG == 4) {
-                // timing experiment: the same flops as 16x16x32 instructions (two per 32x32x16, on quarter accumulators)
-                typedef float f32x4v __attribute__((ext_vector_type(4)));
-#pragma unroll
-                for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                    for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-                        for (int hh = 0; hh < 2; ++hh) {
-                            constexpr int dummy = 0; (void)dummy;
-                            const int q = 2 * ks + hh;
-                            f32x4v c = {acc[rt][jj][4 * q], acc[rt][jj][4 * q + 1], acc[rt][jj][4 * q + 2], acc[rt][jj][4 * q + 3]};
-                            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, mf[ks][jj]), __builtin_bit_cast(bf16x8, xf[ks][rt]), c, 0, 0, 0);
-                            acc[rt][jj][4 * q] = c[0]; acc[rt][jj][4 * q + 1] = c[1]; acc[rt][jj][4 * q + 2] = c[2]; acc[rt][jj][4 * q + 3] = c[3];
-                        }
-                return;
-            }
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -461,8 +444,10 @@ hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pa
 }
 
 int head_tile_rows_per_block(int rows) {
-    static const bool small = getenv("SLIMSPEC_TILE128") != nullptr;      // experiment switch
-    return (rows > 128 && !small) ? 256 : 128;
+#ifdef SLIMSPEC_DIAG_TILE128      // experiment builds only: 128-row blocks at any row count
+    return 128;
+#endif
+    return rows > 128 ? 256 : 128;
 }
 
 template <int WR, bool F16, bool NAT, int DBG>
@@ -471,34 +456,30 @@ static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part,
 {
     using S = TileShape<WR>;
     auto fn = head_tile_kernel<kStreamList, WR, F16, NAT, DBG>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, S::LDS);
+    static LdsLimit lds_limit;
+    hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(fn), S::LDS);
     if (e != hipSuccess) return e;
     HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT};
     fn<<<n_rb * gw, 64 * S::NW, S::LDS, st>>>(static_cast<const uint4 *>(X), M, part, rows, rows_pad, K, V, hg);
     return hipGetLastError();
 }
 
-static int head_tile_dbg() {
-    static const int dbg = getenv("SLIMSPEC_DBG") ? atoi(getenv("SLIMSPEC_DBG")) : 0;
-    return dbg;
-}
-// a timing experiment is selected: the records are not records, the merge must not read them
-bool head_tile_timing_only() { return head_tile_dbg() != 0; }
+// Experiment builds only (-DSLIMSPEC_DIAG_DBG=1|2|3): a timing-only variant of the kernel replaces the real one;
+// its records are not records, the merge must not read them and the calls report SLIMSPEC_UNSUPPORTED.
+#ifndef SLIMSPEC_DIAG_DBG
+#define SLIMSPEC_DIAG_DBG 0
+#endif
+bool head_tile_timing_only() { return SLIMSPEC_DIAG_DBG != 0; }
 
 hipError_t launch_head_tile(const void *X, bool x_is_f16, bool natural_units, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st)
 {
-    const int dbg = head_tile_dbg();
     const bool big = head_tile_rows_per_block(rows) == 256;
 #define SLIMSPEC_TILE_F(F16, NAT, DBG) (big ? launch_tile_cfg<4, F16, NAT, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st) \
                                             : launch_tile_cfg<2, F16, NAT, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
 #define SLIMSPEC_TILE(DBG) (natural_units ? SLIMSPEC_TILE_F(false, true, DBG) \
                                           : (x_is_f16 ? SLIMSPEC_TILE_F(true, false, DBG) : SLIMSPEC_TILE_F(false, false, DBG)))
-    if (dbg == 1) return SLIMSPEC_TILE(1);
-    if (dbg == 2) return SLIMSPEC_TILE(2);
-    if (dbg == 3) return SLIMSPEC_TILE(3);
-    if (dbg == 4) return SLIMSPEC_TILE(4);
-    return SLIMSPEC_TILE(0);
+    return SLIMSPEC_TILE(SLIMSPEC_DIAG_DBG);
 #undef SLIMSPEC_TILE
 #undef SLIMSPEC_TILE_F
 }

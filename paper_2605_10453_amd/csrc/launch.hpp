@@ -3,8 +3,27 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "plan.hpp"
+#include <atomic>
 
 namespace slimspec {
+
+// The dynamic shared memory limit of a kernel is raised once per process and device (and again only if a later call
+// needs more), not on every launch: the attribute call is host work on a path that takes tens of microseconds.
+// One LdsLimit object per kernel instantiation (a function-local static of its launcher).
+struct LdsLimit {
+    static constexpr int kDevices = 16;
+    std::atomic<int> bytes[kDevices] = {};
+    hipError_t raise(const void *fn, int need) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const bool tracked = dev >= 0 && dev < kDevices;
+        if (tracked && bytes[dev].load(std::memory_order_acquire) >= need) return hipSuccess;
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, need);
+        if (e == hipSuccess && tracked) bytes[dev].store(need, std::memory_order_release);
+        return e;
+    }
+};
 
 // slices of t = h A (fp32, [nds][R][r] with R = 1, 2, 4 or 8 >= rows_here) for up to kGemvMaxRows rows
 hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *tpart,
@@ -43,7 +62,8 @@ hipError_t launch_down_finish(const float *part, int slices, int rows, int rows_
 // natural_units: X holds the bf16 contraction input itself (full head) and the records carry natural-log values
 hipError_t launch_head_tile(const void *X, bool x_is_f16, bool natural_units, const uint16_t *M, float *part, int rows, int rows_pad,
                             int K, int V, int n_rb, int gw, hipStream_t st);
-// true when a timing-only variant of the kernel is selected (SLIMSPEC_DBG): its output must not be merged
+// true only in an experiment build (-DSLIMSPEC_DIAG_DBG=n) where a timing-only variant replaces the kernel: its
+// output is not a result and the calls then return SLIMSPEC_UNSUPPORTED
 bool head_tile_timing_only();
 // bf16 rows [rows, K] -> that X layout ([8 ceil(K / 64)][rows_pad] 16-byte vectors, zero padded)
 hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pad, int K, hipStream_t st);

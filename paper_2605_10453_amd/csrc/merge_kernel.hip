@@ -25,8 +25,8 @@ hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int 
     const bool cache_ids = merge_lds_bytes(chunks, k, true) <= 64 * 1024;
     size_t lds = merge_lds_bytes(chunks, k, cache_ids);
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static LdsLimit lds_limit;
+        hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(merge_kernel), (int)lds);
         if (e != hipSuccess) return e;
     }
     merge_kernel<<<rows, kRowMergeThreads, lds, st>>>(part_ms, part_val, part_id, chunks, k, cache_ids ? 1 : 0, out_ids, out_logprobs);

@@ -20,19 +20,15 @@
 #include "device_utils.hpp"
 #include "launch.hpp"
 
-#ifdef SLIMSPEC_TRACE
-__device__ unsigned long long g_trace2[1024 * 12];
-#define TRACE2(slot) do { if (threadIdx.x == 0) g_trace2[blockIdx.x * 12 + (slot)] = wall_clock64(); } while (0)
-extern "C" void slimspec_read_trace2(unsigned long long *dst) { (void)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_trace2), sizeof(g_trace2)); }
-#else
-#define TRACE2(slot) do { } while (0)
-#endif
-
 namespace slimspec {
 
 namespace {
 
 constexpr int kWorkCap = 2048;          // collected logits per row before the exhaustive fallback
+// The exhaustive pass scans kMergeThreads * 4 columns per step; every one of them may beat the running k-th key
+// (logits rising with the column id), and the k keys kept from the step before come on top.
+constexpr int kExhaustCap = kMergeThreads * 4 + SLIMSPEC_KMAX_INTERNAL;
+static_assert(kMergeThreads * 4 <= kWorkCap, "a step of the exhaustive pass appends at most kWorkCap keys");
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
 constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
 constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
@@ -106,8 +102,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     uint64_t *keys = reinterpret_cast<uint64_t *>(lds_raw);            // [n]            every listed maximum
     uint64_t *hkeys = keys + n;                                         // [ngroups * 64] the streams' largest maxima, padded with kNoKey
     uint64_t *surv = hkeys + (size_t)ngroups * 64;                      // [max(ngroups, 3) * k]  best k of every 64 heads; then the candidates for tau
-    uint64_t *work = surv + (size_t)(ngroups > 3 ? ngroups : 3) * k;    // [kWorkCap]     final keys / fallback buffer
-    int *w_id = reinterpret_cast<int *>(work + kWorkCap);               // [kWorkCap]
+    uint64_t *work = surv + (size_t)(ngroups > 3 ? ngroups : 3) * k;    // [kExhaustCap]  final keys / fallback buffer
+    int *w_id = reinterpret_cast<int *>(work + kExhaustCap);            // [kWorkCap]
     float *w_val = reinterpret_cast<float *>(w_id + kWorkCap);          // [kWorkCap]
     int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]     0 no, 1 / 2 yes; later: list of items to evaluate
     float *w_apx = reinterpret_cast<float *>(w_need + kWorkCap);        // [kWorkCap]     change of the item's term of the sum of exp; later by rank
@@ -124,8 +120,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     ctx.x = x_is_bf16 ? static_cast<const void *>(static_cast<const uint16_t *>(xexact) + (size_t)row * ldx)
                       : static_cast<const void *>(static_cast<const float *>(xexact) + (size_t)row * ldx);
     ctx.x_is_bf16 = x_is_bf16; ctx.M = M; ctx.K = K; ctx.V = V;
-
-    TRACE2(0);
     const ParkedRow pk = parked_row(defer, row);
     int *const park = pk.hdr, *const park_need = pk.need, *const park_id = pk.id;
     float *const park_val = pk.val, *const park_part = pk.part;
@@ -141,7 +135,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             by_rank[rank] = w_apx[c];
         });
         __syncthreads();
-        TRACE2(8);
         float corr = 0.f;
         for (int q = 0; q < n_work; ++q) corr += by_rank[q];
         const float s_fixed = S + corr;
@@ -222,8 +215,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __shared__ float red_x[NWAVES];
     __shared__ float red_x1[NWAVES];
     if (lane == 0) { red_x[wave] = x2; red_x1[wave] = x1; }
-
-    TRACE2(1);
     // ---- keys of the listed maxima
     for (int sidx = tid; sidx < nsr; sidx += NT) {
         float f[REC];
@@ -256,8 +247,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         }
         return;
     }
-
-    TRACE2(2);
     // ---- tau: the k-th largest listed maximum.  The lists are sorted, so first T = the k-th largest of the
     // streams' heads (best k of every 64 heads, then all pairs); every listed maximum >= T (at most 3 k of them,
     // all of them if there are fewer than k heads) is a candidate, and tau is the k-th largest candidate.
@@ -274,7 +263,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         if (rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
     }
     __syncthreads();
-    TRACE2(3);
     const int n_surv = (int)cnt_surv;
     __shared__ uint64_t head_bound;
     __shared__ uint32_t cnt_cand;
@@ -291,7 +279,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __syncthreads();
     rank_all_pairs(surv, (int)cnt_cand, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
     __syncthreads();
-    TRACE2(4);
     const bool have_tau = tau_key != kNoKey;
     const float tau = have_tau ? key_value(tau_key) : kNegInf;
     float eps;
@@ -363,7 +350,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         }
     }
     __syncthreads();
-    TRACE2(5);
     int n_work = (int)cnt_work;
     if (n_work > kWorkCap || n_work < k) exhaustive = true;
 
@@ -379,7 +365,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             if (need) w_need[c] = 2;                      // 2: decided in this pass (w_val still the computed value)
         }
         __syncthreads();
-        TRACE2(6);
         // list the items to evaluate (any order: every result goes back to its own slot)
         constexpr int PER = (kWorkCap + NT - 1) / NT;       // fixed trip count: the array stays in registers
         int my_need[PER];
@@ -444,7 +429,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             __syncthreads();
         }
         __syncthreads();
-        TRACE2(7);
         finish(n_work, S, Mx, lse);
         return;
     }
@@ -473,13 +457,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 es = es * fast_exp(em - m_new) + fast_exp(z[e] - m_new);
                 em = m_new;
                 const uint64_t key = make_key(z[e], (uint32_t)(col + e));
-                if (key > thr) work[atomicAdd(&cnt_buf, 1u)] = key;     // at most k + 1024 entries: fits
+                if (key > thr) work[atomicAdd(&cnt_buf, 1u)] = key;     // at most k + 4 NT = kExhaustCap entries: fits
             }
         }
         __syncthreads();
         const int nb = (int)cnt_buf;
-        uint64_t mykey[(kWorkCap + NT - 1) / NT];
-        int myrank[(kWorkCap + NT - 1) / NT];
+        constexpr int PER_X = (kExhaustCap + NT - 1) / NT;
+        uint64_t mykey[PER_X];
+        int myrank[PER_X];
         int cnt_mine = 0;
         rank_all_pairs(work, nb, tid, NT, [&](int, uint64_t key, int rank) { mykey[cnt_mine] = key; myrank[cnt_mine] = rank; ++cnt_mine; });
         __syncthreads();
@@ -562,7 +547,7 @@ size_t merge_defer_bytes(int rows) { return sizeof(int) * kDeferRowInts * (size_
 size_t merge_streams_lds_bytes(int nsr, int k) {
     const size_t n = (size_t)nsr * kStreamList;
     const size_t ngroups = ((size_t)nsr + 63) / 64;
-    return sizeof(uint64_t) * (n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k + kWorkCap) + 16u * kWorkCap;
+    return sizeof(uint64_t) * (n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k + kExhaustCap) + 16u * kWorkCap;
 }
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
@@ -571,8 +556,8 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, void *defer_buf, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(merge_streams_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static LdsLimit lds_limit;
+    hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(merge_streams_kernel), (int)lds);
     if (e != hipSuccess) return e;
     int *defer = static_cast<int *>(defer_buf);
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,

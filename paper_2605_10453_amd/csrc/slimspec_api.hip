@@ -4,7 +4,6 @@
 #include "../../include/slimspec.h"
 #include "launch.hpp"
 #include <string.h>
-#include <stdlib.h>
 
 using namespace slimspec;
 namespace slimspec { bool head_tile_f16(int k); }
@@ -46,11 +45,19 @@ int check_shape(HeadKind kind, const slimspec_shape *s, int32_t k)
 constexpr int kMfmaMaxK = 16;      // the lane streams keep 3 groups: enough for k <= 16 (larger k: streaming path)
 constexpr int kMfmaMinRows = 5;    // from here on the matrix-core path is faster than streaming rows in lock step (measured at C2's shape)
 
+// The launches of one call share the workspace in stream order; a last, smaller batch has a plan of its own
+// (fewer row blocks, more slices of d), so the call needs the larger of the two plans.
 size_t mfma_workspace_bytes(HeadKind kind, const slimspec_shape *s)
 {
     const int per = mfma_max_rows_per_launch(s->rows);
     const int rows0 = s->rows < per ? s->rows : per;
-    return make_mfma_plan(kind, rows0, s->d, s->r, s->V).bytes;
+    size_t need = make_mfma_plan(kind, rows0, s->d, s->r, s->V).bytes;
+    const int tail = s->rows % per;
+    if (s->rows > per && tail != 0) {
+        const size_t t = make_mfma_plan(kind, tail, s->d, s->r, s->V).bytes;
+        if (t > need) need = t;
+    }
+    return need;
 }
 
 int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
@@ -87,7 +94,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            if (head_tile_timing_only()) continue;          // diagnostic build of the kernel: nothing to merge, outputs stay untouched
+            if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;      // diagnostic build, timing-only kernel: no result
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
@@ -101,7 +108,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             e = launch_head_tile(hx, false, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
-            if (head_tile_timing_only()) continue;
+            if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
                                      (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, s);
@@ -163,6 +170,18 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     return SLIMSPEC_OK;
 }
 
+// Scratch one call of `kind` needs (the query slimspec_workspace_bytes reports the larger of the two heads).
+size_t head_workspace_bytes(HeadKind kind, const slimspec_shape *shape, int32_t k)
+{
+    if (check_shape(kind, shape, k) != SLIMSPEC_OK) return 0;
+    size_t need = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k).bytes;
+    if (shape->rows >= kMfmaMinRows) {
+        const size_t m = mfma_workspace_bytes(kind, shape);
+        if (m > need) need = m;
+    }
+    return need;
+}
+
 }  // namespace
 
 namespace slimspec {
@@ -170,10 +189,10 @@ bool head_tile_f16(int k) {
     // The direct-to-LDS kernel takes bf16 operands as they are, or turns the weight tiles into f16 inside LDS and
     // takes an f16 t (8 times finer).  The conversion costs the projection kernel about 12 %; the finer operand
     // saves most of the merge's exact re-evaluations, which grow with k: measured break-even at k = 10, 5-9 % of
-    // the call in favour of f16 at k = 16.  Diagnostic override: SLIMSPEC_TILE_OPERAND=bf16|f16.
-    static const char *force = getenv("SLIMSPEC_TILE_OPERAND");
-    if (force && force[0] == 'b') return false;
-    if (force && force[0] == 'f') return true;
+    // the call in favour of f16 at k = 16.
+#ifdef SLIMSPEC_DIAG_OPERAND_F16      // experiment builds only: force the operand mode (1 f16, 0 bf16)
+    return SLIMSPEC_DIAG_OPERAND_F16 != 0;
+#endif
     return k > 12;
 }
 }  // namespace slimspec
@@ -185,24 +204,10 @@ int slimspec_version(void) { return SLIMSPEC_VERSION; }
 size_t slimspec_workspace_bytes(const slimspec_shape *shape, int32_t k)
 {
     if (!shape) return 0;
-    size_t need = 0;
     // the larger of: streaming path (also serves fp32 W and large k), matrix-core path, for both heads
-    if (check_shape(HeadKind::Full, shape, k) == SLIMSPEC_OK) {
-        need = make_plan(HeadKind::Full, shape->rows, shape->d, shape->r, shape->V, k).bytes;
-        if (shape->rows >= kMfmaMinRows) {
-            size_t m = mfma_workspace_bytes(HeadKind::Full, shape);
-            if (m > need) need = m;
-        }
-    }
-    if (check_shape(HeadKind::LowRank, shape, k) == SLIMSPEC_OK) {
-        size_t lo = make_plan(HeadKind::LowRank, shape->rows, shape->d, shape->r, shape->V, k).bytes;
-        if (lo > need) need = lo;
-        if (shape->rows >= kMfmaMinRows) {
-            size_t m = mfma_workspace_bytes(HeadKind::LowRank, shape);
-            if (m > need) need = m;
-        }
-    }
-    return need;
+    const size_t full = head_workspace_bytes(HeadKind::Full, shape, k);
+    const size_t low = head_workspace_bytes(HeadKind::LowRank, shape, k);
+    return full > low ? full : low;
 }
 
 int slimspec_head_topk(const void *h, const void *A, const void *B,

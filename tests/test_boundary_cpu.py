@@ -129,3 +129,24 @@ def test_kernels_use_no_scratch_memory(source, kernel):
     found = [(n, int(sz)) for n, sz in zip(names, scratch) if kernel in n]
     assert len(found) >= 1, text[-2000:]
     assert all(sz == 0 for _, sz in found), found
+
+
+def test_workspace_check_covers_every_batch_of_a_call(lib):
+    """Calls with more than 512 rows run in batches that reuse the workspace; the last batch has a plan of its own
+    (fewer row blocks, more slices of d) that can need more room than the first.  The size the call checks must be
+    the size the query reports, and the query must cover the first batch and the tail batch alike."""
+    l, b = lib
+    fake = ctypes.c_void_p(0x1000)
+    for d, r, V in ((5120, 640, 8192), (4096, 512, 128256), (1024, 1024, 4096)):
+        for rows in list(range(513, 1024, 37)) + [1023, 1024, 1025, 1536 + 300]:
+            need = b.slimspec_workspace_bytes(rows, d, r, V, 10)
+            assert need > 0
+            shape = b.SlimspecShape(rows, d, r, V)
+            for call in (lambda wsb: l.slimspec_head_topk(fake, fake, fake, ctypes.byref(shape), 10, fake, fake, fake, wsb, None),
+                         lambda wsb: l.full_head_topk(fake, fake, 0, ctypes.byref(shape), 10, fake, fake, fake, wsb, None)):
+                assert call(256) == b.STATUS_WORKSPACE_TOO_SMALL
+            # a call of its own with only the first 512 rows, or only the tail rows, never needs more than the whole call
+            assert need >= b.slimspec_workspace_bytes(512, d, r, V, 10)
+            tail = rows % 512
+            if tail >= 5:
+                assert need >= b.slimspec_workspace_bytes(tail, d, r, V, 10), (rows, d, r, V)

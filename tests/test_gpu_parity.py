@@ -215,12 +215,51 @@ def test_planted_exact_ties(gpu, oracle_mod, rows):
         assert ids[0].tolist() == [0, V // 2, V - 1][:k]
 
 
-def test_run_to_run_determinism(gpu):
-    cfg = synth.small_config(rows=5, d=512, r=64, V=20000, k=10)
+@pytest.mark.parametrize("k", [16, 10])
+def test_rising_logits_through_the_exhaustive_pass(gpu, oracle_mod, k):
+    """Logits that rise strictly with the column id over the whole vocabulary.  With k = 16 the matrix cores take an
+    f16 contraction input, which overflows for rows 0-2 here, so the merge answers with its exhaustive exact pass;
+    there every scanned column beats the running k-th key, which fills the pass's key buffer to its bound."""
+    rows, d, r, V = 6, 8, 8, 16384
+    one = synth.f32_to_bf16_bits(np.float32(1.0))
+    h = np.zeros((rows, d), np.float32)
+    h[:, 0] = [65536.0, -65536.0, 98304.0, 0.0, 1.0, 65536.0]
+    A = np.zeros((d, r), np.float32)
+    A[0, 0], A[0, 1] = 1.0, 2.0 ** -8
+    v = np.arange(V)
+    B = np.zeros((r, V), np.float32)
+    B[0] = 1.0 + (v >> 7) / 128.0
+    B[1] = 1.0 + (v & 127) / 128.0
+    x = synth.HeadInputs(cfg=synth.small_config(rows, d, r, V, k), seed=0, h=synth.f32_to_bf16_bits(h),
+                         A=synth.f32_to_bf16_bits(A), B=synth.f32_to_bf16_bits(B))
+    assert one == 0x3F80 and np.array_equal(synth.bf16_bits_to_f32(x.B), B)         # every value is exact in bf16
+    g_ids, _, ora, _ = check_low_rank(gpu, oracle_mod, x, k)
+    assert np.array_equal(g_ids, ora.ids)
+    assert g_ids[0].tolist() == list(range(V - 1, V - 1 - k, -1))
+    assert g_ids[1].tolist() == list(range(k))
+
+
+@pytest.mark.parametrize("rows,d,r,V,k", [(1, 512, 64, 20000, 10), (3, 256, 32, 9000, 7), (5, 512, 64, 20000, 10),
+                                          (512, 256, 64, 20000, 10), (40, 128, 32, 6000, 16)])
+def test_run_to_run_determinism(gpu, rows, d, r, V, k):
+    """Same inputs, same bits out: the streaming path, the matrix-core path with both operand modes and two row blocks."""
+    cfg = synth.small_config(rows=rows, d=d, r=r, V=V, k=k, peaked_every=7)
     x = synth.make_inputs(cfg, 3)
     a = run_low_rank(gpu, x, cfg.k)
-    b = run_low_rank(gpu, x, cfg.k)
-    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+    for _ in range(2):
+        b = run_low_rank(gpu, x, cfg.k)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+
+
+def test_run_to_run_determinism_full_head_parked_rows(gpu):
+    """Full head with a long contraction: rows that need exact re-evaluations are parked and finished by later launches."""
+    cfg = synth.small_config(rows=12, d=2048, r=8, V=4104, k=8)
+    x = synth.make_inputs(cfg, 5, with_full_head=True)
+    x.W[:, 2048:2048 + 1024] = x.W[:, :1024]
+    a = run_full(gpu, x.h, x.W, cfg.k)
+    for _ in range(2):
+        b = run_full(gpu, x.h, x.W, cfg.k)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
 
 
 def test_side_stream_and_caller_buffers(gpu, oracle_mod):
