@@ -31,6 +31,7 @@ constexpr int kExhaustCap = kMergeThreads * 4 + SLIMSPEC_KMAX_INTERNAL;
 static_assert(kMergeThreads * 4 <= kWorkCap, "a step of the exhaustive pass appends at most kWorkCap keys");
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
 constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
+constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes the exhaustive exact pass
 constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
 constexpr float kEpsSigmas = 4.0f;      // eps = this many standard deviations of the rounding error of t
                                         // (values are re-evaluated when within 2 eps = 5.6 sigma of their difference)
@@ -292,7 +293,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const float theta = have_tau ? tau - 2.f * eps : kNegInf;
     // a computed value may be off by eps: beyond this bound the winners' log-probabilities take the exact value
     const bool exact_all = eps > kExactWinnersEps;
-    bool exhaustive = !(eps < 1e30f) || !(lse == lse) || !(fabsf(lse) < 1e30f);   // overflow of the 16-bit input
+    // Overflow of the 16-bit input; or a rounding bound so wide that the streams' sum of exponentials (whose terms
+    // are off by up to a factor e^eps) no longer gives the log-sum-exp to the reported precision, and the
+    // correction by the re-evaluated terms could itself overflow.
+    bool exhaustive = !(eps < kExhaustiveEps) || !(lse == lse) || !(fabsf(lse) < 1e30f);
 
     // ---- collect
     auto push = [&](int id, float val, int need) {
