@@ -72,11 +72,14 @@ typedef enum slimspec_status {
     SLIMSPEC_UNSUPPORTED = -2,         /* k > SLIMSPEC_KMAX, d/r/V not a multiple of 8, misaligned,  */
                                        /* V > 2^28, d * r >= 2^31                                    */
     SLIMSPEC_WORKSPACE_TOO_SMALL = -3,
-    SLIMSPEC_HIP_ERROR = -4            /* a launch failed; text via slimspec_last_hip_error()        */
+    SLIMSPEC_HIP_ERROR = -4,           /* a launch failed; text via slimspec_last_hip_error()        */
+    SLIMSPEC_SCRATCH_LIMIT = -5        /* slimspec_head_topk_static: the shape needs more scratch    */
+                                       /* than SLIMSPEC_STATIC_SCRATCH_BYTES                         */
 } slimspec_status;
 
 #define SLIMSPEC_KMAX 64
 #define SLIMSPEC_VERSION 1
+#define SLIMSPEC_STATIC_SCRATCH_BYTES (32u << 20)   /* device scratch built into the library, per GPU */
 
 /* Library version (SLIMSPEC_VERSION it was built with).  Host only, no HIP call. */
 int slimspec_version(void);
@@ -93,6 +96,22 @@ int slimspec_head_topk(const void *h, const void *A, const void *B,
                        int32_t *out_ids, float *out_logprobs,
                        void *workspace, size_t workspace_bytes,
                        void *stream);
+
+/* The low-rank head for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same operation, kernels and results as slimspec_head_topk, but the scratch
+ * is a fixed array of SLIMSPEC_STATIC_SCRATCH_BYTES inside the library's device code
+ * (every GPU the library runs on holds one copy until the process ends); the call
+ * allocates and frees nothing.  Shapes whose scratch need
+ * (slimspec_workspace_bytes' figure for the low-rank head alone) exceeds that size are
+ * refused with SLIMSPEC_SCRATCH_LIMIT before anything is enqueued.  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (different streams or
+ * host threads) race and give undefined results; calls on one stream are ordered and
+ * safe.  The array keeps the previous call's contents; no kernel relies on them. */
+int slimspec_head_topk_static(const void *h, const void *A, const void *B,
+                              const slimspec_shape *shape, int32_t k,
+                              int32_t *out_ids, float *out_logprobs,
+                              void *stream);
 
 /* Full head (first display of section 4.1): z = h W, same reduction.  W is bf16 or
  * fp32 as named by w_dtype; shape->r is ignored. */

@@ -25,9 +25,11 @@ STATUS_INVALID_ARGUMENT = -1
 STATUS_UNSUPPORTED = -2
 STATUS_WORKSPACE_TOO_SMALL = -3
 STATUS_HIP_ERROR = -4
+STATUS_SCRATCH_LIMIT = -5
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = (
-    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "full_head_topk",
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk",
     "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
@@ -63,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     lib.slimspec_workspace_bytes.argtypes = [shp, i32]
     lib.slimspec_head_topk.restype = ctypes.c_int
     lib.slimspec_head_topk.argtypes = [vp, vp, vp, shp, i32, vp, vp, vp, sz, vp]
+    lib.slimspec_head_topk_static.restype = ctypes.c_int
+    lib.slimspec_head_topk_static.argtypes = [vp, vp, vp, shp, i32, vp, vp, vp]
     lib.full_head_topk.restype = ctypes.c_int
     lib.full_head_topk.argtypes = [vp, vp, ctypes.c_int, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_status_string.restype = ctypes.c_char_p
@@ -166,6 +170,31 @@ def slimspec_head_topk(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, k: int
                                 _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
                                 _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                 _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs
+
+
+def slimspec_head_topk_static(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, k: int,
+                              out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                              stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """slimspec_head_topk on the library's built-in scratch: the C call allocates nothing and takes no workspace.
+
+    Pass out_ids / out_logprobs to keep this wrapper from allocating them.
+    """
+    rows, d = h.shape
+    d2, r = A.shape
+    r2, V = B.shape
+    if d != d2 or r != r2:
+        raise ValueError("shape mismatch between h, A and B")
+    for t, n in ((h, "h"), (A, "A"), (B, "B")):
+        if t.element_size() != 2:
+            raise ValueError(f"{n} must hold bf16 (2-byte) elements")
+    out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
+    shape = SlimspecShape(rows, d, r, V)
+    st = load_library().slimspec_head_topk_static(
+        _dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"), ctypes.byref(shape), k,
+        _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"), _stream_handle(stream))
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs

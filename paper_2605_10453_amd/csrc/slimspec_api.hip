@@ -4,11 +4,19 @@
 #include "../../include/slimspec.h"
 #include "launch.hpp"
 #include <string.h>
+#include <atomic>
 
 using namespace slimspec;
 namespace slimspec { bool head_tile_f16(int k); }
 
 namespace {
+
+// Scratch of slimspec_head_topk_static: device memory that belongs to the library's code object, so the entry point
+// needs no allocation and no workspace argument.  Every GPU the library runs on holds its own copy at its own
+// address; in host code the array's name is only a handle for hipGetSymbolAddress, never a device pointer.
+static __device__ __align__(256) unsigned char scratch[SLIMSPEC_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 16;
+std::atomic<void *> g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch`, per device, looked up once
 
 thread_local char g_hip_error[256] = "";
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
@@ -58,6 +66,23 @@ size_t mfma_workspace_bytes(HeadKind kind, const slimspec_shape *s)
         if (t > need) need = t;
     }
     return need;
+}
+
+// Device address of this device's copy of `scratch` (looked up at the first call on the device).
+int static_scratch_address(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e);
+    if (dev < 0 || dev >= kMaxDevices) return SLIMSPEC_UNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail_hip(e != hipSuccess ? e : hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return SLIMSPEC_OK;
 }
 
 int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
@@ -219,6 +244,22 @@ int slimspec_head_topk(const void *h, const void *A, const void *B,
                     workspace, workspace_bytes, stream);
 }
 
+int slimspec_head_topk_static(const void *h, const void *A, const void *B,
+                              const slimspec_shape *shape, int32_t k,
+                              int32_t *out_ids, float *out_logprobs, void *stream)
+{
+    const int st = check_shape(HeadKind::LowRank, shape, k);
+    if (st != SLIMSPEC_OK) return st;
+    if (head_workspace_bytes(HeadKind::LowRank, shape, k) > (size_t)SLIMSPEC_STATIC_SCRATCH_BYTES)
+        return SLIMSPEC_SCRATCH_LIMIT;
+    if (!h || !A || !B || !out_ids || !out_logprobs) return SLIMSPEC_INVALID_ARGUMENT;      // before any HIP call
+    void *ptr = nullptr;
+    const int sa = static_scratch_address(&ptr);
+    if (sa != SLIMSPEC_OK) return sa;
+    return run_head(HeadKind::LowRank, h, A, B, false, shape, k, out_ids, out_logprobs,
+                    ptr, (size_t)SLIMSPEC_STATIC_SCRATCH_BYTES, stream);
+}
+
 int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
                    const slimspec_shape *shape, int32_t k,
                    int32_t *out_ids, float *out_logprobs,
@@ -237,6 +278,7 @@ const char *slimspec_status_string(int status)
     case SLIMSPEC_UNSUPPORTED: return "unsupported shape, k or alignment";
     case SLIMSPEC_WORKSPACE_TOO_SMALL: return "workspace too small";
     case SLIMSPEC_HIP_ERROR: return "HIP error";
+    case SLIMSPEC_SCRATCH_LIMIT: return "shape needs more scratch than the library's static buffer holds";
     default: return "unknown status";
     }
 }
