@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const float *__restrict__ part, int nsr, int gw, int n_vt,
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
-    const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ brms,
+    const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ bsq, int n_bsq,
     int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
     int *__restrict__ defer, int resume)
 {
@@ -205,7 +205,15 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     }
     for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
     __shared__ float stat_sh[64];
-    const float b_rms = (stat != nullptr) ? brms[0] : 0.f;      // asked for early: by the time eps needs it, it has arrived
+    // rms of B from the down-projection's partial sums of squares over a fixed sample (added in a fixed order;
+    // asked for early: by the time eps needs it, it has arrived)
+    __shared__ float b_rms_sh;
+    if (stat != nullptr && wave == NWAVES - 1) {
+        float a = 0.f;
+        for (int i = lane; i < n_bsq; i += 64) a += bsq[i];
+        a = wave_sum(a);
+        if (lane == 0) b_rms_sh = sqrtf(a / (float)(K * kBrmsPositions * 8));
+    }
     if (stat != nullptr && tid < n_stat && tid < 64) stat_sh[tid] = stat[(size_t)tid * rows_pad + row].x;
     const float m_w = wave_max(m_t);
     float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         float dt2 = 0.f;                                     // squared norm of t - f16(t), summed in a fixed order
         for (int q = 0; q < n_stat; ++q) dt2 += (q < 64) ? stat_sh[q] : stat[(size_t)q * rows_pad + row].x;
         // + weights the kernel flushed to zero (magnitude below tiny_w) times the 1-norm of the contraction input
-        eps = kEpsSigmas * sqrtf(dt2) * b_rms + fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
+        eps = kEpsSigmas * sqrtf(dt2) * b_rms_sh + fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
     }
     else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
     const float theta = have_tau ? tau - 2.f * eps : kNegInf;
@@ -556,7 +564,7 @@ size_t merge_streams_lds_bytes(int nsr, int k) {
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
-                                const float2 *stat, int n_stat, int rows_pad, const float *brms, int k,
+                                const float2 *stat, int n_stat, int rows_pad, const float *bsq, int n_bsq, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, void *defer_buf, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
@@ -565,14 +573,14 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
     if (e != hipSuccess) return e;
     int *defer = static_cast<int *>(defer_buf);
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, brms, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           M, K, V, stat, n_stat, rows_pad, bsq, n_bsq, k, unit, tiny_w, out_ids, out_logprobs,
                                                            defer, 0);
     if ((e = hipGetLastError()) != hipSuccess || !defer) return e;
     // parked rows: their exact columns on many CUs, then the rest of their merge
     exact_cols_kernel<<<dim3(kDeferSlices, rows), 256, 0, st>>>(defer, xexact, x_is_bf16 ? 1 : 0, ldx, M, K, V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, brms, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           M, K, V, stat, n_stat, rows_pad, bsq, n_bsq, k, unit, tiny_w, out_ids, out_logprobs,
                                                            defer, 1);
     return hipGetLastError();
 }

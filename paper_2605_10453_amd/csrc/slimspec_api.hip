@@ -45,6 +45,8 @@ int check_shape(HeadKind kind, const slimspec_shape *s, int32_t k)
     // weight matrix (up to four rows of V bf16 values) and of an element of A (d * r).
     if ((int64_t)s->V > (int64_t)1 << 28) return SLIMSPEC_UNSUPPORTED;
     if (kind == HeadKind::LowRank && (int64_t)s->d * s->r >= (int64_t)1 << 31) return SLIMSPEC_UNSUPPORTED;
+    // ... and of a row of h inside one launch's 512 rows, and of 32 rows of A (the many-row down-projection)
+    if (kind == HeadKind::LowRank && (s->d > (1 << 21) || s->r > (1 << 24))) return SLIMSPEC_UNSUPPORTED;
     const int chunks = make_chunk_geom(s->rows, s->V).chunks;
     if (merge_lds_bytes(chunks, k) > kMergeLdsLimit) return SLIMSPEC_UNSUPPORTED;
     return SLIMSPEC_OK;
@@ -105,15 +107,13 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
         hipError_t e;
         const bool timed = g_ev_start && row0 == 0;
         if (kind == HeadKind::LowRank) {
-            float *down_part = reinterpret_cast<float *>(ws + p.off_down_part);
             float *t32 = reinterpret_cast<float *>(ws + p.off_t32);
             void *t16 = ws + p.off_t16;
             float2 *stat = reinterpret_cast<float2 *>(ws + p.off_stat);
             float *brms = reinterpret_cast<float *>(ws + p.off_brms);
-            e = launch_down_gemm(hrow, static_cast<const uint16_t *>(A), down_part, rows, p.rows_pad, d, r, p.slices, p.kslice, s);
-            if (e != hipSuccess) return fail_hip(e);
             const bool tile_f16 = head_tile_f16(k);
-            e = launch_down_finish(down_part, p.slices, rows, p.rows_pad, r, t32, t16, stat, Mb, V, brms, tile_f16, s);
+            e = launch_down_projection_tiles(hrow, static_cast<const uint16_t *>(A), reinterpret_cast<float *>(ws + p.off_down_part), p.down,
+                                             rows, p.rows_pad, d, r, t32, t16, stat, Mb, V, brms, tile_f16, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
             e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
@@ -121,7 +121,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;      // diagnostic build, timing-only kernel: no result
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, p.n_bsq, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
                                      (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);
@@ -134,7 +134,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, 0, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
                                      (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);
