@@ -2,7 +2,8 @@
 //
 //   down_tile_kernel     64 x 64 tiles of t over a slice of the contraction (bf16 MFMA, fp32 accumulate)
 //   down_finish_kernel   fixed-order sum of the slices -> fp32 t, the 16-bit t in the k-grouped layout the
-//                        up-projection kernel reads, per-row rounding statistics, sums of squares of a sample of B
+//                        up-projection kernel reads, per-row rounding statistics; further blocks of the same launch
+//                        estimate the scale of B's columns per 256-column vocabulary tile
 //
 // A CU fills its LDS at a few tens of bytes per clock, so what a block has to load decides the time: a block owns a
 // 64 x 64 tile (its four wavefronts share every stage, 32 x 32 each) and the contraction is split over as many slices
@@ -27,6 +28,7 @@ constexpr int kDStageBytes = 8192;          // 4 KB of A (32 rows x 128 B), 4 KB
 constexpr int kDNB = 8;                     // stage buffers
 constexpr int kDLoads = 2;                  // loads per wavefront and stage
 constexpr int kDLds = kDNB * kDStageBytes;  // 64 KB
+constexpr int kColSamples = 32;             // entries sampled per column of B for its scale (see column_scale_block)
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -45,6 +47,81 @@ __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)
 
 }  // namespace
 
+// Scale of B's columns, for the bound on what rounding t to 16 bits does to a logit (the error of column v is
+// sum_j dt_j B[j, v], about |dt| times the column's rms).  Block b covers columns [512 b, 512 b + 512): thread
+// (8 adjacent columns, row phase tid / 64) squares every col_stride-th row of its columns, 16 loads in flight at a
+// time (full 128-byte lines per wavefront); the four phases meet in shared memory in a fixed order; the block writes,
+// for each of its two 256-column vocabulary tiles, (the largest column rms, the mean square of the tile's entries).  The sample covers every column and a
+// subset of rows (all rows up to r = kColSamples, at least kColSamples rows beyond), 1 / col_stride of B's bytes: sample i of a group
+// of 64 columns (one 128-byte line per row) is row i col_stride + (c + 5 i) mod col_stride with c depending on the
+// group, so that a periodic pattern over the rows of B is sampled in proportion and cannot hide from a column's sum.
+__device__ __forceinline__ void column_scale_block(const uint16_t *__restrict__ B, int r, int V, float2 *__restrict__ tilescale,
+                                                   int b, float *sh, int tid)
+{
+    const int col_stride = max(1, r / kColSamples), n_s = (r + col_stride - 1) / col_stride;
+    const int oct = tid & 63, phase = tid >> 6;
+    const int col = b * 512 + oct * 8;
+    const int g64 = col >> 6;
+    const int row_off = 13 * (g64 >> 2) + 3 * (g64 & 3);
+    const auto sample_row = [&](int i) { return i * col_stride + (row_off + 5 * i) % col_stride; };
+    float ss[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss[e] = 0.f;
+    if (col < V) {
+        const uint16_t *src = B + col;
+        constexpr int NL = 8;                                  // loads in flight per thread
+        for (int i0 = phase; i0 < n_s; i0 += 4 * NL) {
+            uint4 w[NL];
+#pragma unroll
+            for (int u = 0; u < NL; ++u)
+                w[u] = *reinterpret_cast<const uint4 *>(src + (size_t)min(sample_row(min(i0 + 4 * u, n_s - 1)), r - 1) * V);
+#pragma unroll
+            for (int u = 0; u < NL; ++u) {
+                if (i0 + 4 * u >= n_s || sample_row(i0 + 4 * u) >= r) continue;
+                const float f[8] = {bf16_lo(w[u].x), bf16_hi(w[u].x), bf16_lo(w[u].y), bf16_hi(w[u].y),
+                                    bf16_lo(w[u].z), bf16_hi(w[u].z), bf16_lo(w[u].w), bf16_hi(w[u].w)};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss[e] = fmaf(f[e], f[e], ss[e]);
+            }
+        }
+    }
+    float m = 0.f;                                             // largest sum of squares among this thread's columns
+    if (phase != 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sh[((phase - 1) * 64 + oct) * 8 + e] = ss[e];
+    }
+    __syncthreads();
+    if (phase == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float v = ((ss[e] + sh[oct * 8 + e]) + sh[(64 + oct) * 8 + e]) + sh[(128 + oct) * 8 + e];
+            m = fmaxf(m, v);
+        }
+        // lanes 0..31: the block's first vocabulary tile, lanes 32..63: its second
+        m = fmaxf(m, dpp_f32<0xB1>(m));
+        m = fmaxf(m, dpp_f32<0x4E>(m));
+        m = fmaxf(m, dpp_f32<0x141>(m));
+        m = fmaxf(m, dpp_f32<0x140>(m));
+        uint32_t x, y;
+        swap_pair<16>(__float_as_uint(m), x, y);
+        m = fmaxf(__uint_as_float(x), __uint_as_float(y));
+        // ... and the tile's mean square (its columns' sums added in lane order)
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum += ((ss[e] + sh[oct * 8 + e]) + sh[(64 + oct) * 8 + e]) + sh[(128 + oct) * 8 + e];
+        sum += dpp_f32<0xB1>(sum);
+        sum += dpp_f32<0x4E>(sum);
+        sum += dpp_f32<0x141>(sum);
+        sum += dpp_f32<0x140>(sum);
+        swap_pair<16>(__float_as_uint(sum), x, y);
+        sum = __uint_as_float(x) + __uint_as_float(y);
+        const int vt = 2 * b + (oct >> 5);
+        const int tile_cols = min(256, V - vt * 256);
+        if ((oct & 31) == 0 && tile_cols > 0)
+            tilescale[vt] = make_float2(sqrtf(m / (float)n_s), sum / ((float)n_s * (float)tile_cols));
+    }
+}
+
 // part [slices][n_rt][n_ct][4 wavefronts][16][64] fp32: the accumulators as the wavefronts hold them; wavefront
 // (wr, wc) of tile (rt, ct) owns rows 64 rt + 32 wr + lane % 32 and, for element i, column
 // 64 ct + 32 wc + 8 (i / 4) + 4 (lane / 32) + i % 4.
@@ -57,6 +134,7 @@ __global__ __launch_bounds__(256) void down_tile_kernel(
     extern __shared__ __align__(1024) unsigned char lds_raw[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)lds_raw);
     const int tid = threadIdx.x, lane = tid & 63;
+
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, wc = wave & 1;
 
@@ -144,32 +222,24 @@ __global__ __launch_bounds__(256) void down_tile_kernel(
 //   t16   [8 ceil(r / 64), rows_pad]   16-byte vectors of 8 values t log2(e) in bf16 or f16 (round to nearest even),
 //                                      zero for k >= r and for padding rows
 //   stat  [2 ceil(r / 64), rows_pad]   per 32-column piece: (sum of (t - its 16-bit value)^2, sum of t^2) of its entries
-//   bsq   [4 n_rt_pad n_ct]        per block: sum of squares of its share of a fixed sample of B (kBrmsPositions
-//                                  16-byte vectors of every row of B, at column positions spread over V)
 __global__ __launch_bounds__(256) void down_finish_kernel(
     const float *__restrict__ part, const uint16_t *__restrict__ h, const uint16_t *__restrict__ A,
     int rows, int rows_pad, int d, int r,
     float *__restrict__ t32, uint4 *__restrict__ t16, float2 *__restrict__ stat,
-    const uint16_t *__restrict__ B, int V, float *__restrict__ bsq, int as_f16, DownGrid g)
+    const uint16_t *__restrict__ B, int V, float2 *__restrict__ tilescale, int as_f16, DownGrid g)
 {
     __shared__ float tile[32 * 33];
     __shared__ float red_a[4 * 32], red_b[4 * 32];
-    __shared__ float red_s[4];
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    __shared__ float colsh[3 * 64 * 8];
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x >= 4 * g.n_rt_pad * g.n_ct) {
+        // (next to the tile kernel's blocks instead, these blocks cost 6.7 us at 512 rows; here 2-3)
+        column_scale_block(B, r, V, tilescale, (int)blockIdx.x - 4 * g.n_rt_pad * g.n_ct, colsh, tid);
+        return;
+    }
     const int piece = blockIdx.x;                              // ((rt * n_ct + ct) * 4 + wave of the tile kernel)
     const int w = piece & 3, ct = (piece >> 2) % g.n_ct, rt = (piece >> 2) / g.n_ct;      // rt < n_rt_pad; no partial sums exist for rt >= n_rt
     const int row0 = rt * kDT + 32 * (w >> 1), n0 = ct * kDT + 32 * (w & 1);
-
-    // this block's share of the sample of B, asked for first (it is cold in HBM)
-    const int n_sample = r * kBrmsPositions, n_blocks = 4 * g.n_rt_pad * g.n_ct;
-    const int per_block = (n_sample + n_blocks - 1) / n_blocks;                       // <= 256
-    const int q = piece * per_block + tid;
-    uint4 bw = make_uint4(0u, 0u, 0u, 0u);
-    if (tid < per_block && q < n_sample) {
-        const int j = q / kBrmsPositions, pos = q % kBrmsPositions;
-        const int col = (int)(((long long)pos * (V / 8)) / kBrmsPositions) * 8;
-        bw = *reinterpret_cast<const uint4 *>(B + (size_t)j * V + col);
-    }
 
     // the slices, in order: several loads of a thread are in flight together (they come from other CUs' writes)
     const size_t slice_stride = (size_t)g.n_rt * g.n_ct * 4 * (16 * 64);
@@ -251,18 +321,7 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
         red_a[grp * 32 + row] = a;
         red_b[grp * 32 + row] = b;
     }
-    // the sample of B
-    {
-        const float f[8] = {bf16_lo(bw.x), bf16_hi(bw.x), bf16_lo(bw.y), bf16_hi(bw.y),
-                            bf16_lo(bw.z), bf16_hi(bw.z), bf16_lo(bw.w), bf16_hi(bw.w)};
-        float a = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) a += f[e] * f[e];
-        a = wave_sum(a);
-        if (lane == 0) red_s[wv] = a;
-    }
     __syncthreads();
-    if (tid == 0) bsq[piece] = ((red_s[0] + red_s[1]) + red_s[2]) + red_s[3];
     if (tid < 32)
         stat[(size_t)(n0 >> 5) * rows_pad + row0 + tid] =
             make_float2(((red_a[tid] + red_a[32 + tid]) + red_a[64 + tid]) + red_a[96 + tid],
@@ -271,7 +330,7 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
 
 hipError_t launch_down_projection_tiles(const uint16_t *h, const uint16_t *A, float *part, const DownGrid &g,
                                         int rows, int rows_pad, int d, int r,
-                                        float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *bsq,
+                                        float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float2 *tilescale,
                                         bool as_f16, hipStream_t st)
 {
     static LdsLimit lds_limit;
@@ -282,8 +341,8 @@ hipError_t launch_down_projection_tiles(const uint16_t *h, const uint16_t *A, fl
     const int blocks = g.slices >= 8 ? tiles * g.slices : 8 * ((tiles + 8 / g.slices - 1) / (8 / g.slices));
     down_tile_kernel<<<blocks, 256, kDLds, st>>>(h, A, part, rows, d, r, g);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    down_finish_kernel<<<4 * g.n_rt_pad * g.n_ct, 256, 0, st>>>(part, h, A, rows, rows_pad, d, r, t32, static_cast<uint4 *>(t16), stat,
-                                                  B, V, bsq, as_f16 ? 1 : 0, g);
+    down_finish_kernel<<<4 * g.n_rt_pad * g.n_ct + (V + 511) / 512, 256, 0, st>>>(
+        part, h, A, rows, rows_pad, d, r, t32, static_cast<uint4 *>(t16), stat, B, V, tilescale, as_f16 ? 1 : 0, g);
     return hipGetLastError();
 }
 

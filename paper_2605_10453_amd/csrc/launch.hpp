@@ -49,10 +49,11 @@ constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial
 // t = h A for up to 512 rows: 64 x 64 tiles over slices of the contraction (partial tiles in `part`), then the
 // fixed-order sum of the slices: fp32 t, the 16-bit operand t log2(e) (bf16, or f16 when as_f16) in the k-grouped
 // layout of head_tile_kernel (zero beyond r and beyond the last row), per-row rounding statistics per 32 columns,
-// and per 32 x 32 piece the sum of squares of its share of a fixed sample of B (bsq [4 n_rt_pad n_ct])
+// and per 256-column vocabulary tile (the largest column rms, the mean square) of B over a sample of its rows
+// (tilescale [ceil(V / 256)])
 hipError_t launch_down_projection_tiles(const uint16_t *h, const uint16_t *A, float *part, const DownGrid &g,
                                         int rows, int rows_pad, int d, int r,
-                                        float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float *bsq,
+                                        float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float2 *tilescale,
                                         bool as_f16, hipStream_t st);
 
 // vocabulary projection with the fused epilogue, stages loaded straight into LDS; X is 16-byte vectors of 8 contraction
@@ -75,7 +76,7 @@ hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pa
 // two more launches that spread the column gathers over many CUs (worth it for long contractions only)
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
-                                const float2 *stat, int n_stat, int rows_pad, const float *bsq, int n_bsq, int k,
+                                const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, void *defer_buf, hipStream_t st);
 
 }  // namespace slimspec

@@ -6,8 +6,9 @@
 //   * L listed groups of 16 logits: the group maximum x (its low 4 bits name its position in the
 //     group), the second largest value y of the group, a tag naming the group;
 //   * U: an upper bound of every logit in its unlisted groups.
-// Let tau be the k-th largest listed maximum and eps a bound of |computed - exact|.  Every logit
-// that can be among the exact top-k is computed >= tau - 2 eps =: theta.  The block therefore
+// Let tau be the k-th largest listed maximum and eps_v a bound of |computed - exact| for column v (the same for
+// all columns of a 256-column vocabulary tile: see below), eps the largest of them.  Every logit that can be among
+// the exact top-k is computed >= tau - eps - eps_v, in particular >= tau - 2 eps =: theta.  The block therefore
 // collects (a) listed maxima >= theta, (b) the other 15 members of listed groups whose second
 // largest value reaches theta, (c) all members of unlisted groups of streams with U >= theta
 // (b and c are rare), evaluates exactly, in fp32 from the fp32 contraction input, every
@@ -33,8 +34,12 @@ constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are em
 constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
 constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes the exhaustive exact pass
 constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
-constexpr float kEpsSigmas = 4.0f;      // eps = this many standard deviations of the rounding error of t
-                                        // (values are re-evaluated when within 2 eps = 5.6 sigma of their difference)
+constexpr float kEpsSigmas = 4.0f;      // eps_v = this many standard deviations of the rounding error of t in column v
+                                        // (values are re-evaluated when within eps_a + eps_b = 5.6 sigma of their difference)
+constexpr float kTileMaxBias = 1.35f;   // expected largest / true of 256 column rms estimates from 32 samples each
+constexpr int kTsCap = 4096;            // vocabulary tiles whose column scale is kept in shared memory (1 M columns)
+constexpr float kEpsViolation = 1.5f;   // a re-evaluated value further than this many eps_v from its computed value
+                                        // shows that the bound does not hold for this input: the row is done exhaustively
 
 // Deferred exact evaluation (long contractions, i.e. the full head).  A column of M is one 2-byte element per row,
 // every row in a cache line and mostly a page of its own; one block (one CU) gets through only about 160 such lines
@@ -48,17 +53,18 @@ constexpr int kDeferNeed = 1280;        // columns to evaluate per parked row, a
 constexpr int kDeferWork = 1536;        // collected logits per parked row, at most
 constexpr int kDeferSlices = 16;        // blocks that share one row's gathers (slices of the contraction)
 constexpr int kDeferHeader = 16;        // ints: [0] n_need (0: not parked), [1] n_work, [2] S, [3] Mx, [4] lse (floats)
-constexpr size_t kDeferRowInts = kDeferHeader + kDeferNeed + 2 * kDeferWork + (size_t)kDeferSlices * kDeferNeed;
+constexpr size_t kDeferRowInts = kDeferHeader + kDeferNeed + 3 * kDeferWork + (size_t)kDeferSlices * kDeferNeed;
 
-struct ParkedRow { int *hdr, *need, *id; float *val, *part; };     // part: [kDeferSlices][kDeferNeed]
+struct ParkedRow { int *hdr, *need, *id; float *val, *eps, *part; };     // part: [kDeferSlices][kDeferNeed]
 __device__ __forceinline__ ParkedRow parked_row(int *defer, int row) {
-    ParkedRow p{nullptr, nullptr, nullptr, nullptr, nullptr};
+    ParkedRow p{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     if (defer) {
         p.hdr = defer + (size_t)row * kDeferRowInts;
         p.need = p.hdr + kDeferHeader;
         p.id = p.need + kDeferNeed;
         p.val = reinterpret_cast<float *>(p.id + kDeferWork);
-        p.part = p.val + kDeferWork;
+        p.eps = p.val + kDeferWork;
+        p.part = p.eps + kDeferWork;
     }
     return p;
 }
@@ -92,7 +98,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const float *__restrict__ part, int nsr, int gw, int n_vt,
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
-    const float2 *__restrict__ stat, int n_stat, int rows_pad, const float *__restrict__ bsq, int n_bsq,
+    const float2 *__restrict__ stat, int n_stat, int rows_pad, const float2 *__restrict__ tilescale,
     int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
     int *__restrict__ defer, int resume)
 {
@@ -108,10 +114,16 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     float *w_val = reinterpret_cast<float *>(w_id + kWorkCap);          // [kWorkCap]
     int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]     0 no, 1 / 2 yes; later: list of items to evaluate
     float *w_apx = reinterpret_cast<float *>(w_need + kWorkCap);        // [kWorkCap]     change of the item's term of the sum of exp; later by rank
-    float *xrow = w_apx + kWorkCap;                                     // [K]            the row's exact contraction input
+    float *w_eps = w_apx + kWorkCap;                                    // [kWorkCap]     the item's bound eps_v
+    float *ts = w_eps + kWorkCap;                                       // [min(n_vt, kTsCap)]  column scale of B per vocabulary tile
+    const bool ts_cached = n_vt <= kTsCap;                              // a larger vocabulary uses the largest scale for every tile
+    float *xrow = ts + ((min(n_vt, kTsCap) + 3) & ~3);                  // [K]            the row's exact contraction input
     __shared__ float red_m[NWAVES], red_s[NWAVES];
     __shared__ uint64_t tau_key;
     __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden, cnt_need;
+    __shared__ int tau_slot, eps_violated;
+    __shared__ uint64_t thr_key;
+    __shared__ uint32_t cnt_buf;
     __shared__ uint32_t winners[SLIMSPEC_KMAX_INTERNAL];
 
     const int row = blockIdx.x;
@@ -123,7 +135,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     ctx.x_is_bf16 = x_is_bf16; ctx.M = M; ctx.K = K; ctx.V = V;
     const ParkedRow pk = parked_row(defer, row);
     int *const park = pk.hdr, *const park_need = pk.need, *const park_id = pk.id;
-    float *const park_val = pk.val, *const park_part = pk.part;
+    float *const park_val = pk.val, *const park_eps = pk.eps, *const park_part = pk.part;
 
     // The tail of the row's merge once every collected logit has its final value: rank the collected set, correct
     // the sum of exp by the changes of the re-evaluated terms (summed in rank order: a fixed order), write.
@@ -147,308 +159,20 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         }
     };
     // A listed maximum had its computed value in the streams' sum of exp: remember by how much its term changes.
+    // ... and check it against the bound that decided what to re-evaluate.
     const auto take_exact = [&](int entry, float z, float Mx) {
         const int item = entry & (kListedBit - 1);
-        if (entry & kListedBit) w_apx[item] = __builtin_amdgcn_exp2f(z * kLog2e - Mx) - __builtin_amdgcn_exp2f(w_val[item] * kLog2e - Mx);
+        if (entry & kListedBit) {
+            if (fabsf(z - w_val[item]) > kEpsViolation * w_eps[item]) eps_violated = 1;
+            w_apx[item] = __builtin_amdgcn_exp2f(z * kLog2e - Mx) - __builtin_amdgcn_exp2f(w_val[item] * kLog2e - Mx);
+        }
         w_val[item] = z;
     };
 
-    if (resume) {
-        // second launch: only rows parked by the first one; their columns have been evaluated in between
-        const int n_need = park[0];
-        if (n_need == 0) return;
-        const int n_work = park[1];
-        const float S = __int_as_float(park[2]), Mx = __int_as_float(park[3]), lse = __int_as_float(park[4]);
-        for (int c = tid; c < n_work; c += NT) { w_id[c] = park_id[c]; w_val[c] = park_val[c]; w_apx[c] = 0.f; }
-        __syncthreads();
-        for (int i = tid; i < n_need; i += NT) {           // every entry names its own item: no two threads share a slot
-            float z = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < kDeferSlices; ++ks) z += park_part[ks * kDeferNeed + i];      // fixed order
-            take_exact(park_need[i], z, Mx);
-        }
-        __syncthreads();
-        finish(n_work, S, Mx, lse);
-        return;
-    }
-    if (tid == 0) {
-        tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; cnt_need = 0u;
-        if (park) park[0] = 0;                              // not parked, unless decided otherwise below
-    }
-
-    // a stream record as three 16-byte loads; the thread's first stream stays in registers
-    static_assert(REC == 12, "three float4 per record");
-    typedef float f32x4 __attribute__((ext_vector_type(4)));      // native vectors stay in registers (a float4 array did not)
-    const f32x4 *mine_src = reinterpret_cast<const f32x4 *>(rec + (size_t)min(tid, nsr - 1) * REC);
-    const f32x4 mine0 = mine_src[0], mine1 = mine_src[1], mine2 = mine_src[2];
-    auto load_rec = [&](int sidx, float (&f)[REC]) {
-        f32x4 a = mine0, b = mine1, c = mine2;
-        if (sidx != tid) {
-            const f32x4 *src = reinterpret_cast<const f32x4 *>(rec + (size_t)sidx * REC);
-            a = src[0]; b = src[1]; c = src[2];
-        }
-        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
-        f[8] = c.x; f[9] = c.y; f[10] = c.z; f[11] = c.w;
-    };
-
-    // ---- log-sum-exp of the streams, and the squared norm of the row's contraction input
-    float m_t = kNegInf, s_t = 0.f, x2 = 0.f, x1 = 0.f;
-    for (int sidx = tid; sidx < nsr; sidx += NT) {
-        float f[REC];
-        load_rec(sidx, f);
-        const float mc = f[0], s = f[1];
-        if (s > 0.f) {
-            const float m_new = fmaxf(m_t, mc);
-            s_t = s_t * __builtin_amdgcn_exp2f(m_t - m_new) + s * __builtin_amdgcn_exp2f(mc - m_new);
-            m_t = m_new;
-        }
-    }
-    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
-    __shared__ float stat_sh[64];
-    // rms of B from the down-projection's partial sums of squares over a fixed sample (added in a fixed order;
-    // asked for early: by the time eps needs it, it has arrived)
-    __shared__ float b_rms_sh;
-    if (stat != nullptr && wave == NWAVES - 1) {
-        float a = 0.f;
-        for (int i = lane; i < n_bsq; i += 64) a += bsq[i];
-        a = wave_sum(a);
-        if (lane == 0) b_rms_sh = sqrtf(a / (float)(K * kBrmsPositions * 8));
-    }
-    if (stat != nullptr && tid < n_stat && tid < 64) stat_sh[tid] = stat[(size_t)tid * rows_pad + row].x;
-    const float m_w = wave_max(m_t);
-    float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
-    s_w = wave_sum(s_w);
-    x2 = wave_sum(x2);
-    x1 = wave_sum(x1);
-    if (lane == 0) { red_m[wave] = m_w; red_s[wave] = s_w; }
-    __shared__ float red_x[NWAVES];
-    __shared__ float red_x1[NWAVES];
-    if (lane == 0) { red_x[wave] = x2; red_x1[wave] = x1; }
-    // ---- keys of the listed maxima
-    for (int sidx = tid; sidx < nsr; sidx += NT) {
-        float f[REC];
-        load_rec(sidx, f);
-#pragma unroll
-        for (int l = 0; l < L; ++l) {
-            const float x = f[3 + 3 * l];
-            keys[sidx * L + l] = (x > kNoValue) ? make_key(mask4(x) * unit, (uint32_t)(sidx * L + l)) : kNoKey;
-        }
-    }
-    for (int sidx = tid; sidx < ngroups * 64; sidx += NT) hkeys[sidx] = (sidx < nsr) ? keys[sidx * L] : kNoKey;   // own writes
-    __syncthreads();
-    float Mx = red_m[0], X2 = 0.f, X1 = 0.f;
-#pragma unroll
-    for (int w = 1; w < NWAVES; ++w) Mx = fmaxf(Mx, red_m[w]);
-    float S = 0.f;
-#pragma unroll
-    for (int w = 0; w < NWAVES; ++w) {
-        S += (red_m[w] == kNegInf) ? 0.f : red_s[w] * __builtin_amdgcn_exp2f(red_m[w] - Mx);
-        X2 += red_x[w];
-        X1 += red_x1[w];
-    }
-    const float lse = (Mx + __builtin_amdgcn_logf(S)) * kLn2;
-
-    if (X2 == 0.f) {
-        // zero contraction input (for instance a padded batch slot): every logit is exactly +0
-        if (tid < k) {
-            out_ids[(size_t)row * k + tid] = tid;
-            out_logprobs[(size_t)row * k + tid] = -__builtin_amdgcn_logf((float)V) * kLn2;
-        }
-        return;
-    }
-    // ---- tau: the k-th largest listed maximum.  The lists are sorted, so first T = the k-th largest of the
-    // streams' heads (best k of every 64 heads, then all pairs); every listed maximum >= T (at most 3 k of them,
-    // all of them if there are fewer than k heads) is a candidate, and tau is the k-th largest candidate.
-    for (int e = tid; e < nsr; e += NT) {
-        const uint64_t mine = hkeys[e];
-        if (mine == kNoKey) continue;
-        const uint4 *grp = reinterpret_cast<const uint4 *>(hkeys + (e & ~63));      // 64 keys, two per 16-byte read
-        int rank = 0;
-#pragma unroll
-        for (int q = 0; q < 32; ++q) {
-            const uint4 v = grp[q];
-            rank += (u64_from(v.y, v.x) > mine ? 1 : 0) + (u64_from(v.w, v.z) > mine ? 1 : 0);
-        }
-        if (rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
-    }
-    __syncthreads();
-    const int n_surv = (int)cnt_surv;
-    __shared__ uint64_t head_bound;
-    __shared__ uint32_t cnt_cand;
-    if (tid == 0) { head_bound = kNoKey; cnt_cand = 0u; }
-    __syncthreads();
-    rank_all_pairs(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) head_bound = key; });
-    __syncthreads();
-    const uint64_t T = head_bound;                                       // kNoKey (smallest): fewer than k heads
-    __syncthreads();                                                     // surv is reused below
-    for (int e = tid; e < n; e += NT) {
-        const uint64_t mine = keys[e];
-        if (mine != kNoKey && mine >= T) surv[atomicAdd(&cnt_cand, 1u)] = mine;
-    }
-    __syncthreads();
-    rank_all_pairs(surv, (int)cnt_cand, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
-    __syncthreads();
-    const bool have_tau = tau_key != kNoKey;
-    const float tau = have_tau ? key_value(tau_key) : kNegInf;
-    float eps;
-    if (stat != nullptr) {
-        float dt2 = 0.f;                                     // squared norm of t - f16(t), summed in a fixed order
-        for (int q = 0; q < n_stat; ++q) dt2 += (q < 64) ? stat_sh[q] : stat[(size_t)q * rows_pad + row].x;
-        // + weights the kernel flushed to zero (magnitude below tiny_w) times the 1-norm of the contraction input
-        eps = kEpsSigmas * sqrtf(dt2) * b_rms_sh + fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
-    }
-    else eps = fabsf(tau) * 1.6e-5f + 1e-6f;
-    const float theta = have_tau ? tau - 2.f * eps : kNegInf;
-    // a computed value may be off by eps: beyond this bound the winners' log-probabilities take the exact value
-    const bool exact_all = eps > kExactWinnersEps;
-    // Overflow of the 16-bit input; or a rounding bound so wide that the streams' sum of exponentials (whose terms
-    // are off by up to a factor e^eps) no longer gives the log-sum-exp to the reported precision, and the
-    // correction by the re-evaluated terms could itself overflow.
-    bool exhaustive = !(eps < kExhaustiveEps) || !(lse == lse) || !(fabsf(lse) < 1e30f);
-
-    // ---- collect
-    auto push = [&](int id, float val, int need) {
-        const uint32_t slot = atomicAdd(&cnt_work, 1u);
-        if (slot < (uint32_t)kWorkCap) { w_id[slot] = id; w_val[slot] = val; w_need[slot] = need; w_apx[slot] = 0.f; }
-        if (need) atomicAdd(&cnt_hidden, 1u);
-    };
-    // column of member i of a group: MFMA tile (tag & 7) of vocabulary tile (tag >> 3) covers 32 adjacent columns
-    auto id_of = [&](int tag, int i, int half) {
-        const int pos = 8 * (i >> 2) + 4 * half + (i & 3);
-        return (tag >> 3) * 256 + 32 * (tag & 7) + pos;
-    };
-    if (!exhaustive) {
-        for (int sidx = tid; sidx < nsr; sidx += NT) {
-            float r[REC];
-            load_rec(sidx, r);
-            int listed[L];
-#pragma unroll
-            for (int l = 0; l < L; ++l) {
-                const float x = r[3 + 3 * l], y = r[4 + 3 * l];
-                const int rawtag = __float_as_int(r[5 + 3 * l]);
-                // the tag's lowest bit names the half-wavefront that held the group
-                const int half = rawtag & 1, tag = rawtag >> 1;
-                listed[l] = (x > kNoValue) ? rawtag : -1;
-                if (!(x > kNoValue) || !(mask4(x) * unit >= theta)) continue;
-                const int imax = (int)(__float_as_uint(x) & 15u);
-                const int id_max = id_of(tag, imax, half);
-                if ((unsigned)id_max >= (unsigned)V) continue;      // cannot come from the head kernel: keeps the gathers in bounds whatever the records hold
-                push(id_max, mask4(x) * unit, 0);
-                if (y > kNoValue && mask4(y) * unit >= theta) {
-                    for (int i = 0; i < 16; ++i) {
-                        const int id = id_of(tag, i, half);
-                        if (i != imax && (unsigned)id < (unsigned)V) push(id, 0.f, 1);
-                    }
-                }
-            }
-            const float U = r[2];
-            if (U > kNoValue && mask4(U) * unit >= theta) {
-                // every unlisted group of the stream: record sidx covers vocabulary tiles sidx, sidx + gw, ...
-                for (int vt = sidx; vt < n_vt; vt += gw)
-                    for (int j = 0; j < 8; ++j)
-                        for (int half = 0; half < 2; ++half) {
-                            const int tag = vt * 8 + j;
-                            const int rawtag = tag * 2 + half;
-                            bool is_listed = false;
-#pragma unroll
-                            for (int l = 0; l < L; ++l) is_listed |= (listed[l] == rawtag);
-                            if (is_listed) continue;
-                            for (int i = 0; i < 16; ++i) {
-                                const int id = id_of(tag, i, half);
-                                if (id < V) push(id, 0.f, 1);
-                            }
-                        }
-            }
-        }
-    }
-    __syncthreads();
-    int n_work = (int)cnt_work;
-    if (n_work > kWorkCap || n_work < k) exhaustive = true;
-
-    if (!exhaustive) {
-        // ---- which listed maxima need the exact value
-        const bool any_hidden = cnt_hidden != 0u;
-        for (int c = tid; c < n_work; c += NT) {
-            if (w_need[c]) continue;
-            bool need = any_hidden || exact_all;
-            const float mine = w_val[c];
-            for (int q = 0; q < n_work && !need; ++q)
-                if (q != c && fabsf(w_val[q] - mine) <= 2.f * eps) need = true;
-            if (need) w_need[c] = 2;                      // 2: decided in this pass (w_val still the computed value)
-        }
-        __syncthreads();
-        // list the items to evaluate (any order: every result goes back to its own slot)
-        constexpr int PER = (kWorkCap + NT - 1) / NT;       // fixed trip count: the array stays in registers
-        int my_need[PER];
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-            const int c = tid + i * NT;
-            my_need[i] = (c < n_work && w_need[c]) ? (c | (w_need[c] == 2 ? kListedBit : 0)) : -1;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < PER; ++i)
-            if (my_need[i] >= 0) w_need[atomicAdd(&cnt_need, 1u)] = my_need[i];
-        __syncthreads();
-        if (park && cnt_need != 0u && cnt_need <= (uint32_t)kDeferNeed && n_work <= kDeferWork) {
-            // park the row: collected set, list of columns, the streams' log-sum-exp
-            const int n_need = (int)cnt_need;
-            for (int c = tid; c < n_work; c += NT) { park_id[c] = w_id[c]; park_val[c] = w_val[c]; }
-            for (int c = tid; c < n_need; c += NT) park_need[c] = w_need[c];
-            if (tid == 0) {
-                park[0] = n_need; park[1] = n_work;
-                park[2] = __float_as_int(S); park[3] = __float_as_int(Mx); park[4] = __float_as_int(lse);
-            }
-            return;
-        }
-        // exact fp32 logits, 16 columns at a time: a lane owns (column lane % 16, row phase lane / 16), the
-        // four wavefronts interleave rows, so one load instruction touches 4 rows of M x 16 columns and the
-        // whole block has 16 rows in flight per step; partial sums are combined in a fixed order
-        const int n_need = (int)cnt_need;
-        __shared__ float red_ex[NWAVES][16];
-        for (int g0 = 0; g0 < n_need; g0 += 16) {
-            const int u = lane & 15, jsub = lane >> 4;
-            const int entry = w_need[min(g0 + u, n_need - 1)];
-            const int item = entry & (kListedBit - 1);
-            const int id = w_id[item];
-            float acc = 0.f;
-            // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 8 independent loads per lane
-            const uint16_t *mcol = M + id;
-            constexpr int RSTEP = 4 * NWAVES;
-            for (int j0 = wave * 4 + jsub; j0 < K; j0 += 8 * RSTEP) {
-                uint16_t w[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) w[e] = mcol[(size_t)min(j0 + e * RSTEP, K - 1) * V];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int j = j0 + e * RSTEP;
-                    acc = fmaf(j < K ? xrow[j] : 0.f, bf16_to_float(w[e]), acc);
-                }
-            }
-            uint32_t a, b;
-            swap_pair<16>(__float_as_uint(acc), a, b);
-            acc = __uint_as_float(a) + __uint_as_float(b);
-            swap_pair<32>(__float_as_uint(acc), a, b);
-            acc = __uint_as_float(a) + __uint_as_float(b);
-            if (lane < 16) red_ex[wave][lane] = acc;
-            __syncthreads();
-            if (tid < 16 && g0 + tid < n_need) {
-                float z = red_ex[0][tid];
-#pragma unroll
-                for (int w = 1; w < NWAVES; ++w) z += red_ex[w][tid];
-                take_exact(entry, z, Mx);                 // tid < 16: u == tid, so `entry` is this column's
-            }
-            __syncthreads();
-        }
-        __syncthreads();
-        finish(n_work, S, Mx, lse);
-        return;
-    }
-
     // ---- exhaustive exact pass: every logit of the row in fp32, running top-k in `work`
     // (also recomputes the log-sum-exp, since the streams' sums may have overflowed)
-    __shared__ uint64_t thr_key;
-    __shared__ uint32_t cnt_buf;
+    const auto exhaustive_pass = [&]() {
+    __syncthreads();
     if (tid == 0) { thr_key = kNoKey; cnt_buf = 0u; }
     __syncthreads();
     float em = kNegInf, es = 0.f;
@@ -503,7 +227,339 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         out_ids[(size_t)row * k + tid] = (int)key_tiebreak(work[tid]);
         out_logprobs[(size_t)row * k + tid] = key_value(work[tid]) - lse_exact;
     }
+    };
+
+    if (resume) {
+        // second launch: only rows parked by the first one; their columns have been evaluated in between
+        const int n_need = park[0];
+        if (n_need == 0) return;
+        const int n_work = park[1];
+        const float S = __int_as_float(park[2]), Mx = __int_as_float(park[3]), lse = __int_as_float(park[4]);
+        for (int c = tid; c < n_work; c += NT) { w_id[c] = park_id[c]; w_val[c] = park_val[c]; w_eps[c] = park_eps[c]; w_apx[c] = 0.f; }
+        if (tid == 0) eps_violated = 0;
+        __syncthreads();
+        for (int i = tid; i < n_need; i += NT) {           // every entry names its own item: no two threads share a slot
+            float z = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < kDeferSlices; ++ks) z += park_part[ks * kDeferNeed + i];      // fixed order
+            take_exact(park_need[i], z, Mx);
+        }
+        __syncthreads();
+        if (eps_violated) { exhaustive_pass(); return; }
+        finish(n_work, S, Mx, lse);
+        return;
+    }
+    if (tid == 0) {
+        tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; cnt_need = 0u; tau_slot = -1; eps_violated = 0;
+        if (park) park[0] = 0;                              // not parked, unless decided otherwise below
+    }
+
+    // a stream record as three 16-byte loads; the thread's first stream stays in registers
+    static_assert(REC == 12, "three float4 per record");
+    typedef float f32x4 __attribute__((ext_vector_type(4)));      // native vectors stay in registers (a float4 array did not)
+    const f32x4 *mine_src = reinterpret_cast<const f32x4 *>(rec + (size_t)min(tid, nsr - 1) * REC);
+    const f32x4 mine0 = mine_src[0], mine1 = mine_src[1], mine2 = mine_src[2];
+    auto load_rec = [&](int sidx, float (&f)[REC]) {
+        f32x4 a = mine0, b = mine1, c = mine2;
+        if (sidx != tid) {
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(rec + (size_t)sidx * REC);
+            a = src[0]; b = src[1]; c = src[2];
+        }
+        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+        f[8] = c.x; f[9] = c.y; f[10] = c.z; f[11] = c.w;
+    };
+
+    // ---- log-sum-exp of the streams, and the squared norm of the row's contraction input
+    float m_t = kNegInf, s_t = 0.f, x2 = 0.f, x1 = 0.f;
+    for (int sidx = tid; sidx < nsr; sidx += NT) {
+        float f[REC];
+        load_rec(sidx, f);
+        const float mc = f[0], s = f[1];
+        if (s > 0.f) {
+            const float m_new = fmaxf(m_t, mc);
+            s_t = s_t * __builtin_amdgcn_exp2f(m_t - m_new) + s * __builtin_amdgcn_exp2f(mc - m_new);
+            m_t = m_new;
+        }
+    }
+    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
+    __shared__ float stat_sh[64];
+    // Column scale of B per vocabulary tile (asked for early: by the time eps needs it, it has arrived): the largest
+    // column rms of the tile, and the rms of all of B from the tiles' mean squares (added in a fixed order).
+    float ts_max = 0.f, ts_msq = 0.f;
+    if (tilescale != nullptr)
+        for (int i = tid; i < n_vt; i += NT) {
+            const float2 v = tilescale[i];
+            if (ts_cached) ts[i] = v.x;
+            ts_max = fmaxf(ts_max, v.x);
+            ts_msq += v.y;
+        }
+    __shared__ float red_ts[NWAVES], red_tq[NWAVES];
+    if (stat != nullptr && tid < n_stat && tid < 64) stat_sh[tid] = stat[(size_t)tid * rows_pad + row].x;
+    const float m_w = wave_max(m_t);
+    float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
+    s_w = wave_sum(s_w);
+    x2 = wave_sum(x2);
+    x1 = wave_sum(x1);
+    if (lane == 0) { red_m[wave] = m_w; red_s[wave] = s_w; }
+    __shared__ float red_x[NWAVES];
+    __shared__ float red_x1[NWAVES];
+    ts_max = wave_max(ts_max);
+    ts_msq = wave_sum(ts_msq);
+    if (lane == 0) { red_x[wave] = x2; red_x1[wave] = x1; red_ts[wave] = ts_max; red_tq[wave] = ts_msq; }
+    // ---- keys of the listed maxima
+    for (int sidx = tid; sidx < nsr; sidx += NT) {
+        float f[REC];
+        load_rec(sidx, f);
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+            const float x = f[3 + 3 * l];
+            keys[sidx * L + l] = (x > kNoValue) ? make_key(mask4(x) * unit, (uint32_t)(sidx * L + l)) : kNoKey;
+        }
+    }
+    for (int sidx = tid; sidx < ngroups * 64; sidx += NT) hkeys[sidx] = (sidx < nsr) ? keys[sidx * L] : kNoKey;   // own writes
+    __syncthreads();
+    float Mx = red_m[0], X2 = 0.f, X1 = 0.f;
+#pragma unroll
+    for (int w = 1; w < NWAVES; ++w) Mx = fmaxf(Mx, red_m[w]);
+    float S = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) {
+        S += (red_m[w] == kNegInf) ? 0.f : red_s[w] * __builtin_amdgcn_exp2f(red_m[w] - Mx);
+        X2 += red_x[w];
+        X1 += red_x1[w];
+        ts_max = fmaxf(ts_max, red_ts[w]);
+    }
+    float b_rms = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) b_rms += red_tq[w];
+    b_rms = sqrtf(b_rms / (float)n_vt);
+    const float lse = (Mx + __builtin_amdgcn_logf(S)) * kLn2;
+
+    if (X2 == 0.f) {
+        // zero contraction input (for instance a padded batch slot): every logit is exactly +0
+        if (tid < k) {
+            out_ids[(size_t)row * k + tid] = tid;
+            out_logprobs[(size_t)row * k + tid] = -__builtin_amdgcn_logf((float)V) * kLn2;
+        }
+        return;
+    }
+    // ---- tau: the k-th largest listed maximum.  The lists are sorted, so first T = the k-th largest of the
+    // streams' heads (best k of every 64 heads, then all pairs); every listed maximum >= T (at most 3 k of them,
+    // all of them if there are fewer than k heads) is a candidate, and tau is the k-th largest candidate.
+    for (int e = tid; e < nsr; e += NT) {
+        const uint64_t mine = hkeys[e];
+        if (mine == kNoKey) continue;
+        const uint4 *grp = reinterpret_cast<const uint4 *>(hkeys + (e & ~63));      // 64 keys, two per 16-byte read
+        int rank = 0;
+#pragma unroll
+        for (int q = 0; q < 32; ++q) {
+            const uint4 v = grp[q];
+            rank += (u64_from(v.y, v.x) > mine ? 1 : 0) + (u64_from(v.w, v.z) > mine ? 1 : 0);
+        }
+        if (rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
+    }
+    __syncthreads();
+    const int n_surv = (int)cnt_surv;
+    __shared__ uint64_t head_bound;
+    __shared__ uint32_t cnt_cand;
+    if (tid == 0) { head_bound = kNoKey; cnt_cand = 0u; }
+    __syncthreads();
+    rank_all_pairs(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) head_bound = key; });
+    __syncthreads();
+    const uint64_t T = head_bound;                                       // kNoKey (smallest): fewer than k heads
+    __syncthreads();                                                     // surv is reused below
+    for (int e = tid; e < n; e += NT) {
+        const uint64_t mine = keys[e];
+        if (mine != kNoKey && mine >= T) surv[atomicAdd(&cnt_cand, 1u)] = mine;
+    }
+    __syncthreads();
+    rank_all_pairs(surv, (int)cnt_cand, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
+    __syncthreads();
+    const bool have_tau = tau_key != kNoKey;
+    const float tau = have_tau ? key_value(tau_key) : kNegInf;
+    // eps_v = kEpsSigmas |t - rounded t| (column scale of v's vocabulary tile) + eps_abs: the rounding errors dt_j of t
+    // are taken as independent, so that column v's error sum_j dt_j B[j, v] has standard deviation |dt| rms(B[:, v]);
+    // eps_abs covers the fp32 accumulation, the 4 packed bits and, in f16 mode, the weights the kernel flushed to
+    // zero (magnitude below tiny_w, times the 1-norm of the contraction input).
+    float dt_scale = 0.f, eps_abs;
+    if (stat != nullptr) {
+        float dt2 = 0.f;                                     // squared norm of t - rounded t, summed in a fixed order
+        for (int q = 0; q < n_stat; ++q) dt2 += (q < 64) ? stat_sh[q] : stat[(size_t)q * rows_pad + row].x;
+        dt_scale = kEpsSigmas * sqrtf(dt2);
+        eps_abs = fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
+    }
+    else eps_abs = fabsf(tau) * 1.6e-5f + 1e-6f;
+    // Scale of a tile's columns: the rms of all of B (tens of thousands of sampled entries: no noise to speak of), or
+    // the tile's own largest column rms (32 samples per column: the largest of 256 estimates overshoots by about a
+    // third, which kTileMaxBias takes off again) where that is larger, i.e. where the tile holds columns well above
+    // the average.
+    const auto tile_scale = [&](float tile_max) { return fmaxf(b_rms, tile_max * (1.f / kTileMaxBias)); };
+    const auto eps_of_tile = [&](int vt) {
+        return (stat != nullptr) ? dt_scale * tile_scale(ts_cached ? ts[min(vt, n_vt - 1)] : ts_max) + eps_abs : eps_abs;
+    };
+    const float eps = dt_scale * tile_scale(ts_max) + eps_abs;      // the bound of the vocabulary tile with the largest columns
+    const float theta = have_tau ? tau - 2.f * eps : kNegInf;
+    // Overflow of the 16-bit input; or a rounding bound so wide that the streams' sum of exponentials (whose terms
+    // are off by up to a factor e^eps) no longer gives the log-sum-exp to the reported precision, and the
+    // correction by the re-evaluated terms could itself overflow.
+    bool exhaustive = !(eps < kExhaustiveEps) || !(lse == lse) || !(fabsf(lse) < 1e30f);
+
+    // ---- collect
+    auto push = [&](int id, float val, int need, float e_item) {
+        const uint32_t slot = atomicAdd(&cnt_work, 1u);
+        if (slot < (uint32_t)kWorkCap) { w_id[slot] = id; w_val[slot] = val; w_need[slot] = need; w_apx[slot] = 0.f; w_eps[slot] = e_item; }
+        if (need) atomicAdd(&cnt_hidden, 1u);
+        return slot;
+    };
+    // column of member i of a group: MFMA tile (tag & 7) of vocabulary tile (tag >> 3) covers 32 adjacent columns
+    auto id_of = [&](int tag, int i, int half) {
+        const int pos = 8 * (i >> 2) + 4 * half + (i & 3);
+        return (tag >> 3) * 256 + 32 * (tag & 7) + pos;
+    };
+    if (!exhaustive) {
+        for (int sidx = tid; sidx < nsr; sidx += NT) {
+            float r[REC];
+            load_rec(sidx, r);
+            int listed[L];
+#pragma unroll
+            for (int l = 0; l < L; ++l) {
+                const float x = r[3 + 3 * l], y = r[4 + 3 * l];
+                const int rawtag = __float_as_int(r[5 + 3 * l]);
+                // the tag's lowest bit names the half-wavefront that held the group
+                const int half = rawtag & 1, tag = rawtag >> 1;
+                listed[l] = (x > kNoValue) ? rawtag : -1;
+                if (!(x > kNoValue) || !(mask4(x) * unit >= theta)) continue;
+                const int imax = (int)(__float_as_uint(x) & 15u);
+                const int id_max = id_of(tag, imax, half);
+                if ((unsigned)id_max >= (unsigned)V) continue;      // cannot come from the head kernel: keeps the gathers in bounds whatever the records hold
+                // its own tile's bound decides (theta was the bound of the widest tile)
+                const float e_item = eps_of_tile(tag >> 3);
+                if (!(mask4(x) * unit >= tau - eps - e_item)) continue;
+                const uint32_t slot = push(id_max, mask4(x) * unit, 0, e_item);
+                if (keys[sidx * L + l] == tau_key) tau_slot = (int)slot;      // one writer: keys are unique
+                if (y > kNoValue && mask4(y) * unit >= tau - eps - e_item) {
+                    for (int i = 0; i < 16; ++i) {
+                        const int id = id_of(tag, i, half);
+                        if (i != imax && (unsigned)id < (unsigned)V) push(id, 0.f, 1, e_item);
+                    }
+                }
+            }
+            const float U = r[2];
+            if (U > kNoValue && mask4(U) * unit >= theta) {
+                // every unlisted group of the stream: record sidx covers vocabulary tiles sidx, sidx + gw, ...
+                for (int vt = sidx; vt < n_vt; vt += gw)
+                    for (int j = 0; j < 8; ++j)
+                        for (int half = 0; half < 2; ++half) {
+                            const int tag = vt * 8 + j;
+                            const int rawtag = tag * 2 + half;
+                            bool is_listed = false;
+#pragma unroll
+                            for (int l = 0; l < L; ++l) is_listed |= (listed[l] == rawtag);
+                            if (is_listed) continue;
+                            for (int i = 0; i < 16; ++i) {
+                                const int id = id_of(tag, i, half);
+                                if (id < V) push(id, 0.f, 1, eps_of_tile(vt));
+                            }
+                        }
+            }
+        }
+    }
+    __syncthreads();
+    int n_work = (int)cnt_work;
+    if (n_work > kWorkCap || n_work < k) exhaustive = true;
+
+    if (!exhaustive) {
+        // ---- which listed maxima need the exact value
+        const bool any_hidden = cnt_hidden != 0u;
+        for (int c = tid; c < n_work; c += NT) {
+            if (w_need[c]) continue;
+            // a computed value may be off by its eps_v: beyond kExactWinnersEps a log-probability takes the exact value
+            const float mine = w_val[c], e_mine = w_eps[c];
+            bool need = any_hidden || e_mine > kExactWinnersEps;
+            for (int q = 0; q < n_work && !need; ++q)
+                if (q != c && fabsf(w_val[q] - mine) <= w_eps[q] + e_mine) need = true;
+            if (need) w_need[c] = 2;                      // 2: decided in this pass (w_val still the computed value)
+        }
+        __syncthreads();
+        // list the items to evaluate (any order: every result goes back to its own slot)
+        constexpr int PER = (kWorkCap + NT - 1) / NT;       // fixed trip count: the array stays in registers
+        int my_need[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int c = tid + i * NT;
+            my_need[i] = (c < n_work && w_need[c]) ? (c | (w_need[c] == 2 ? kListedBit : 0)) : -1;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER; ++i)
+            if (my_need[i] >= 0) w_need[atomicAdd(&cnt_need, 1u)] = my_need[i];
+        __syncthreads();
+        // No item to evaluate: the k-th listed maximum is evaluated all the same, so that every row checks the bound
+        // it relied on against one exact value at least (take_exact).
+        if (cnt_need == 0u && tau_slot >= 0 && tau_slot < n_work && stat != nullptr) {
+            __syncthreads();
+            if (tid == 0) { w_need[0] = tau_slot | kListedBit; cnt_need = 1u; }
+            __syncthreads();
+        }
+        if (park && cnt_need != 0u && cnt_need <= (uint32_t)kDeferNeed && n_work <= kDeferWork) {
+            // park the row: collected set, list of columns, the streams' log-sum-exp
+            const int n_need = (int)cnt_need;
+            for (int c = tid; c < n_work; c += NT) { park_id[c] = w_id[c]; park_val[c] = w_val[c]; park_eps[c] = w_eps[c]; }
+            for (int c = tid; c < n_need; c += NT) park_need[c] = w_need[c];
+            if (tid == 0) {
+                park[0] = n_need; park[1] = n_work;
+                park[2] = __float_as_int(S); park[3] = __float_as_int(Mx); park[4] = __float_as_int(lse);
+            }
+            return;
+        }
+        // exact fp32 logits, 16 columns at a time: a lane owns (column lane % 16, row phase lane / 16), the
+        // four wavefronts interleave rows, so one load instruction touches 4 rows of M x 16 columns and the
+        // whole block has 16 rows in flight per step; partial sums are combined in a fixed order
+        const int n_need = (int)cnt_need;
+        __shared__ float red_ex[NWAVES][16];
+        for (int g0 = 0; g0 < n_need; g0 += 16) {
+            const int u = lane & 15, jsub = lane >> 4;
+            const int entry = w_need[min(g0 + u, n_need - 1)];
+            const int item = entry & (kListedBit - 1);
+            const int id = w_id[item];
+            float acc = 0.f;
+            // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 8 independent loads per lane
+            const uint16_t *mcol = M + id;
+            constexpr int RSTEP = 4 * NWAVES;
+            for (int j0 = wave * 4 + jsub; j0 < K; j0 += 8 * RSTEP) {
+                uint16_t w[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e] = mcol[(size_t)min(j0 + e * RSTEP, K - 1) * V];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int j = j0 + e * RSTEP;
+                    acc = fmaf(j < K ? xrow[j] : 0.f, bf16_to_float(w[e]), acc);
+                }
+            }
+            uint32_t a, b;
+            swap_pair<16>(__float_as_uint(acc), a, b);
+            acc = __uint_as_float(a) + __uint_as_float(b);
+            swap_pair<32>(__float_as_uint(acc), a, b);
+            acc = __uint_as_float(a) + __uint_as_float(b);
+            if (lane < 16) red_ex[wave][lane] = acc;
+            __syncthreads();
+            if (tid < 16 && g0 + tid < n_need) {
+                float z = red_ex[0][tid];
+#pragma unroll
+                for (int w = 1; w < NWAVES; ++w) z += red_ex[w][tid];
+                take_exact(entry, z, Mx);                 // tid < 16: u == tid, so `entry` is this column's
+            }
+            __syncthreads();
+        }
+        __syncthreads();
+        if (!eps_violated) {
+            finish(n_work, S, Mx, lse);
+            return;
+        }
+    }
+    exhaustive_pass();
 }
+
 
 // Partial exact logits of the parked rows: block (ks, row) covers slice ks of the contraction for every column on
 // the row's list, 16 columns at a time (lane = column lane % 16, row phase lane / 16; the four wavefronts interleave
@@ -556,31 +612,32 @@ __global__ __launch_bounds__(256) void exact_cols_kernel(
 
 size_t merge_defer_bytes(int rows) { return sizeof(int) * kDeferRowInts * (size_t)rows; }
 
-size_t merge_streams_lds_bytes(int nsr, int k) {
+size_t merge_streams_lds_bytes(int nsr, int k, int n_vt) {
     const size_t n = (size_t)nsr * kStreamList;
     const size_t ngroups = ((size_t)nsr + 63) / 64;
-    return sizeof(uint64_t) * (n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k + kExhaustCap) + 16u * kWorkCap;
+    return sizeof(uint64_t) * (n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k + kExhaustCap) + 20u * kWorkCap
+           + sizeof(float) * (((size_t)(n_vt < kTsCap ? n_vt : kTsCap) + 3) & ~(size_t)3);
 }
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
-                                const float2 *stat, int n_stat, int rows_pad, const float *bsq, int n_bsq, int k,
+                                const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, void *defer_buf, hipStream_t st)
 {
-    const size_t lds = merge_streams_lds_bytes(nsr, k) + sizeof(float) * (size_t)K;      // + the row's contraction input
+    const size_t lds = merge_streams_lds_bytes(nsr, k, n_vt) + sizeof(float) * (size_t)K;      // + the row's contraction input
     static LdsLimit lds_limit;
     hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(merge_streams_kernel), (int)lds);
     if (e != hipSuccess) return e;
     int *defer = static_cast<int *>(defer_buf);
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, bsq, n_bsq, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs,
                                                            defer, 0);
     if ((e = hipGetLastError()) != hipSuccess || !defer) return e;
     // parked rows: their exact columns on many CUs, then the rest of their merge
     exact_cols_kernel<<<dim3(kDeferSlices, rows), 256, 0, st>>>(defer, xexact, x_is_bf16 ? 1 : 0, ldx, M, K, V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, bsq, n_bsq, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs,
                                                            defer, 1);
     return hipGetLastError();
 }

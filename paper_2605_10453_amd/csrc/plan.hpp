@@ -102,7 +102,6 @@ constexpr size_t kMergeLdsLimit = 160 * 1024 - 1024;
 
 // ---- matrix-core path -------------------------------------------------------------------
 constexpr int kPlanSlotsPerXcd = 32;     // blocks per XCD of the persistent kernel (256 CUs / 8 XCDs)
-constexpr int kBrmsPositions = 4;        // 16-byte vectors sampled per row of B for the rms estimate
 constexpr int kStreamListPlan = 3;       // must equal kStreamList (launch.hpp)
 constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
 
@@ -138,8 +137,7 @@ struct MfmaPlan {
     size_t off_t32 = 0;                  // fp32 [rows_pad, r]
     size_t off_t16 = 0;                  // 16-byte vectors [8 ceil(K / 64), rows_pad]: the head kernel's row operand
     size_t off_stat = 0;                 // float2 [2 ceil(r / 64), rows_pad]
-    size_t off_brms = 0;                 // float [n_bsq]: sums of squares over shares of the sample of B
-    int n_bsq = 0;
+    size_t off_tilescale = 0;            // float2 [n_vt]: (largest column rms, mean square) of B per vocabulary tile
     size_t off_streams = 0;              // fp32 [rows, nsr, kStreamRec]
     size_t off_defer = 0;                // parked rows of the merge (long contractions only; bytes 0 otherwise)
     bool defer = false;
@@ -167,8 +165,7 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
         p.off_stat = off;      off = align_up(off + 2 * sizeof(float) * (size_t)p.rows_pad * 2 * ((r + 63) / 64));
         p.down = make_down_grid(rows, p.rows_pad, d, r);
         p.off_down_part = off; off = align_up(off + sizeof(float) * 4096 * (size_t)p.down.slices * p.down.n_rt * p.down.n_ct);
-        p.n_bsq = 4 * p.down.n_rt_pad * p.down.n_ct;      // one partial sum of squares of B per 32 x 32 piece of t
-        p.off_brms = off;      off = align_up(off + sizeof(float) * (size_t)p.n_bsq);
+        p.off_tilescale = off; off = align_up(off + 2 * sizeof(float) * (size_t)p.n_vt);
     } else {
         p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((d + 63) / 64 * 64));      // h regrouped for the kernel
     }
@@ -182,6 +179,6 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
 // stream records per row (gw of them), and a row whose top-k crowd into one stream pays an exact rescan of that
 // stream: at 512 rows a row still has 128 records or more.
 inline int mfma_max_rows_per_launch(int rows) { return rows > 512 ? 512 : rows; }
-size_t merge_streams_lds_bytes(int nsr, int k);
+size_t merge_streams_lds_bytes(int nsr, int k, int n_vt);
 
 }  // namespace slimspec

@@ -110,10 +110,10 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             float *t32 = reinterpret_cast<float *>(ws + p.off_t32);
             void *t16 = ws + p.off_t16;
             float2 *stat = reinterpret_cast<float2 *>(ws + p.off_stat);
-            float *brms = reinterpret_cast<float *>(ws + p.off_brms);
+            float2 *tilescale = reinterpret_cast<float2 *>(ws + p.off_tilescale);
             const bool tile_f16 = head_tile_f16(k);
             e = launch_down_projection_tiles(hrow, static_cast<const uint16_t *>(A), reinterpret_cast<float *>(ws + p.off_down_part), p.down,
-                                             rows, p.rows_pad, d, r, t32, t16, stat, Mb, V, brms, tile_f16, s);
+                                             rows, p.rows_pad, d, r, t32, t16, stat, Mb, V, tilescale, tile_f16, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
             e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
@@ -121,7 +121,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;      // diagnostic build, timing-only kernel: no result
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, brms, p.n_bsq, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, tilescale, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
                                      (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);
@@ -134,7 +134,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, 0, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
                                      (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);

@@ -287,6 +287,39 @@ def test_side_stream_and_caller_buffers(gpu, oracle_mod):
     assert int((ids == -7).sum()) == ids.numel()
 
 
+# ------------------------------------------------------------------ weights that are not i.i.d. Gaussian
+
+def _non_gaussian_B(kind, cfg, seed):
+    """B for the matrix-core path's error model (the rounding of t to 16 bits is bounded per vocabulary tile from a
+    sample of B): a few columns much larger than the rest, heavy tails, and a periodic pattern over the rows."""
+    x = synth.make_inputs(cfg, seed)
+    rng = np.random.default_rng(seed + 99)
+    B = synth.bf16_bits_to_f32(x.B)
+    if kind == "scaled_columns":
+        cols = rng.choice(cfg.V, 40, replace=False)
+        B[:, cols[:30]] *= np.float32(8.0)                      # exact in bf16
+        B[:, cols[30:]] *= np.float32(32.0)
+    elif kind == "heavy_tailed":
+        B = (rng.standard_t(3, size=B.shape) * (cfg.r ** -0.5) / math.sqrt(3.0)).astype(np.float32)
+    elif kind == "small_every_8th_row":
+        B[::8] *= np.float32(2.0 ** -4)
+    elif kind == "large_every_8th_row_offset_3":
+        B[3::8] *= np.float32(16.0)
+    else:
+        raise ValueError(kind)
+    x.B = synth.f32_to_bf16_bits(B)
+    return x
+
+
+@pytest.mark.parametrize("k", [10, 16])
+@pytest.mark.parametrize("kind", ["scaled_columns", "heavy_tailed", "small_every_8th_row", "large_every_8th_row_offset_3"])
+def test_matrix_core_path_weights_not_gaussian(gpu, oracle_mod, kind, k):
+    cfg = synth.small_config(rows=96, d=256, r=512, V=20008, k=k, peaked_every=6)
+    x = _non_gaussian_B(kind, cfg, seed=500 + k)
+    _, _, _, n_exempt = check_low_rank(gpu, oracle_mod, x, k)
+    print(f"{kind} k={k}: {n_exempt} positions used the tie exemption", flush=True)
+
+
 # ------------------------------------------------------------------ the five workloads at full size
 
 @pytest.mark.parametrize("seed", list(range(10)))
