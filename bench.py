@@ -4,8 +4,10 @@
 One step = one call of the low-rank head (down-projection, vocabulary projection with the
 fused running log-sum-exp / top-k, cross-workgroup merge) through the C ABI on one batch of
 synthetic hidden states, with every input already resident in HBM.  The headline workload is
-the single-row latency shape d=4096, r=512, V=128256, k=10 (C2); the 512-row throughput shape
-(C4) and the full-head comparator are reported in the "extra" object of the same JSON line.
+the single-row latency shape d=4096, r=512, V=128256, k=10 (C2); the other workloads (C3, the
+512-row throughput shape C4 with its rank sweep, C5, 16 and 64 rows, the full-head comparator,
+a warm-cache run, six calls in one HIP graph) are reported in the "extra" object of the same
+JSON line, each with its own roofline entry.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C5] [--quick]
 
@@ -14,6 +16,8 @@ Prints exactly one JSON line on stdout (progress goes to stderr).
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -26,15 +30,33 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 / fp16 matrix peak
 GEMV_MAX_ROWS = 4              # rows up to which the library streams (from 5 rows on: matrix cores)
-
-# HBM bytes per launch of the dominant kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/ (each scaled by the same counter's reading for a plain copy kernel of
-# known size); None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C2": 131990491, "C4": 146981121}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def kernel_sources_digest():
+    """SHA-256 over the library's kernel sources: names the code a counter run was made on."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2605_10453_amd", "csrc")
+    for path in sorted(glob.glob(os.path.join(csrc, "*.hip")) + glob.glob(os.path.join(csrc, "*.hpp"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (profiles/hbm_traffic.json); None unless that summary was made on exactly these kernel sources."""
+    try:
+        rec = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        return None
+    if rec.get("kernel_sources_sha256") != kernel_sources_digest():
+        return None
+    return rec.get("traffic_bytes_per_launch", {}).get(workload)
 
 
 def algorithmic_bytes_low_rank(rows, d, r, V, k):
@@ -46,6 +68,12 @@ def projection_kernel_bytes(rows, K, V):
     """Algorithmic bytes of one launch of the vocabulary-projection kernel: the [K, V] bf16 weight
     matrix once plus its [rows, K] input (fp32 when streaming, 16-bit on the matrix cores)."""
     return 2 * K * V + (4 if rows <= GEMV_MAX_ROWS else 2) * rows * K
+
+
+def percentiles(v):
+    v = sorted(v)
+    n = len(v)
+    return {"median": v[n // 2], "p10": v[max(0, (n * 10) // 100)], "p90": v[min(n - 1, (n * 90) // 100)], "mean": sum(v) / n}
 
 
 def main():
@@ -96,7 +124,18 @@ def main():
         v = sorted(a.elapsed_time(b) for a, b in pairs)
         return v[len(v) // 2]
 
-    def _timed(step, steps, warmup, with_events):
+    def _event_pairs(n):
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in pairs:      # create the HIP handles
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        return pairs
+
+    def _timed(step, steps, warmup, with_events=True):
+        """Wall-clock time of `steps` back-to-back calls; then, in two more passes over the same steps, the
+        per-call durations (an event pair around every call) and the projection kernel's (an event pair
+        recorded by the library around that kernel, on the call's stream)."""
         for i in range(warmup):
             step(i)
         torch.cuda.synchronize()
@@ -105,23 +144,40 @@ def main():
             step(i)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        kern_ms = None
+        kern_ms, call_us = None, None
         if with_events:
-            # The same steps once more, with a HIP event pair recorded by the library around the
-            # projection kernel of every call, on the call's own stream.
-            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                     for _ in range(steps)]
-            for a, b in pairs:      # create the HIP handles
+            pairs = _event_pairs(steps)
+            for i, (a, b) in enumerate(pairs):
                 a.record()
+                step(i)
                 b.record()
             torch.cuda.synchronize()
+            call_us = percentiles([a.elapsed_time(b) * 1e3 for a, b in pairs])
+            pairs = _event_pairs(steps)
             for i, (a, b) in enumerate(pairs):
                 binding.slimspec_set_timing_events(a, b)
                 step(i)
             binding.slimspec_set_timing_events(None, None)
             torch.cuda.synchronize()
             kern_ms = sum(a.elapsed_time(b) for a, b in pairs) / steps
-        return dt, kern_ms
+        return dt, kern_ms, call_us
+
+    def out_buffers(rows, d, r, V, k):
+        ids = torch.empty((rows, k), dtype=torch.int32, device=dev)
+        lp = torch.empty((rows, k), dtype=torch.float32, device=dev)
+        ws = torch.empty(binding.slimspec_workspace_bytes(rows, d, r, V, k), dtype=torch.uint8, device=dev)
+        return ids, lp, ws
+
+    def time_low_rank_tensors(h, As, Bs, k, steps, warmup, with_events=True):
+        rows, d = h.shape
+        r, V = Bs[0].shape
+        ids, lp, ws = out_buffers(rows, d, r, V, k)
+        n = len(Bs)
+
+        def step(i):
+            binding.slimspec_head_topk(h, As[i % n], Bs[i % n], k, out_ids=ids, out_logprobs=lp, workspace=ws)
+
+        return _timed(step, steps, warmup, with_events)
 
     def time_low_rank(cfg, x, steps, warmup, copies, with_events=True):
         h = upload(x.h)
@@ -130,55 +186,69 @@ def main():
         for _ in range(copies - 1):
             As.append(As[0].clone())
             Bs.append(Bs[0].clone())
-        ids = torch.empty((cfg.rows, cfg.k), dtype=torch.int32, device=dev)
-        lp = torch.empty((cfg.rows, cfg.k), dtype=torch.float32, device=dev)
-        ws = torch.empty(binding.slimspec_workspace_bytes(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k),
-                         dtype=torch.uint8, device=dev)
+        return time_low_rank_tensors(h, As, Bs, cfg.k, steps, warmup, with_events)
+
+    def time_full_tensors(h, Ws, k, steps, warmup, with_events=True):
+        rows, d = h.shape
+        V = Ws[0].shape[1]
+        ids, lp, ws = out_buffers(rows, d, 8, V, k)
+        n = len(Ws)
 
         def step(i):
-            binding.slimspec_head_topk(h, As[i % copies], Bs[i % copies], cfg.k,
-                                       out_ids=ids, out_logprobs=lp, workspace=ws)
+            binding.full_head_topk(h, Ws[i % n], k, out_ids=ids, out_logprobs=lp, workspace=ws)
 
         return _timed(step, steps, warmup, with_events)
 
-    def time_full(cfg, x, steps, warmup, copies, with_events=True):
-        h = upload(x.h)
-        Ws = [upload(x.W)]
-        for _ in range(copies - 1):
-            Ws.append(Ws[0].clone())
-        ids = torch.empty((cfg.rows, cfg.k), dtype=torch.int32, device=dev)
-        lp = torch.empty((cfg.rows, cfg.k), dtype=torch.float32, device=dev)
-        ws = torch.empty(binding.slimspec_workspace_bytes(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k),
-                         dtype=torch.uint8, device=dev)
+    def device_inputs(rows, d, r, V, seed, copies, peaked_every=0):
+        """Inputs of the same distributions as the seeded host generator, drawn on the device (the extra
+        workloads are timed only; their values do not matter beyond their distribution)."""
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed)
+        h = torch.randn((rows, d), generator=g, device=dev, dtype=torch.float32)
+        if peaked_every:
+            h[::peaked_every] *= 4.0
+        h = h.to(torch.bfloat16)
+        A = (torch.randn((d, r), generator=g, device=dev, dtype=torch.float32) * d ** -0.5).to(torch.bfloat16)
+        B = torch.empty((r, V), device=dev, dtype=torch.bfloat16)
+        for j0 in range(0, r, 128):
+            j1 = min(r, j0 + 128)
+            B[j0:j1] = (torch.randn((j1 - j0, V), generator=g, device=dev, dtype=torch.float32) * r ** -0.5).to(torch.bfloat16)
+        return h, [A] + [A.clone() for _ in range(copies - 1)], [B] + [B.clone() for _ in range(copies - 1)]
 
-        def step(i):
-            binding.full_head_topk(h, Ws[i % copies], cfg.k, out_ids=ids, out_logprobs=lp, workspace=ws)
-
-        return _timed(step, steps, warmup, with_events)
-
-    def roofline_of(cfg, K, kern_ms, null_ms):
+    def roofline_of(name, rows, K, V, kern_ms, null_ms):
         """Roofline entry of the vocabulary-projection kernel of one call."""
-        kbytes = projection_kernel_bytes(cfg.rows, K, cfg.V)
-        flops = 2.0 * cfg.rows * K * cfg.V
+        kbytes = projection_kernel_bytes(rows, K, V)
+        flops = 2.0 * rows * K * V
         kern_s = kern_ms * 1e-3
-        if cfg.rows > GEMV_MAX_ROWS:
-            ach = flops / kern_s / 1e12
-            out = {"bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                   "frac": ach / MFMA_PEAK_TFLOPS,
-                   "hbm_frac_same_kernel": kbytes / kern_s / 1e9 / HBM_PEAK_GBS}
+        hbm = kbytes / kern_s / 1e9
+        mfma = flops / kern_s / 1e12
+        # the kernel's arithmetic intensity (about `rows` flop per byte) against the ridge of the two peaks (312 flop/B)
+        if flops / kbytes >= MFMA_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+            out = {"bound": "mfma", "achieved": mfma, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                   "frac": mfma / MFMA_PEAK_TFLOPS, "hbm_frac_same_kernel": hbm / HBM_PEAK_GBS}
         else:
-            ach = kbytes / kern_s / 1e9
-            out = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                   "frac": ach / HBM_PEAK_GBS}
-        out.update({"traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            out = {"bound": "hbm", "achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm / HBM_PEAK_GBS,
+                   "mfma_frac_same_kernel": mfma / MFMA_PEAK_TFLOPS}
+        out.update({"traffic": measured_traffic(name),
                     "kernel": "vocabulary projection + running log-sum-exp / top-k "
-                              + ("(head_tile_kernel)" if cfg.rows > GEMV_MAX_ROWS else "(stream_topk_kernel)"),
+                              + ("(head_tile_kernel)" if rows > GEMV_MAX_ROWS else "(stream_topk_kernel)"),
                     "kernel_us": kern_ms * 1e3,
                     "kernel_us_minus_empty_event_pair": (kern_ms - null_ms) * 1e3,
                     "empty_event_pair_us": null_ms * 1e3,
                     "algorithmic_bytes_per_launch": kbytes,
                     "algorithmic_flops_per_launch": flops})
         return out
+
+    def low_rank_entry(name, rows, d, r, V, k, dt, steps, kern_ms, call_us, null_ms):
+        """What is reported for one timed low-rank workload."""
+        us = dt / steps * 1e6
+        flops = 2.0 * rows * (d * r + r * V)
+        return {"shape": {"rows": rows, "d": d, "r": r, "V": V, "k": k},
+                "us_per_call": us, "rows_per_s": rows / (us * 1e-6),
+                "us_per_call_event_pairs": call_us,
+                "call_hbm_frac": algorithmic_bytes_low_rank(rows, d, r, V, k) / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "call_mfma_frac": flops / (us * 1e-6) / 1e12 / MFMA_PEAK_TFLOPS,
+                "roofline": roofline_of(name, rows, r, V, kern_ms, null_ms)}
 
     # ------------------------------------------------------------------ headline workload
     cfg = synth.CONFIGS[args.workload]
@@ -187,7 +257,7 @@ def main():
     copies = max(1, args.copies)
     null_ms = null_event_pair_ms()
     log(f"[bench] timing low-rank head: {args.warmup} warm-up + {args.steps} steps, {copies} weight copies")
-    dt, kern_ms = time_low_rank(cfg, x, args.steps, args.warmup, copies)
+    dt, kern_ms, call_us = time_low_rank(cfg, x, args.steps, args.warmup, copies)
     ms_per_step = dt / args.steps * 1e3
     rows_per_s = cfg.rows * args.steps / dt
     log(f"[bench] {ms_per_step * 1e3:.2f} us/call, {rows_per_s:.1f} rows/s, projection kernel {kern_ms * 1e3:.2f} us "
@@ -198,14 +268,18 @@ def main():
         "value": rows_per_s, "unit": "rows/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "us_per_call": ms_per_step * 1e3,
+        "us_per_call_event_pairs": call_us,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights and hidden states, fp32 accumulate", "data": "synthetic",
+        "dtype": "bf16 weights and hidden states, fp32 accumulate",
+        "data": "synthetic (seeded host generator for the headline workload; the extra workloads draw the same "
+                "distributions on the device)",
         "config": {"workload": f"{cfg.name}: low-rank head rows={cfg.rows} d={cfg.d} r={cfg.r} V={cfg.V} k={cfg.k}, "
                                f"{copies} rotating weight copies (cold last-level cache)",
                    "rows": cfg.rows, "d": cfg.d, "r": cfg.r, "V": cfg.V, "k": cfg.k},
-        "roofline": roofline_of(cfg, cfg.r, kern_ms, null_ms),
+        "roofline": roofline_of(cfg.name, cfg.rows, cfg.r, cfg.V, kern_ms, null_ms),
         "call_hbm_frac": algorithmic_bytes_low_rank(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k)
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "kernel_sources_sha256": kernel_sources_digest(),
     }
 
     if args.copy_probe:
@@ -244,30 +318,39 @@ def main():
     # ------------------------------------------------------------------ extra workloads (context)
     if not (args.quick or args.no_extra):
         extra = {}
+        # the same workload from a warm last-level cache: one copy of the weights, every call re-reads it
+        log("[bench] warm cache (one weight copy)")
+        wdt, wk, wcall = time_low_rank(cfg, x, args.steps, args.warmup, 1)
+        extra["warm_cache"] = {"us_per_call": wdt / args.steps * 1e6, "projection_kernel_us": wk * 1e3,
+                               "us_per_call_event_pairs": wcall, "weight_copies": 1,
+                               "note": "the weights (135 MB at C2) stay in the 256 MB last-level cache between calls"}
+
         log("[bench] full head on the same shape")
-        xf = synth.make_inputs(cfg, seed=0, with_full_head=True)
+        g = torch.Generator(device=dev)
+        g.manual_seed(1)
+        W = torch.empty((cfg.d, cfg.V), device=dev, dtype=torch.bfloat16)
+        for j0 in range(0, cfg.d, 256):
+            W[j0:j0 + 256] = (torch.randn((min(256, cfg.d - j0), cfg.V), generator=g, device=dev) * cfg.d ** -0.5).to(torch.bfloat16)
+        Ws = [W, W.clone()]
+        hdev = upload(x.h)
         nf = max(10, args.steps // 4)
-        fdt, fk = time_full(cfg, xf, nf, 5, 2)
+        fdt, fk, fcall = time_full_tensors(hdev, Ws, cfg.k, nf, 5)
         fms = fdt / nf * 1e3
-        full_cfg_roof = roofline_of(cfg, cfg.d, fk, null_ms)
+        froof = roofline_of(cfg.name + "_full", cfg.rows, cfg.d, cfg.V, fk, null_ms)
         extra["full_head"] = {"us_per_call": fms * 1e3, "projection_kernel_us": fk * 1e3,
-                              "roofline_frac_kernel": full_cfg_roof["frac"], "bound": full_cfg_roof["bound"],
+                              "us_per_call_event_pairs": fcall,
+                              "roofline_frac_kernel": froof["frac"], "bound": froof["bound"],
                               "low_rank_speedup": fms / ms_per_step,
                               "ideal_speedup": 1.0 / ((cfg.r / cfg.d) * (1 + cfg.d / cfg.V)),
                               "paper_relative_head_time_r_d8": 0.21,
                               "paper_hardware": "NVIDIA H200, vLLM 0.17.1 (context only; the paper's head time "
                                                 "excludes softmax / top-k)"}
-        w_bits = xf.W
-        del xf
-        torch.cuda.empty_cache()
         # six head calls (the paper's six draft steps, section 5.1) captured in one HIP graph: no host launch jitter
         try:
             hg = upload(x.h)
             Ag = [upload(x.A) for _ in range(2)]
             Bg = [upload(x.B) for _ in range(2)]
-            idg = torch.empty((cfg.rows, cfg.k), dtype=torch.int32, device=dev)
-            lpg = torch.empty((cfg.rows, cfg.k), dtype=torch.float32, device=dev)
-            wsg = torch.empty(binding.slimspec_workspace_bytes(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k), dtype=torch.uint8, device=dev)
+            idg, lpg, wsg = out_buffers(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k)
             binding.slimspec_head_topk(hg, Ag[0], Bg[0], cfg.k, out_ids=idg, out_logprobs=lpg, workspace=wsg)
             torch.cuda.synchronize()
             eager_ids, eager_lp = idg.clone(), lpg.clone()
@@ -292,29 +375,42 @@ def main():
             del graph
         except Exception as exc:                      # graph capture is a convenience figure only
             extra["graph_of_6_calls"] = {"error": repr(exc)[:200]}
+
         if cfg.name == "C2":
+            # full head on 512 rows first (it shares W with the run above), then the other low-rank workloads
             c4 = synth.CONFIGS["C4"]
-            log("[bench] 512-row throughput shape (C4)")
-            x4 = synth.make_inputs(c4, seed=0)
-            s4 = 50
-            dt4, k4 = time_low_rank(c4, x4, s4, 5, 2)
-            ms4 = dt4 / s4 * 1e3
-            fl4 = 2.0 * c4.rows * (c4.d * c4.r + c4.r * c4.V)
-            r4 = roofline_of(c4, c4.r, k4, null_ms)
-            extra["C4_512_rows"] = {"us_per_call": ms4 * 1e3, "rows_per_s": c4.rows / (ms4 * 1e-3),
-                                    "mfma_frac_call": fl4 / (ms4 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
-                                    "roofline": r4}
-            if c4.d == cfg.d and c4.V == cfg.V:
-                # the full head on the same 512 rows (same kernel, contraction length d): the comparison of section 4.1
-                import types
+            others = [("C3", 1, 5120, 640, 151936, 10, 0, 4, 100), ("C4_512_rows", 512, 4096, 512, 128256, 10, 10, 2, 50),
+                      ("C4_r256", 512, 4096, 256, 128256, 10, 10, 3, 50), ("C4_r1024", 512, 4096, 1024, 128256, 10, 10, 2, 40),
+                      ("C5", 256, 8192, 1024, 128256, 16, 0, 2, 40),
+                      ("rows_16", 16, 4096, 512, 128256, 10, 0, 3, 60), ("rows_64", 64, 4096, 512, 128256, 10, 0, 3, 60)]
+            full512 = None
+            try:
                 log("[bench] full head, 512 rows")
-                sf = 40          # (the first calls after idle run at lower clocks: ten warm-up calls)
-                fdt4, fk4 = time_full(c4, types.SimpleNamespace(h=x4.h, W=w_bits), sf, 10, 2)
-                fms4 = fdt4 / sf * 1e3
-                rf4 = roofline_of(c4, c4.d, fk4, null_ms)
-                extra["C4_512_rows"]["full_head"] = {"us_per_call": fms4 * 1e3, "projection_kernel_us": fk4 * 1e3,
-                                                     "roofline_frac_kernel": rf4["frac"], "bound": rf4["bound"],
-                                                     "low_rank_speedup": fms4 / ms4}
+                h4, _, _ = device_inputs(c4.rows, c4.d, 8, 8, 4, 1, peaked_every=c4.peaked_every)
+                sf = 30          # (the first calls after idle run at lower clocks: ten warm-up calls)
+                fdt4, fk4, fcall4 = time_full_tensors(h4, Ws, c4.k, sf, 10)
+                rf4 = roofline_of("C4_full", c4.rows, c4.d, c4.V, fk4, null_ms)
+                full512 = {"us_per_call": fdt4 / sf * 1e6, "projection_kernel_us": fk4 * 1e3, "us_per_call_event_pairs": fcall4,
+                           "roofline_frac_kernel": rf4["frac"], "bound": rf4["bound"]}
+            except Exception as exc:
+                full512 = {"error": repr(exc)[:200]}
+            del Ws, W
+            torch.cuda.empty_cache()
+            for name, rows, d, r, V, k, peaked, ncopies, nsteps in others:
+                log(f"[bench] {name}: rows={rows} d={d} r={r} V={V} k={k}")
+                try:
+                    h, As, Bs = device_inputs(rows, d, r, V, 7, ncopies, peaked_every=peaked)
+                    edt, ek, ecall = time_low_rank_tensors(h, As, Bs, k, nsteps, 8)
+                    extra[name] = low_rank_entry(name, rows, d, r, V, k, edt, nsteps, ek, ecall, null_ms)
+                    extra[name]["weight_copies"] = ncopies
+                    del h, As, Bs
+                    torch.cuda.empty_cache()
+                except Exception as exc:
+                    extra[name] = {"error": repr(exc)[:200]}
+            if "us_per_call" in extra.get("C4_512_rows", {}) and full512 and "us_per_call" in full512:
+                full512["low_rank_speedup"] = full512["us_per_call"] / extra["C4_512_rows"]["us_per_call"]
+            if "C4_512_rows" in extra:
+                extra["C4_512_rows"]["full_head"] = full512
         out["extra"] = extra
 
     print(json.dumps(out), flush=True)

@@ -523,15 +523,15 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             const int item = entry & (kListedBit - 1);
             const int id = w_id[item];
             float acc = 0.f;
-            // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 8 independent loads per lane
+            // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 16 independent loads per lane (K = 512: one round trip)
             const uint16_t *mcol = M + id;
-            constexpr int RSTEP = 4 * NWAVES;
-            for (int j0 = wave * 4 + jsub; j0 < K; j0 += 8 * RSTEP) {
-                uint16_t w[8];
+            constexpr int RSTEP = 4 * NWAVES, NLD = 16;
+            for (int j0 = wave * 4 + jsub; j0 < K; j0 += NLD * RSTEP) {
+                uint16_t w[NLD];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) w[e] = mcol[(size_t)min(j0 + e * RSTEP, K - 1) * V];
+                for (int e = 0; e < NLD; ++e) w[e] = mcol[(size_t)min(j0 + e * RSTEP, K - 1) * V];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < NLD; ++e) {
                     const int j = j0 + e * RSTEP;
                     acc = fmaf(j < K ? xrow[j] : 0.f, bf16_to_float(w[e]), acc);
                 }
