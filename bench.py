@@ -345,6 +345,23 @@ def main():
                               "paper_relative_head_time_r_d8": 0.21,
                               "paper_hardware": "NVIDIA H200, vLLM 0.17.1 (context only; the paper's head time "
                                                 "excludes softmax / top-k)"}
+        # the static-truncation comparator of Appendix C: the full head over the first V_tr columns with an id map
+        try:
+            trunc = {}
+            for v_tr, nu_paper in ((65536, 0.58), (32768, 0.33), (16384, 0.20)):
+                Wt = [w[:, :v_tr].contiguous() for w in Ws]
+                idm = torch.arange(v_tr, dtype=torch.int32, device=dev)
+                ids_t, lp_t, ws_t = out_buffers(cfg.rows, cfg.d, 8, v_tr, cfg.k)
+                step_t = lambda i: binding.truncated_head_topk(hdev, Wt[i % 2], idm, cfg.k, out_ids=ids_t, out_logprobs=lp_t, workspace=ws_t)
+                tdt, _, tcall = _timed(step_t, nf, 5, with_events=False)
+                trunc[f"V_tr_{v_tr}"] = {"us_per_call": tdt / nf * 1e6, "relative_to_full_head": tdt / fdt,
+                                         "paper_relative_head_time": nu_paper}
+                del Wt
+            trunc["note"] = ("truncated_head_topk on the first V_tr columns; the paper's ratios are VocabTrim / FR-Spec "
+                             "on H200 in vLLM without softmax / top-k (context only)")
+            extra["truncated_head"] = trunc
+        except Exception as exc:
+            extra["truncated_head"] = {"error": repr(exc)[:200]}
         # six head calls (the paper's six draft steps, section 5.1) captured in one HIP graph: no host launch jitter
         try:
             hg = upload(x.h)

@@ -121,6 +121,19 @@ int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
                    void *workspace, size_t workspace_bytes,
                    void *stream);
 
+/* Truncated-vocabulary head (section 2, "Static vocabulary truncation": the drafter's head
+ * restricted to a kept subset V_tr of the vocabulary, plus a token-index map; the baseline
+ * family of Appendix C's VocabTrim / FR-Spec rows): z = h W_tr over the V_tr kept columns only,
+ * W_tr [d, V_tr] row-major (shape->V = V_tr, shape->r ignored), the softmax and the top-k run
+ * over those columns, and the emitted ids are id_map[column].  id_map: device, int32 [V_tr],
+ * read only for the k winners of every row.  Equal logits: smaller COLUMN first.  Everything
+ * else as full_head_topk (workspace: slimspec_workspace_bytes of the same shape). */
+int truncated_head_topk(const void *h, const void *W_tr, slimspec_dtype w_dtype, const int32_t *id_map,
+                        const slimspec_shape *shape, int32_t k,
+                        int32_t *out_ids, float *out_logprobs,
+                        void *workspace, size_t workspace_bytes,
+                        void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *slimspec_status_string(int status);
 

@@ -29,7 +29,7 @@ STATUS_SCRATCH_LIMIT = -5
 STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = (
-    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk",
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk",
     "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.slimspec_head_topk_static.argtypes = [vp, vp, vp, shp, i32, vp, vp, vp]
     lib.full_head_topk.restype = ctypes.c_int
     lib.full_head_topk.argtypes = [vp, vp, ctypes.c_int, shp, i32, vp, vp, vp, sz, vp]
+    lib.truncated_head_topk.restype = ctypes.c_int
+    lib.truncated_head_topk.argtypes = [vp, vp, ctypes.c_int, vp, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_status_string.restype = ctypes.c_char_p
     lib.slimspec_status_string.argtypes = [ctypes.c_int]
     lib.slimspec_last_hip_error.restype = ctypes.c_char_p
@@ -226,6 +228,39 @@ def full_head_topk(h: torch.Tensor, W: torch.Tensor, k: int,
                             _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
                             _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                             _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs
+
+
+def truncated_head_topk(h: torch.Tensor, W_tr: torch.Tensor, id_map: torch.Tensor, k: int,
+                        out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None,
+                        stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Full head over the kept columns W_tr [d, V_tr]; ids come back as id_map[column] (id_map: int32 device [V_tr])."""
+    rows, d = h.shape
+    d2, V = W_tr.shape
+    if d != d2:
+        raise ValueError("shape mismatch between h and W_tr")
+    if h.element_size() != 2:
+        raise ValueError("h must hold bf16 (2-byte) elements")
+    if id_map.dtype != torch.int32 or tuple(id_map.shape) != (V,):
+        raise ValueError("id_map must be int32 [V_tr]")
+    if W_tr.dtype == torch.float32:
+        w_dtype = SLIMSPEC_F32
+    elif W_tr.element_size() == 2:
+        w_dtype = SLIMSPEC_BF16
+    else:
+        raise ValueError("W_tr must be bf16 or float32")
+    out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, 0, V)
+    need = int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k))
+    workspace = _workspace(need, h.device, workspace)
+    st = lib.truncated_head_topk(_dev_ptr(h, "h"), _dev_ptr(W_tr, "W_tr"), w_dtype, _dev_ptr(id_map, "id_map"),
+                                 ctypes.byref(shape), k, _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+                                 _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                 _stream_handle(stream))
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs

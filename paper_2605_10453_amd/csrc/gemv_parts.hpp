@@ -194,7 +194,8 @@ template <int NT>
 __device__ __forceinline__ void merge_row(unsigned char *dyn, bool cache_ids, MergeSmall &S, int tid,
                                           const float2 *__restrict__ ms, const float *__restrict__ pv,
                                           const int *__restrict__ pi, int chunks, int k,
-                                          int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs)
+                                          int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
+                                          const int32_t *__restrict__ id_map)
 {
     constexpr int NWAVES = NT / 64;
     uint64_t *heads = reinterpret_cast<uint64_t *>(dyn);                      // [chunks]
@@ -293,7 +294,8 @@ __device__ __forceinline__ void merge_row(unsigned char *dyn, bool cache_ids, Me
     __syncthreads();
     if (tid < k) {                                      // n_cand >= k whenever k <= V
         const uint32_t e = S.winners[tid];
-        out_ids[tid] = cache_ids ? ids[e] : pi[e];
+        const int id = cache_ids ? ids[e] : pi[e];
+        out_ids[tid] = id_map ? id_map[id] : id;                // truncated vocabulary: column -> vocabulary id
         out_logprobs[tid] = vals[e] - lse;
     }
     __syncthreads();                                    // the buffers may be reused for the next row

@@ -39,8 +39,10 @@ hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_
                               int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st);
 
 // Combine the partials of every row into the final ids and log-probabilities.
+// id_map (may be null): the vocabulary id of every column, for heads over a kept subset of the vocabulary
 hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int *part_id,
-                        int rows, int chunks, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st);
+                        int rows, int chunks, int k, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
+                        hipStream_t st);
 
 // ---- matrix-core path (rows > kGemvMaxRows, bf16 weights) ----
 constexpr int kStreamList = 3;          // groups kept per lane stream
@@ -77,6 +79,7 @@ hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pa
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
-                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, void *defer_buf, hipStream_t st);
+                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
+                                void *defer_buf, hipStream_t st);
 
 }  // namespace slimspec

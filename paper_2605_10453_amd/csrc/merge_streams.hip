@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float2 *__restrict__ tilescale,
     int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
-    int *__restrict__ defer, int resume)
+    const int32_t *__restrict__ id_map, int *__restrict__ defer, int resume)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         const float lse_fixed = (s_fixed > 0.f) ? (Mx + __builtin_amdgcn_logf(s_fixed)) * kLn2 : lse;
         if (tid < k) {
             const uint32_t c = winners[tid];
-            out_ids[(size_t)row * k + tid] = w_id[c];
+            out_ids[(size_t)row * k + tid] = id_map ? id_map[w_id[c]] : w_id[c];
             out_logprobs[(size_t)row * k + tid] = w_val[c] - lse_fixed;
         }
     };
@@ -224,7 +224,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     for (int w = 0; w < NWAVES; ++w) ES += (red_m[w] == kNegInf) ? 0.f : red_s[w] * fast_exp(red_m[w] - EM);
     const float lse_exact = EM + fast_log(ES);
     if (tid < k) {                                          // work[0..k) is sorted by rank
-        out_ids[(size_t)row * k + tid] = (int)key_tiebreak(work[tid]);
+        const int id = (int)key_tiebreak(work[tid]);
+        out_ids[(size_t)row * k + tid] = id_map ? id_map[id] : id;
         out_logprobs[(size_t)row * k + tid] = key_value(work[tid]) - lse_exact;
     }
     };
@@ -338,7 +339,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     if (X2 == 0.f) {
         // zero contraction input (for instance a padded batch slot): every logit is exactly +0
         if (tid < k) {
-            out_ids[(size_t)row * k + tid] = tid;
+            out_ids[(size_t)row * k + tid] = id_map ? id_map[tid] : tid;
             out_logprobs[(size_t)row * k + tid] = -__builtin_amdgcn_logf((float)V) * kLn2;
         }
         return;
@@ -622,7 +623,8 @@ size_t merge_streams_lds_bytes(int nsr, int k, int n_vt) {
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
-                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, void *defer_buf, hipStream_t st)
+                                float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
+                                void *defer_buf, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k, n_vt) + sizeof(float) * (size_t)K;      // + the row's contraction input
     static LdsLimit lds_limit;
@@ -630,14 +632,14 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
     if (e != hipSuccess) return e;
     int *defer = static_cast<int *>(defer_buf);
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
                                                            defer, 0);
     if ((e = hipGetLastError()) != hipSuccess || !defer) return e;
     // parked rows: their exact columns on many CUs, then the rest of their merge
     exact_cols_kernel<<<dim3(kDeferSlices, rows), 256, 0, st>>>(defer, xexact, x_is_bf16 ? 1 : 0, ldx, M, K, V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs,
+                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
                                                            defer, 1);
     return hipGetLastError();
 }

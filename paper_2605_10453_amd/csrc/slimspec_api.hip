@@ -88,7 +88,7 @@ int static_scratch_address(void **out)
 }
 
 int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
-                  const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
+                  const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
                   void *workspace, size_t workspace_bytes, void *stream)
 {
     if (workspace_bytes < mfma_workspace_bytes(kind, shape)) return SLIMSPEC_WORKSPACE_TOO_SMALL;
@@ -122,7 +122,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;      // diagnostic build, timing-only kernel: no result
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, tilescale, k,
-                                     0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
+                                     0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
                                      (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
@@ -135,7 +135,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
-                                     1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k,
+                                     1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
                                      (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, s);
             if (e != hipSuccess) return fail_hip(e);
         }
@@ -145,7 +145,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
 
 int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_is_f32,
              const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
-             void *workspace, size_t workspace_bytes, void *stream)
+             void *workspace, size_t workspace_bytes, void *stream, const int32_t *id_map = nullptr)
 {
     int st = check_shape(kind, shape, k);
     if (st != SLIMSPEC_OK) return st;
@@ -157,7 +157,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         return SLIMSPEC_UNSUPPORTED;
     const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK;
     if (use_mfma)
-        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
+        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, id_map, workspace, workspace_bytes, stream);
     const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
     if (workspace_bytes < p.bytes) return SLIMSPEC_WORKSPACE_TOO_SMALL;
 
@@ -190,7 +190,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         if (e != hipSuccess) return fail_hip(e);
         if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
     }
-    hipError_t e = launch_merge(part_ms, part_val, part_id, p.rows, p.chunks, k, out_ids, out_logprobs, s);
+    hipError_t e = launch_merge(part_ms, part_val, part_id, p.rows, p.chunks, k, out_ids, out_logprobs, id_map, s);
     if (e != hipSuccess) return fail_hip(e);
     return SLIMSPEC_OK;
 }
@@ -268,6 +268,18 @@ int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
     if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
     return run_head(HeadKind::Full, h, nullptr, W, w_dtype == SLIMSPEC_F32, shape, k, out_ids, out_logprobs,
                     workspace, workspace_bytes, stream);
+}
+
+int truncated_head_topk(const void *h, const void *W_tr, slimspec_dtype w_dtype, const int32_t *id_map,
+                        const slimspec_shape *shape, int32_t k,
+                        int32_t *out_ids, float *out_logprobs,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
+    if (!id_map) return SLIMSPEC_INVALID_ARGUMENT;
+    if (reinterpret_cast<uintptr_t>(id_map) & 3u) return SLIMSPEC_UNSUPPORTED;
+    return run_head(HeadKind::Full, h, nullptr, W_tr, w_dtype == SLIMSPEC_F32, shape, k, out_ids, out_logprobs,
+                    workspace, workspace_bytes, stream, id_map);
 }
 
 const char *slimspec_status_string(int status)

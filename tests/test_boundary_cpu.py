@@ -150,3 +150,19 @@ def test_workspace_check_covers_every_batch_of_a_call(lib):
             tail = rows % 512
             if tail >= 5:
                 assert need >= b.slimspec_workspace_bytes(tail, d, r, V, 10), (rows, d, r, V)
+
+
+def test_truncated_head_argument_validation(lib):
+    l, b = lib
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    good = b.SlimspecShape(1, 4096, 0, 65536)
+
+    def call(shape, k, dtype=0, id_map=fake, wsb=1 << 40):
+        return l.truncated_head_topk(fake, fake, dtype, id_map, ctypes.byref(shape), k, fake, fake, fake, wsb, None)
+
+    assert call(good, 10, id_map=null) == b.STATUS_INVALID_ARGUMENT
+    assert call(good, 10, id_map=ctypes.c_void_p(0x1002)) == b.STATUS_UNSUPPORTED        # misaligned
+    assert call(good, 10, dtype=5) == b.STATUS_INVALID_ARGUMENT
+    assert call(good, 0) == b.STATUS_INVALID_ARGUMENT
+    assert call(good, 10, wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
+    assert call(b.SlimspecShape(1, 4096, 0, 65537), 10) == b.STATUS_UNSUPPORTED

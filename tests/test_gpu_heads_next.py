@@ -1,0 +1,65 @@
+"""GPU parity of the heads around the low-rank head (truncated vocabulary, position-specific down-projections,
+router-then-exact) and of the stochastic-decoding outputs, against the CPU fp64 checker.  Same bar as the main
+parity tests: ids identical except where the checker's logits are within 1e-3, log-probabilities within 2e-2."""
+import numpy as np
+import pytest
+
+from paper_2605_10453_amd import synth
+from parity_util import compare_with_oracle, to_dev_bf16, to_dev_f32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    from paper_2605_10453_amd import binding
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    binding.load_library()
+    return torch, binding
+
+
+# ------------------------------------------------------------------ truncated-vocabulary head
+
+@pytest.mark.parametrize("rows,d,V_full,V_tr,k,w_f32", [
+    (1, 256, 20000, 8200, 10, False),       # streaming path
+    (3, 128, 9000, 3080, 7, True),          # fp32 weights
+    (9, 96, 9000, 2056, 6, False),          # matrix-core path, natural-unit mode
+    (70, 128, 12000, 5000, 16, False),
+    (12, 2048, 9000, 4104, 8, False),       # long contraction: parked rows
+])
+def test_truncated_head(gpu, oracle_mod, rows, d, V_full, V_tr, k, w_f32):
+    torch, b = gpu
+    print(f"truncated head rows={rows} d={d} V={V_full} V_tr={V_tr} k={k} f32={w_f32}", flush=True)
+    x = synth.make_inputs(synth.small_config(rows, d, 8, V_full, k, peaked_every=4), seed=40 + rows, with_full_head=True)
+    keep = np.sort(np.random.default_rng(rows).choice(V_full, V_tr, replace=False)).astype(np.int32)
+    id_map = keep[np.random.default_rng(rows + 1).permutation(V_tr)]                # kept columns in an arbitrary order
+    W_tr = np.ascontiguousarray(x.W[:, id_map])
+    if w_f32:
+        W_tr = synth.bf16_bits_to_f32(W_tr)
+    Wd = to_dev_f32(W_tr) if w_f32 else to_dev_bf16(W_tr)
+    ids, lp = b.truncated_head_topk(to_dev_bf16(x.h), Wd, torch.from_numpy(id_map).cuda(), k)
+    torch.cuda.synchronize()
+    ids, lp = ids.cpu().numpy(), lp.cpu().numpy()
+    ora = oracle_mod.truncated_head_topk(x.h, W_tr, id_map, k)
+    # back to columns of W_tr, where the comparator and the checker's logits live
+    col_of = np.full(V_full, -1, np.int64)
+    col_of[id_map] = np.arange(V_tr)
+    assert (col_of[ids] >= 0).all(), "an id outside the kept subset"
+    z_at = lambda ri, ci: oracle_mod.full_logits_at(x.h, W_tr, ri, ci)
+    compare_with_oracle(col_of[ids].astype(np.int32), lp, col_of[ora.ids].astype(np.int32), ora.lse, z_at, V_tr)
+
+
+def test_truncated_head_tied_columns_break_by_column(gpu, oracle_mod):
+    """Identical kept columns: the smaller column wins whatever vocabulary id it maps to."""
+    torch, b = gpu
+    for rows in (2, 12):
+        x = synth.make_inputs(synth.small_config(rows, 64, 8, 1032, 4), seed=3, with_full_head=True)
+        W = x.W.copy()
+        h0 = synth.bf16_bits_to_f64(x.h[0])
+        synth.plant_identical_columns(W, 0.5 * h0 / 8.0, [5, 500, 1000])
+        id_map = np.arange(1032, dtype=np.int32)[::-1].copy()                       # column c is vocabulary id 1031 - c
+        ids, _ = b.truncated_head_topk(to_dev_bf16(x.h), to_dev_bf16(W), torch.from_numpy(id_map).cuda(), 4)
+        torch.cuda.synchronize()
+        ora = oracle_mod.truncated_head_topk(x.h, W, id_map, 4)
+        assert ids.cpu().numpy()[0, :3].tolist() == [1026, 531, 31] == ora.ids[0, :3].tolist()
