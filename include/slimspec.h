@@ -79,6 +79,7 @@ typedef enum slimspec_status {
 
 #define SLIMSPEC_KMAX 64
 #define SLIMSPEC_VERSION 1
+#define SLIMSPEC_MAX_POSITIONS 16
 #define SLIMSPEC_STATIC_SCRATCH_BYTES (32u << 20)   /* device scratch built into the library, per GPU */
 
 /* Library version (SLIMSPEC_VERSION it was built with).  Host only, no HIP call. */
@@ -120,6 +121,20 @@ int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
                    int32_t *out_ids, float *out_logprobs,
                    void *workspace, size_t workspace_bytes,
                    void *stream);
+
+/* Low-rank head with one down-projection per drafted position and a shared up-projection
+ * (the direction section 7 names as future work: "position-specific down-projections while
+ * sharing a single up-projection"):  t_i = h_i A^(p(i)),  z_i = t_i B.  A_stack: device, bf16,
+ * [n_pos, d, r] row-major.  The rows are ordered by position: rows [pos_offsets[p],
+ * pos_offsets[p + 1]) use matrix p.  pos_offsets: HOST array of n_pos + 1 int32, read during
+ * the call only; pos_offsets[0] = 0, pos_offsets[n_pos] = rows, non-decreasing (a position may
+ * have no rows); 1 <= n_pos <= SLIMSPEC_MAX_POSITIONS.  Everything else, the workspace size
+ * included, as slimspec_head_topk; with n_pos = 1 it is slimspec_head_topk. */
+int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,
+                                 const void *B, const slimspec_shape *shape, int32_t k,
+                                 int32_t *out_ids, float *out_logprobs,
+                                 void *workspace, size_t workspace_bytes,
+                                 void *stream);
 
 /* Truncated-vocabulary head (section 2, "Static vocabulary truncation": the drafter's head
  * restricted to a kept subset V_tr of the vocabulary, plus a token-index map; the baseline

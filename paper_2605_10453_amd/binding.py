@@ -29,7 +29,7 @@ STATUS_SCRATCH_LIMIT = -5
 STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = (
-    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk",
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions",
     "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.slimspec_head_topk_static.argtypes = [vp, vp, vp, shp, i32, vp, vp, vp]
     lib.full_head_topk.restype = ctypes.c_int
     lib.full_head_topk.argtypes = [vp, vp, ctypes.c_int, shp, i32, vp, vp, vp, sz, vp]
+    lib.slimspec_head_topk_positions.restype = ctypes.c_int
+    lib.slimspec_head_topk_positions.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int32), vp, shp, i32, vp, vp, vp, sz, vp]
     lib.truncated_head_topk.restype = ctypes.c_int
     lib.truncated_head_topk.argtypes = [vp, vp, ctypes.c_int, vp, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_status_string.restype = ctypes.c_char_p
@@ -261,6 +263,38 @@ def truncated_head_topk(h: torch.Tensor, W_tr: torch.Tensor, id_map: torch.Tenso
                                  ctypes.byref(shape), k, _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
                                  _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                  _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs
+
+
+def slimspec_head_topk_positions(h: torch.Tensor, A_stack: torch.Tensor, pos_offsets, B: torch.Tensor, k: int,
+                                 out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                                 workspace: Optional[torch.Tensor] = None,
+                                 stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Low-rank head with one down-projection per drafted position: A_stack [n_pos, d, r]; rows
+    [pos_offsets[p], pos_offsets[p + 1]) use matrix p (pos_offsets: a host sequence of n_pos + 1 ints)."""
+    rows, d = h.shape
+    n_pos, d2, r = A_stack.shape
+    r2, V = B.shape
+    if d != d2 or r != r2:
+        raise ValueError("shape mismatch between h, A_stack and B")
+    off = [int(v) for v in pos_offsets]
+    if len(off) != n_pos + 1:
+        raise ValueError("pos_offsets must have n_pos + 1 entries")
+    for t, n in ((h, "h"), (A_stack, "A_stack"), (B, "B")):
+        if t.element_size() != 2:
+            raise ValueError(f"{n} must hold bf16 (2-byte) elements")
+    out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, r, V)
+    need = int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k))
+    workspace = _workspace(need, h.device, workspace)
+    off_arr = (ctypes.c_int32 * (n_pos + 1))(*off)
+    st = lib.slimspec_head_topk_positions(_dev_ptr(h, "h"), _dev_ptr(A_stack, "A_stack"), n_pos, off_arr, _dev_ptr(B, "B"),
+                                          ctypes.byref(shape), k, _dev_ptr(out_ids, "out_ids"),
+                                          _dev_ptr(out_logprobs, "out_logprobs"), _dev_ptr(workspace, "workspace"),
+                                          workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs

@@ -129,7 +129,7 @@ __device__ __forceinline__ void column_scale_block(const uint16_t *__restrict__ 
 // only its slices' rows of A and columns of h.
 __global__ __launch_bounds__(256) void down_tile_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ part,
-    int rows, int d, int r, DownGrid g)
+    int d, int r, DownGrid g)
 {
     extern __shared__ __align__(1024) unsigned char lds_raw[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) unsigned char *)lds_raw);
@@ -146,7 +146,11 @@ __global__ __launch_bounds__(256) void down_tile_kernel(
     }
     if (tile >= g.n_rt * g.n_ct) return;
     const int rt = tile % g.n_rt, ct = tile / g.n_rt;
-    const int row0 = rt * kDT, n0 = ct * kDT;
+    int grp = 0;                                               // the group of rows (one down-projection matrix) this row tile belongs to
+    while (grp + 1 < g.n_groups && rt >= g.g_tile0[grp + 1]) ++grp;
+    const int row0 = g.g_row0[grp] + (rt - g.g_tile0[grp]) * kDT, n0 = ct * kDT;
+    const int rows = g.g_row0[grp + 1];                        // rows beyond the group's last are not this tile's
+    A += (size_t)g.g_mat[grp] * d * r;
     const int half = lane >> 5, l32 = lane & 31, g1 = (lane >> 4) & 1, j16 = lane & 15;
 
     f32x16 acc0, acc1;
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(256) void down_tile_kernel(
     const int n_full = d / kDKB;
     const int per = (n_full + g.slices - 1) / g.slices;
     const int s_beg = min(n_full, slice * per), s_end = min(n_full, s_beg + per);
-    const int nst = (row0 < rows && n0 < r) ? s_end - s_beg : 0;          // a padding tile loads nothing
+    const int nst = (n0 < r) ? s_end - s_beg : 0;                         // columns of padding load nothing
     if (nst > 0) {
         // The two loads of this wavefront per stage:
         //   A: stage rows 8 wave + lane / 8, 16-byte piece lane % 8 of the tile's 128 bytes; the piece is stored at
@@ -224,7 +228,7 @@ __global__ __launch_bounds__(256) void down_tile_kernel(
 //   stat  [2 ceil(r / 64), rows_pad]   per 32-column piece: (sum of (t - its 16-bit value)^2, sum of t^2) of its entries
 __global__ __launch_bounds__(256) void down_finish_kernel(
     const float *__restrict__ part, const uint16_t *__restrict__ h, const uint16_t *__restrict__ A,
-    int rows, int rows_pad, int d, int r,
+    int rows_pad, int d, int r,
     float *__restrict__ t32, uint4 *__restrict__ t16, float2 *__restrict__ stat,
     const uint16_t *__restrict__ B, int V, float2 *__restrict__ tilescale, int as_f16, DownGrid g)
 {
@@ -232,14 +236,19 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
     __shared__ float red_a[4 * 32], red_b[4 * 32];
     __shared__ float colsh[3 * 64 * 8];
     const int tid = threadIdx.x;
-    if ((int)blockIdx.x >= 4 * g.n_rt_pad * g.n_ct) {
+    if ((int)blockIdx.x >= 4 * g.n_rt_all * g.n_ct) {
         // (next to the tile kernel's blocks instead, these blocks cost 6.7 us at 512 rows; here 2-3)
-        column_scale_block(B, r, V, tilescale, (int)blockIdx.x - 4 * g.n_rt_pad * g.n_ct, colsh, tid);
+        column_scale_block(B, r, V, tilescale, (int)blockIdx.x - 4 * g.n_rt_all * g.n_ct, colsh, tid);
         return;
     }
     const int piece = blockIdx.x;                              // ((rt * n_ct + ct) * 4 + wave of the tile kernel)
-    const int w = piece & 3, ct = (piece >> 2) % g.n_ct, rt = (piece >> 2) / g.n_ct;      // rt < n_rt_pad; no partial sums exist for rt >= n_rt
-    const int row0 = rt * kDT + 32 * (w >> 1), n0 = ct * kDT + 32 * (w & 1);
+    const int w = piece & 3, ct = (piece >> 2) % g.n_ct, rt = (piece >> 2) / g.n_ct;      // rt < n_rt_all; no partial sums exist for rt >= n_rt
+    int grp = 0;                                               // group n_groups: the rows of padding, zero-filled
+    while (grp < g.n_groups && rt >= g.g_tile0[grp + 1]) ++grp;
+    const int row0 = g.g_row0[grp] + (rt - g.g_tile0[grp]) * kDT + 32 * (w >> 1), n0 = ct * kDT + 32 * (w & 1);
+    const int row_end = g.g_row0[grp + 1];                     // this piece's rows end with its group
+    const int rows = (grp < g.n_groups) ? row_end : 0;         // rows that carry values
+    A += (size_t)g.g_mat[grp < g.n_groups ? grp : 0] * d * r;
 
     // the slices, in order: several loads of a thread are in flight together (they come from other CUs' writes)
     const size_t slice_stride = (size_t)g.n_rt * g.n_ct * 4 * (16 * 64);
@@ -248,7 +257,7 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
     // a thread owns four (i, lane) pairs of the accumulator layout; the loads of SB slices of all four are in flight together
     constexpr int SB = 8;
     float v4[4] = {0.f, 0.f, 0.f, 0.f};
-    const int n_slices = rt < g.n_rt ? g.slices : 0;
+    const int n_slices = grp < g.n_groups ? g.slices : 0;
     for (int s0 = 0; s0 < n_slices; s0 += SB) {
         float x[SB][4];
 #pragma unroll
@@ -281,14 +290,15 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
 
     // thread (row, group of 8 columns)
     if (tid < 128) {
-        const int row = tid & 31, grp = tid >> 5;
-        const int kg = (n0 >> 3) + grp;
+        const int row = tid & 31, cg = tid >> 5;
+        const int kg = (n0 >> 3) + cg;
         const bool valid = row0 + row < rows && kg < (r >> 3);
+        const bool mine = row0 + row < row_end;                 // rows beyond belong to the next group's tiles
         float v[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = valid ? tile[row * 33 + grp * 8 + e] : 0.f;
+        for (int e = 0; e < 8; ++e) v[e] = valid ? tile[row * 33 + cg * 8 + e] : 0.f;
         float a = 0.f, b = 0.f;
-        if (kg < (r >> 3)) {
+        if (mine && kg < (r >> 3)) {
             float4 *o = reinterpret_cast<float4 *>(t32 + (size_t)(row0 + row) * r + kg * 8);
             o[0] = make_float4(v[0], v[1], v[2], v[3]);
             o[1] = make_float4(v[4], v[5], v[6], v[7]);
@@ -317,19 +327,19 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
             }
             packed = __builtin_bit_cast(uint4, hv);
         }
-        t16[(size_t)kg * rows_pad + row0 + row] = packed;     // kg < 8 ceil(r / 64): the tile grid covers exactly that
-        red_a[grp * 32 + row] = a;
-        red_b[grp * 32 + row] = b;
+        if (mine) t16[(size_t)kg * rows_pad + row0 + row] = packed;     // kg < 8 ceil(r / 64): the tile grid covers exactly that
+        red_a[cg * 32 + row] = a;
+        red_b[cg * 32 + row] = b;
     }
     __syncthreads();
-    if (tid < 32)
+    if (tid < 32 && row0 + tid < row_end)
         stat[(size_t)(n0 >> 5) * rows_pad + row0 + tid] =
             make_float2(((red_a[tid] + red_a[32 + tid]) + red_a[64 + tid]) + red_a[96 + tid],
                         ((red_b[tid] + red_b[32 + tid]) + red_b[64 + tid]) + red_b[96 + tid]);
 }
 
 hipError_t launch_down_projection_tiles(const uint16_t *h, const uint16_t *A, float *part, const DownGrid &g,
-                                        int rows, int rows_pad, int d, int r,
+                                        int rows_pad, int d, int r,
                                         float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float2 *tilescale,
                                         bool as_f16, hipStream_t st)
 {
@@ -339,10 +349,10 @@ hipError_t launch_down_projection_tiles(const uint16_t *h, const uint16_t *A, fl
     const int tiles = g.n_rt * g.n_ct;
     // slices >= 8: every XCD has slices / 8 slices of every tile; fewer: 8 / slices XCDs share a slice and split the tiles
     const int blocks = g.slices >= 8 ? tiles * g.slices : 8 * ((tiles + 8 / g.slices - 1) / (8 / g.slices));
-    down_tile_kernel<<<blocks, 256, kDLds, st>>>(h, A, part, rows, d, r, g);
+    down_tile_kernel<<<blocks, 256, kDLds, st>>>(h, A, part, d, r, g);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    down_finish_kernel<<<4 * g.n_rt_pad * g.n_ct + (V + 511) / 512, 256, 0, st>>>(
-        part, h, A, rows, rows_pad, d, r, t32, static_cast<uint4 *>(t16), stat, B, V, tilescale, as_f16 ? 1 : 0, g);
+    down_finish_kernel<<<4 * g.n_rt_all * g.n_ct + (V + 511) / 512, 256, 0, st>>>(
+        part, h, A, rows_pad, d, r, t32, static_cast<uint4 *>(t16), stat, B, V, tilescale, as_f16 ? 1 : 0, g);
     return hipGetLastError();
 }
 

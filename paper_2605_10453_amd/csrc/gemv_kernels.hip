@@ -17,13 +17,13 @@ namespace slimspec {
 // full 128-byte lines); tpart is [nds][R][r] and the consumer adds the nds slices in order.
 constexpr int kDownThreads = 1024;
 
-template <int R>
+template <int R, bool POS>
 __global__ __launch_bounds__(kDownThreads) void down_items_kernel(
     const uint16_t *__restrict__ h, const uint16_t *__restrict__ A, float *__restrict__ tpart,
-    int rows_here, int d, int r, int n_cb, int slice)
+    int rows_here, int d, int r, int n_cb, int slice, RowMats mats)
 {
     __shared__ float redd[kDownThreads / 64][R][kItemCols];
-    down_item<R, kDownThreads>(redd, h, A, tpart, blockIdx.x, n_cb, slice, rows_here, d, r, threadIdx.x);
+    down_item<R, kDownThreads, POS>(redd, h, A, tpart, blockIdx.x, n_cb, slice, rows_here, d, r, threadIdx.x, mats);
 }
 
 __global__ __launch_bounds__(256) void widen_rows_kernel(
@@ -187,19 +187,29 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
 
 template <int R>
 static hipError_t launch_down(const uint16_t *h, const uint16_t *A, float *tpart,
-                              int rows_here, int d, int r, const DownPlan &fp, hipStream_t st)
+                              int rows_here, int d, int r, const DownPlan &fp, const int *mat_of_row, hipStream_t st)
 {
-    down_items_kernel<R><<<fp.n_items, kDownThreads, 0, st>>>(h, A, tpart, rows_here, d, r, fp.n_cb, fp.slice);
+    RowMats mats{};
+    bool one_matrix = true;
+    for (int i = 0; i < rows_here && i < 8; ++i) {
+        mats.m[i] = mat_of_row ? mat_of_row[i] : 0;
+        one_matrix = one_matrix && mats.m[i] == mats.m[0];
+    }
+    if (one_matrix)        // every row uses the same matrix: the weights are loaded once for all rows
+        down_items_kernel<R, false><<<fp.n_items, kDownThreads, 0, st>>>(h, A + (size_t)mats.m[0] * d * r, tpart, rows_here, d, r,
+                                                                         fp.n_cb, fp.slice, mats);
+    else
+        down_items_kernel<R, true><<<fp.n_items, kDownThreads, 0, st>>>(h, A, tpart, rows_here, d, r, fp.n_cb, fp.slice, mats);
     return hipGetLastError();
 }
 
 hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *tpart,
-                                  int rows_here, int d, int r, const DownPlan &fp, hipStream_t st)
+                                  int rows_here, int d, int r, const DownPlan &fp, const int *mat_of_row, hipStream_t st)
 {
-    if (rows_here <= 1) return launch_down<1>(h, A, tpart, rows_here, d, r, fp, st);
-    if (rows_here <= 2) return launch_down<2>(h, A, tpart, rows_here, d, r, fp, st);
-    if (rows_here <= 4) return launch_down<4>(h, A, tpart, rows_here, d, r, fp, st);
-    return launch_down<8>(h, A, tpart, rows_here, d, r, fp, st);
+    if (rows_here <= 1) return launch_down<1>(h, A, tpart, rows_here, d, r, fp, mat_of_row, st);
+    if (rows_here <= 2) return launch_down<2>(h, A, tpart, rows_here, d, r, fp, mat_of_row, st);
+    if (rows_here <= 4) return launch_down<4>(h, A, tpart, rows_here, d, r, fp, mat_of_row, st);
+    return launch_down<8>(h, A, tpart, rows_here, d, r, fp, mat_of_row, st);
 }
 
 hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)

@@ -27,12 +27,17 @@ __device__ __forceinline__ void widen8(const Raw8F32 &q, float (&f)[8]) {
 // Down-projection t = h A shared out in items of (64 columns of A) x (a slice of d).
 constexpr int kItemCols = 64;           // columns of A per item: one 128-byte line per row of A
 
+// Which matrix of a stack of down-projection matrices each of up to 8 rows uses (one matrix per drafted position).
+struct RowMats { int m[8]; };
+
 // One down-projection item: columns [64 cb, 64 cb + 64) x rows [ds * slice, ds * slice + slice) of A.
 // Thread = (row slot tid / 8, 16-byte piece tid % 8).  tpart is [nds][R][r].
-template <int R, int NT>
+// POS: A is a stack of [d, r] matrices and row i uses matrix mats.m[i] (every row then loads its own weights).
+template <int R, int NT, bool POS>
 __device__ __forceinline__ void down_item(float (*redd)[R][kItemCols], const uint16_t *__restrict__ h,
                                           const uint16_t *__restrict__ A, float *__restrict__ tpart,
-                                          int item, int n_cb, int slice, int rows_here, int d, int r, int tid)
+                                          int item, int n_cb, int slice, int rows_here, int d, int r, int tid,
+                                          const RowMats &mats)
 {
     constexpr int NW = NT / 64;
     const int cb = item % n_cb, ds = item / n_cb;
@@ -46,14 +51,29 @@ __device__ __forceinline__ void down_item(float (*redd)[R][kItemCols], const uin
         for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
     if (col < r) {
         for (int c = c_beg + slot; c < c_end; c += NT / 8) {
-            const uint4 w = *reinterpret_cast<const uint4 *>(A + (size_t)c * r + col);
-            const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
-                                bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
+            if constexpr (!POS) {
+                const uint4 w = *reinterpret_cast<const uint4 *>(A + (size_t)c * r + col);
+                const float f[8] = {bf16_lo(w.x), bf16_hi(w.x), bf16_lo(w.y), bf16_hi(w.y),
+                                    bf16_lo(w.z), bf16_hi(w.z), bf16_lo(w.w), bf16_hi(w.w)};
 #pragma unroll
-            for (int i = 0; i < R; ++i) {
-                const float hv = (i < rows_here) ? bf16_to_float(h[(size_t)i * d + c]) : 0.f;
+                for (int i = 0; i < R; ++i) {
+                    const float hv = (i < rows_here) ? bf16_to_float(h[(size_t)i * d + c]) : 0.f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(hv, f[e], acc[i][e]);
+                    for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(hv, f[e], acc[i][e]);
+                }
+            } else {
+                uint4 w[R];
+#pragma unroll
+                for (int i = 0; i < R; ++i)
+                    w[i] = *reinterpret_cast<const uint4 *>(A + (size_t)mats.m[i & 7] * d * r + (size_t)c * r + col);
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    const float f[8] = {bf16_lo(w[i].x), bf16_hi(w[i].x), bf16_lo(w[i].y), bf16_hi(w[i].y),
+                                        bf16_lo(w[i].z), bf16_hi(w[i].z), bf16_lo(w[i].w), bf16_hi(w[i].w)};
+                    const float hv = (i < rows_here) ? bf16_to_float(h[(size_t)i * d + c]) : 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(hv, f[e], acc[i][e]);
+                }
             }
         }
     }

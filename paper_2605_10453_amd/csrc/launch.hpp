@@ -26,8 +26,9 @@ struct LdsLimit {
 };
 
 // slices of t = h A (fp32, [nds][R][r] with R = 1, 2, 4 or 8 >= rows_here) for up to kGemvMaxRows rows
+// A: a stack of [d, r] matrices; mat_of_row (host, rows_here entries, or null: matrix 0) names each row's
 hipError_t launch_down_projection(const uint16_t *h, const uint16_t *A, float *tpart,
-                                  int rows_here, int d, int r, const DownPlan &dp, hipStream_t st);
+                                  int rows_here, int d, int r, const DownPlan &dp, const int *mat_of_row, hipStream_t st);
 
 // x = float(h) for the full head.
 hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st);
@@ -53,8 +54,9 @@ constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial
 // layout of head_tile_kernel (zero beyond r and beyond the last row), per-row rounding statistics per 32 columns,
 // and per 256-column vocabulary tile (the largest column rms, the mean square) of B over a sample of its rows
 // (tilescale [ceil(V / 256)])
+// (A: the stack of down-projection matrices, [d, r] each; the grid names the rows and the matrix of every group)
 hipError_t launch_down_projection_tiles(const uint16_t *h, const uint16_t *A, float *part, const DownGrid &g,
-                                        int rows, int rows_pad, int d, int r,
+                                        int rows_pad, int d, int r,
                                         float *t32, void *t16, float2 *stat, const uint16_t *B, int V, float2 *tilescale,
                                         bool as_f16, hipStream_t st);
 

@@ -115,25 +115,53 @@ size_t merge_defer_bytes(int rows);
 constexpr int kDeferMinK = 2048, kDeferMinKFine = 1024;
 inline bool merge_parks_rows(int K, bool fine_operand) { return K >= kDeferMinK || (fine_operand && K >= kDeferMinKFine); }
 
-// Many-row down-projection: n_rt x n_ct tiles of 64 x 64 of t (row tiles that hold rows; n_rt_pad with the padding
-// up to rows_pad), the contraction in `slices` slices (a power of two): enough blocks for every CU, at least two
-// stages of 32 contraction elements per block.
-struct DownGrid { int n_rt = 0, n_ct = 0, slices = 1, n_rt_pad = 0; };
-inline DownGrid make_down_grid(int rows, int rows_pad, int d, int r) {
+// Many-row down-projection: tiles of 64 x 64 of t, the contraction in `slices` slices (a power of two): enough
+// blocks for every CU, at least two stages of 32 contraction elements per block.  The rows come in groups that share
+// a down-projection matrix (one group unless the call names one matrix per drafted position); a row tile never
+// crosses a group, and the rows of padding [rows, rows_pad) form one more group that is only zero-filled.
+constexpr int kMaxPositions = 16;
+struct DownGrid {
+    int n_rt = 0;                        // row tiles that hold rows, over all groups
+    int n_rt_all = 0;                    // ... with the tiles of the padding group
+    int n_ct = 0, slices = 1;
+    int n_groups = 0;                    // groups with rows; group n_groups is the padding
+    int g_row0[kMaxPositions + 2] = {};  // first row of group g; g_row0[n_groups] = rows, g_row0[n_groups + 1] = rows_pad
+    int g_tile0[kMaxPositions + 2] = {}; // first row tile of group g; g_tile0[n_groups + 1] = n_rt_all
+    int g_mat[kMaxPositions + 1] = {};   // which matrix of the stack the group uses
+};
+// group g covers rows [g_first[g], g_first[g + 1]) of the launch (g_first[n_groups] = rows), all groups non-empty
+inline DownGrid make_down_grid(int rows, int rows_pad, int d, int r, int n_groups = 1, const int *g_first = nullptr,
+                               const int *g_mat = nullptr) {
     DownGrid g;
-    g.n_rt = (rows + 63) / 64;
-    g.n_rt_pad = rows_pad / 64;
+    g.n_groups = n_groups;
+    int tile = 0;
+    for (int q = 0; q < n_groups; ++q) {
+        const int lo = g_first ? g_first[q] : 0, hi = g_first ? g_first[q + 1] : rows;
+        g.g_row0[q] = lo; g.g_tile0[q] = tile; g.g_mat[q] = g_mat ? g_mat[q] : 0;
+        tile += (hi - lo + 63) / 64;
+    }
+    g.n_rt = tile;
+    g.g_row0[n_groups] = rows; g.g_tile0[n_groups] = tile;
+    tile += (rows_pad - rows + 63) / 64;
+    g.g_row0[n_groups + 1] = rows_pad; g.g_tile0[n_groups + 1] = tile;
+    g.n_rt_all = tile;
     g.n_ct = (r + 63) / 64;
     const int tiles = g.n_rt * g.n_ct, n_full = d / 32;
     // (two blocks per CU, i.e. twice the slices, measured slower: 10.7 + 4.6 against 8.9 + 4.5 us at 512 rows)
     while (g.slices < 64 && tiles * g.slices < 256 && n_full / (2 * g.slices) >= 2) g.slices *= 2;
     return g;
 }
+// Partial tiles of t, in 64 x 64 tiles of floats, for any grouping of `rows` rows into at most kMaxPositions groups:
+// slices * tiles stays below 512 while the contraction is split, and is the tile count itself when it is not.
+inline size_t down_part_tiles_bound(int rows, int r) {
+    const size_t tiles = ((size_t)(rows + 63) / 64 + kMaxPositions - 1) * (size_t)((r + 63) / 64);
+    return tiles > 512 ? tiles : 512;
+}
 
 struct MfmaPlan {
     int rows = 0, rows_pad = 0, rt = 0, n_rb = 0, gw = 0, nsr = 0, n_vt = 0;
     DownGrid down;
-    size_t off_down_part = 0;            // fp32 [slices][n_rt][n_ct][4][16][64]: partial tiles of t
+    size_t off_down_part = 0;            // fp32 [slices][n_rt][n_ct][4][16][64]: partial tiles of t (sized for any grouping of the rows)
     size_t off_t32 = 0;                  // fp32 [rows_pad, r]
     size_t off_t16 = 0;                  // 16-byte vectors [8 ceil(K / 64), rows_pad]: the head kernel's row operand
     size_t off_stat = 0;                 // float2 [2 ceil(r / 64), rows_pad]
@@ -164,7 +192,7 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
         p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((r + 63) / 64 * 64));
         p.off_stat = off;      off = align_up(off + 2 * sizeof(float) * (size_t)p.rows_pad * 2 * ((r + 63) / 64));
         p.down = make_down_grid(rows, p.rows_pad, d, r);
-        p.off_down_part = off; off = align_up(off + sizeof(float) * 4096 * (size_t)p.down.slices * p.down.n_rt * p.down.n_ct);
+        p.off_down_part = off; off = align_up(off + sizeof(float) * 4096 * down_part_tiles_bound(rows, r));
         p.off_tilescale = off; off = align_up(off + 2 * sizeof(float) * (size_t)p.n_vt);
     } else {
         p.off_t16 = off;       off = align_up(off + 2 * (size_t)p.rows_pad * ((d + 63) / 64 * 64));      // h regrouped for the kernel

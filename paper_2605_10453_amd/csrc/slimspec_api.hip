@@ -87,9 +87,19 @@ int static_scratch_address(void **out)
     return SLIMSPEC_OK;
 }
 
+// One down-projection matrix per drafted position: rows [off[p], off[p + 1]) use matrix p of the stack (host array).
+struct Positions { int n = 0; const int32_t *off = nullptr; };
+
+int position_of_row(const Positions &pos, int row)
+{
+    int p = 0;
+    while (p + 1 < pos.n && row >= pos.off[p + 1]) ++p;
+    return p;
+}
+
 int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
                   const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
-                  void *workspace, size_t workspace_bytes, void *stream)
+                  const Positions &pos, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (workspace_bytes < mfma_workspace_bytes(kind, shape)) return SLIMSPEC_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -101,7 +111,18 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
     for (int row0 = 0; row0 < shape->rows; row0 += per) {
         const int rows = (shape->rows - row0 < per) ? shape->rows - row0 : per;
         // a last, smaller batch may fall below the matrix-core threshold; it still runs here
-        const MfmaPlan p = make_mfma_plan(kind, rows, d, r, V);
+        MfmaPlan p = make_mfma_plan(kind, rows, d, r, V);
+        if (kind == HeadKind::LowRank && pos.n > 0) {
+            // this launch's rows in groups by position (empty groups dropped); the workspace is sized for any grouping
+            int g_first[kMaxPositions + 1], g_mat[kMaxPositions], n_groups = 0;
+            for (int q = 0; q < pos.n; ++q) {
+                const int lo = pos.off[q] > row0 ? pos.off[q] : row0;
+                const int hi = pos.off[q + 1] < row0 + rows ? pos.off[q + 1] : row0 + rows;
+                if (hi > lo) { g_first[n_groups] = lo - row0; g_mat[n_groups] = q; ++n_groups; }
+            }
+            g_first[n_groups] = rows;
+            p.down = make_down_grid(rows, p.rows_pad, d, r, n_groups, g_first, g_mat);
+        }
         float *streams = reinterpret_cast<float *>(ws + p.off_streams);
         const uint16_t *hrow = hb + (size_t)row0 * d;
         hipError_t e;
@@ -113,7 +134,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             float2 *tilescale = reinterpret_cast<float2 *>(ws + p.off_tilescale);
             const bool tile_f16 = head_tile_f16(k);
             e = launch_down_projection_tiles(hrow, static_cast<const uint16_t *>(A), reinterpret_cast<float *>(ws + p.off_down_part), p.down,
-                                             rows, p.rows_pad, d, r, t32, t16, stat, Mb, V, tilescale, tile_f16, s);
+                                             p.rows_pad, d, r, t32, t16, stat, Mb, V, tilescale, tile_f16, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
             e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
@@ -145,7 +166,8 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
 
 int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_is_f32,
              const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
-             void *workspace, size_t workspace_bytes, void *stream, const int32_t *id_map = nullptr)
+             void *workspace, size_t workspace_bytes, void *stream, const int32_t *id_map = nullptr,
+             const Positions &pos = Positions())
 {
     int st = check_shape(kind, shape, k);
     if (st != SLIMSPEC_OK) return st;
@@ -157,7 +179,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         return SLIMSPEC_UNSUPPORTED;
     const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK;
     if (use_mfma)
-        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, id_map, workspace, workspace_bytes, stream);
+        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, id_map, pos, workspace, workspace_bytes, stream);
     const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
     if (workspace_bytes < p.bytes) return SLIMSPEC_WORKSPACE_TOO_SMALL;
 
@@ -176,9 +198,12 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     for (int row0 = 0; row0 < p.rows; row0 += kGemvMaxRows) {
         const int rows_here = (p.rows - row0 < kGemvMaxRows) ? p.rows - row0 : kGemvMaxRows;
         hipError_t e;
-        if (kind == HeadKind::LowRank)
+        if (kind == HeadKind::LowRank) {
+            int mat_of_row[kGemvMaxRows];
+            for (int i = 0; i < rows_here; ++i) mat_of_row[i] = pos.n > 0 ? position_of_row(pos, row0 + i) : 0;
             e = launch_down_projection(hb + (size_t)row0 * p.d, static_cast<const uint16_t *>(A),
-                                       tpart, rows_here, p.d, p.r, dp, s);
+                                       tpart, rows_here, p.d, p.r, dp, mat_of_row, s);
+        }
         else
             e = launch_widen_rows(hb + (size_t)row0 * p.d, x, rows_here * p.d, s);
         if (e != hipSuccess) return fail_hip(e);
@@ -268,6 +293,25 @@ int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
     if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
     return run_head(HeadKind::Full, h, nullptr, W, w_dtype == SLIMSPEC_F32, shape, k, out_ids, out_logprobs,
                     workspace, workspace_bytes, stream);
+}
+
+int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,
+                                 const void *B, const slimspec_shape *shape, int32_t k,
+                                 int32_t *out_ids, float *out_logprobs,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!shape || !pos_offsets) return SLIMSPEC_INVALID_ARGUMENT;
+    if (n_pos < 1) return SLIMSPEC_INVALID_ARGUMENT;
+    if (n_pos > SLIMSPEC_MAX_POSITIONS) return SLIMSPEC_UNSUPPORTED;
+    if (pos_offsets[0] != 0 || pos_offsets[n_pos] != shape->rows) return SLIMSPEC_INVALID_ARGUMENT;
+    for (int p = 0; p < n_pos; ++p)
+        if (pos_offsets[p + 1] < pos_offsets[p]) return SLIMSPEC_INVALID_ARGUMENT;
+    // the stack is addressed as one array of n_pos * d * r elements with the kernels' 32-bit element offsets
+    if (shape->d > 0 && shape->r > 0 && (int64_t)n_pos * shape->d * shape->r >= (int64_t)1 << 31) return SLIMSPEC_UNSUPPORTED;
+    Positions pos;
+    pos.n = n_pos; pos.off = pos_offsets;
+    return run_head(HeadKind::LowRank, h, A_stack, B, false, shape, k, out_ids, out_logprobs,
+                    workspace, workspace_bytes, stream, nullptr, pos);
 }
 
 int truncated_head_topk(const void *h, const void *W_tr, slimspec_dtype w_dtype, const int32_t *id_map,

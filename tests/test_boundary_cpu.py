@@ -166,3 +166,22 @@ def test_truncated_head_argument_validation(lib):
     assert call(good, 0) == b.STATUS_INVALID_ARGUMENT
     assert call(good, 10, wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
     assert call(b.SlimspecShape(1, 4096, 0, 65537), 10) == b.STATUS_UNSUPPORTED
+
+
+def test_positions_argument_validation(lib):
+    l, b = lib
+    fake = ctypes.c_void_p(0x1000)
+    good = b.SlimspecShape(8, 4096, 512, 128256)
+
+    def call(n_pos, off, shape=good, k=10, wsb=1 << 40):
+        arr = (ctypes.c_int32 * len(off))(*off) if off is not None else None
+        return l.slimspec_head_topk_positions(fake, fake, n_pos, arr, fake, ctypes.byref(shape), k, fake, fake, fake, wsb, None)
+
+    assert call(2, None) == b.STATUS_INVALID_ARGUMENT
+    assert call(0, [0]) == b.STATUS_INVALID_ARGUMENT
+    assert call(17, list(range(18))) == b.STATUS_UNSUPPORTED
+    assert call(2, [1, 4, 8]) == b.STATUS_INVALID_ARGUMENT            # does not start at 0
+    assert call(2, [0, 4, 7]) == b.STATUS_INVALID_ARGUMENT            # does not end at rows
+    assert call(3, [0, 6, 4, 8]) == b.STATUS_INVALID_ARGUMENT         # decreasing
+    assert call(2, [0, 4, 8], k=0) == b.STATUS_INVALID_ARGUMENT
+    assert call(2, [0, 4, 8], wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL

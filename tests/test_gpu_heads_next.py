@@ -63,3 +63,43 @@ def test_truncated_head_tied_columns_break_by_column(gpu, oracle_mod):
         torch.cuda.synchronize()
         ora = oracle_mod.truncated_head_topk(x.h, W, id_map, 4)
         assert ids.cpu().numpy()[0, :3].tolist() == [1026, 531, 31] == ora.ids[0, :3].tolist()
+
+
+# ------------------------------------------------------------------ position-specific down-projections
+
+@pytest.mark.parametrize("sizes,d,r,V,k", [
+    ((1, 1, 1), 256, 32, 8200, 8),                  # streaming path, every row its own matrix
+    ((2, 0, 2), 128, 16, 5000, 5),                  # ... an empty position
+    ((4,), 128, 16, 5000, 5),                       # one position: the plain head
+    ((3, 1, 0, 5), 96, 24, 2056, 7),                # matrix-core path, groups smaller than a tile
+    ((70, 1, 0, 129), 128, 40, 3080, 10),           # groups that end inside a row tile
+    ((64, 64, 64), 256, 64, 4104, 16),              # groups that fill their tiles; f16 operands
+    ((300, 250, 50), 64, 32, 1032, 5),              # two launches: a group crosses the 512-row boundary
+    ((9, 11), 128, 32, 3080, 20),                   # k beyond the matrix-core path: streaming in row groups of 8
+])
+def test_position_specific_down_projections(gpu, oracle_mod, sizes, d, r, V, k):
+    torch, b = gpu
+    rows, n_pos = sum(sizes), len(sizes)
+    print(f"positions case sizes={sizes} d={d} r={r} V={V} k={k}", flush=True)
+    x = synth.make_inputs(synth.small_config(rows, d, r, V, k, peaked_every=5), seed=70 + rows)
+    rng = np.random.default_rng(rows)
+    stack = np.stack([x.A] + [synth.f32_to_bf16_bits((rng.standard_normal((d, r)) * d ** -0.5).astype(np.float32))
+                              for _ in range(n_pos - 1)])
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    ids, lp = b.slimspec_head_topk_positions(to_dev_bf16(x.h), to_dev_bf16(stack.reshape(n_pos * d, r)).view(n_pos, d, r),
+                                             off.tolist(), to_dev_bf16(x.B), k)
+    torch.cuda.synchronize()
+    ora = oracle_mod.slimspec_head_topk_positions(x.h, stack, off, x.B, k, return_logits=True)
+    z_at = lambda ri, ci: ora.z[ri, ci]
+    compare_with_oracle(ids.cpu().numpy(), lp.cpu().numpy(), ora.ids, ora.lse, z_at, V)
+
+
+def test_positions_with_one_matrix_equal_the_plain_head(gpu):
+    torch, b = gpu
+    for rows in (2, 40):
+        x = synth.make_inputs(synth.small_config(rows, 128, 32, 4104, 6), seed=5)
+        h, A, B = to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B)
+        a_ids, a_lp = b.slimspec_head_topk(h, A, B, 6)
+        p_ids, p_lp = b.slimspec_head_topk_positions(h, A.view(1, 128, 32), [0, rows], B, 6)
+        torch.cuda.synchronize()
+        assert torch.equal(a_ids, p_ids) and torch.equal(a_lp.view(torch.int32), p_lp.view(torch.int32))
