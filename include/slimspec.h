@@ -122,6 +122,35 @@ int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
                    void *workspace, size_t workspace_bytes,
                    void *stream);
 
+/* The heads with the outputs stochastic decoding needs (section 5.3 evaluates temperature 1;
+ * section 3.2 counts the softmax over the whole vocabulary, which sampling and acceptance need,
+ * among the per-step overheads): besides the top-k of slimspec_head_topk / full_head_topk,
+ *     out_lse             [rows] float   log sum_v exp(z_v) over the whole vocabulary, so that
+ *                                        log q(v) = z_v - lse can be formed for any token
+ *     out_sample_ids      [rows] int32   one draw per row from softmax(z) (temperature 1)
+ *     out_sample_logprobs [rows] float   its log-probability
+ * all DEVICE memory.  The draw is the Gumbel-max rule argmax_v (z_v + g_v) with standard Gumbel
+ * noise that is a pure function of (seed, row, id):
+ *     x = id * 0x9E3779B1 + row * 0x85EBCA77 + seed_lo (mod 2^32);  x = mix(x);
+ *     x = x + seed_hi * 0xC2B2AE3D;  x = mix(x);
+ *     mix(x): x ^= x >> 16; x *= 0x21F0AAAD; x ^= x >> 15; x *= 0x735A2D97; x ^= x >> 15;
+ *     n = x >> 9;  u = (2 n + 1) / 2^24;  E = -ln(1 - u);  g = -ln E
+ * (seed_lo, seed_hi: the halves of `seed`; row: the row's index in the call), so a call with the
+ * same seed draws the same tokens on any row count or launch shape; equal z_v + g_v: the
+ * smaller id.  Same workspace size as the top-k calls. */
+int slimspec_head_sample(const void *h, const void *A, const void *B,
+                         const slimspec_shape *shape, int32_t k, uint64_t seed,
+                         int32_t *out_ids, float *out_logprobs,
+                         float *out_lse, int32_t *out_sample_ids, float *out_sample_logprobs,
+                         void *workspace, size_t workspace_bytes,
+                         void *stream);
+int full_head_sample(const void *h, const void *W, slimspec_dtype w_dtype,
+                     const slimspec_shape *shape, int32_t k, uint64_t seed,
+                     int32_t *out_ids, float *out_logprobs,
+                     float *out_lse, int32_t *out_sample_ids, float *out_sample_logprobs,
+                     void *workspace, size_t workspace_bytes,
+                     void *stream);
+
 /* Low-rank head with one down-projection per drafted position and a shared up-projection
  * (the direction section 7 names as future work: "position-specific down-projections while
  * sharing a single up-projection"):  t_i = h_i A^(p(i)),  z_i = t_i B.  A_stack: device, bf16,

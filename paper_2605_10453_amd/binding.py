@@ -29,7 +29,7 @@ STATUS_SCRATCH_LIMIT = -5
 STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = (
-    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions",
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_sample", "full_head_sample",
     "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
@@ -71,6 +71,10 @@ def load_library() -> ctypes.CDLL:
     lib.full_head_topk.argtypes = [vp, vp, ctypes.c_int, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_head_topk_positions.restype = ctypes.c_int
     lib.slimspec_head_topk_positions.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int32), vp, shp, i32, vp, vp, vp, sz, vp]
+    lib.slimspec_head_sample.restype = ctypes.c_int
+    lib.slimspec_head_sample.argtypes = [vp, vp, vp, shp, i32, ctypes.c_uint64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.full_head_sample.restype = ctypes.c_int
+    lib.full_head_sample.argtypes = [vp, vp, ctypes.c_int, shp, i32, ctypes.c_uint64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.truncated_head_topk.restype = ctypes.c_int
     lib.truncated_head_topk.argtypes = [vp, vp, ctypes.c_int, vp, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_status_string.restype = ctypes.c_char_p
@@ -298,3 +302,54 @@ def slimspec_head_topk_positions(h: torch.Tensor, A_stack: torch.Tensor, pos_off
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs
+
+
+def _sample_outputs(rows, device):
+    return (torch.empty((rows,), dtype=torch.float32, device=device), torch.empty((rows,), dtype=torch.int32, device=device),
+            torch.empty((rows,), dtype=torch.float32, device=device))
+
+
+def slimspec_head_sample(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, k: int, seed: int,
+                         workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """Low-rank head with the outputs of stochastic decoding: (ids, logprobs, lse, sample_ids, sample_logprobs)."""
+    rows, d = h.shape
+    d2, r = A.shape
+    r2, V = B.shape
+    if d != d2 or r != r2:
+        raise ValueError("shape mismatch between h, A and B")
+    out_ids, out_logprobs = _outputs(rows, k, h.device, None, None)
+    lse, sid, slp = _sample_outputs(rows, h.device)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, r, V)
+    workspace = _workspace(int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k)), h.device, workspace)
+    st = lib.slimspec_head_sample(_dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"), ctypes.byref(shape), k, seed,
+                                  _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+                                  _dev_ptr(lse, "lse"), _dev_ptr(sid, "sample_ids"), _dev_ptr(slp, "sample_logprobs"),
+                                  _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                  _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs, lse, sid, slp
+
+
+def full_head_sample(h: torch.Tensor, W: torch.Tensor, k: int, seed: int,
+                     workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """Full head with the outputs of stochastic decoding: (ids, logprobs, lse, sample_ids, sample_logprobs)."""
+    rows, d = h.shape
+    d2, V = W.shape
+    if d != d2:
+        raise ValueError("shape mismatch between h and W")
+    w_dtype = SLIMSPEC_F32 if W.dtype == torch.float32 else SLIMSPEC_BF16
+    out_ids, out_logprobs = _outputs(rows, k, h.device, None, None)
+    lse, sid, slp = _sample_outputs(rows, h.device)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, 0, V)
+    workspace = _workspace(int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k)), h.device, workspace)
+    st = lib.full_head_sample(_dev_ptr(h, "h"), _dev_ptr(W, "W"), w_dtype, ctypes.byref(shape), k, seed,
+                              _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+                              _dev_ptr(lse, "lse"), _dev_ptr(sid, "sample_ids"), _dev_ptr(slp, "sample_logprobs"),
+                              _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                              _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs, lse, sid, slp

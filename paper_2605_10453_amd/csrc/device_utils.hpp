@@ -112,6 +112,36 @@ __device__ __forceinline__ uint64_t wave_max_key(uint64_t k) {
     return u64_max(u64_from(ha, la), u64_from(hb, lb));
 }
 
+// ---------------------------------------------------------------------------
+// Standard Gumbel noise as a pure function of (seed, row, vocabulary id), for one draw per row from softmax(z) by
+// the Gumbel-max rule argmax_v (z_v + g_v) (sampling at temperature 1, section 5.3):
+//     x = id * 0x9E3779B1 + row * 0x85EBCA77 + seed_lo;  x = mix(x);  x += seed_hi * 0xC2B2AE3D;  x = mix(x)
+//     mix(x): x ^= x >> 16; x *= 0x21F0AAAD; x ^= x >> 15; x *= 0x735A2D97; x ^= x >> 15
+//     n = x >> 9,  u = (2 n + 1) / 2^24,  E = -ln(1 - u) ~ Exp(1),  g = -ln E
+// The draws that decide a sample are the large ones, i.e. small E = small u: there E comes from the series of
+// -ln(1 - u) (the hardware logarithm of a number next to 1 would lose them); elsewhere 1 - u is exact in fp32.
+struct GumbelKey { uint32_t row_term, hi_term; };      // row * 0x85EBCA77 + seed_lo,  seed_hi * 0xC2B2AE3D
+__device__ __forceinline__ GumbelKey gumbel_key(uint32_t seed_lo, uint32_t seed_hi, uint32_t row) {
+    return {row * 0x85EBCA77u + seed_lo, seed_hi * 0xC2B2AE3Du};
+}
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x21F0AAADu; x ^= x >> 15; x *= 0x735A2D97u; x ^= x >> 15;
+    return x;
+}
+// g / ln 2 (the noise in base-2 units: add it to a logit times log2 e)
+__device__ __forceinline__ float gumbel_base2(const GumbelKey &key, uint32_t id) {
+    uint32_t x = id * 0x9E3779B1u + key.row_term;
+    x = mix32(x);
+    x += key.hi_term;
+    x = mix32(x);
+    const uint32_t m = 2u * (x >> 9) + 1u;                          // u = m / 2^24, m odd, < 2^24
+    const float u = (float)m * 5.9604644775390625e-8f;              // exact
+    const float series = u * (1.f + u * (0.5f + u * (0.33333334f + u * (0.25f + u * 0.2f))));
+    const float direct = -__builtin_amdgcn_logf((float)(16777216u - m) * 5.9604644775390625e-8f) * kLn2;   // 1 - u is exact
+    const float E = (m < (1u << 18)) ? series : direct;
+    return -__builtin_amdgcn_logf(E);
+}
+
 // Orders the shared-memory accesses of one wavefront: writes before it are visible to
 // the reads of the other lanes after it (the LDS serves a wavefront's requests in
 // order; this keeps the compiler from reordering across the point).

@@ -47,7 +47,8 @@ template <int R, int NW, typename WT, bool SLICES>
 __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     const float *__restrict__ x, int nds, const WT *__restrict__ M,
     float2 *__restrict__ part_ms, float *__restrict__ part_val, int *__restrict__ part_id,
-    int rows_here, int row0, int K, int V, int chunks, int lanes, int k)
+    int rows_here, int row0, int K, int V, int chunks, int lanes, int k,
+    float4 *__restrict__ part_smp, uint32_t seed_lo, uint32_t seed_hi)
 {
     extern __shared__ __align__(16) unsigned char dyn[];         // ChunkLds, then (SLICES) t as fp32 [R][K]
     ChunkLds<R, NW> &L = *reinterpret_cast<ChunkLds<R, NW> *>(dyn);
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(NW * 64) void stream_topk_kernel(
     __syncthreads();
     for (int i = wave; i < rows_here; i += NW)
         chunk_row_epilogue<R, NW>(L, i, wave, lane, active, col, k, (size_t)(row0 + i) * chunks + chunk,
-                                  part_ms, part_val, part_id);
+                                  part_ms, part_val, part_id, part_smp, gumbel_key(seed_lo, seed_hi, (uint32_t)(row0 + i)));
 }
 
 // ---------------------------------------------------------------------------
@@ -227,7 +228,8 @@ constexpr size_t stream_lds_bytes(bool slices, int K) {
 
 template <int R, int NW, typename WT>
 static hipError_t launch_stream(const float *x, int nds, const WT *M, float2 *ms, float *pv, int *pi,
-                                int rows_here, int row0, int K, int V, int chunks, int lanes, int k, hipStream_t st)
+                                int rows_here, int row0, int K, int V, int chunks, int lanes, int k,
+                                float4 *smp, uint32_t seed_lo, uint32_t seed_hi, hipStream_t st)
 {
     static_assert(sizeof(ChunkLds<R, NW>) % 16 == 0, "t follows the struct in shared memory");
     const size_t dyn = stream_lds_bytes<R, NW>(nds > 0, K);
@@ -239,17 +241,20 @@ static hipError_t launch_stream(const float *x, int nds, const WT *M, float2 *ms
         if (e != hipSuccess) return e;
     }
     if (nds > 0)
-        stream_topk_kernel<R, NW, WT, true><<<chunks, NW * 64, dyn, st>>>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
+        stream_topk_kernel<R, NW, WT, true><<<chunks, NW * 64, dyn, st>>>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k,
+                                                                          smp, seed_lo, seed_hi);
     else
-        stream_topk_kernel<R, NW, WT, false><<<chunks, NW * 64, dyn, st>>>(x, 0, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k);
+        stream_topk_kernel<R, NW, WT, false><<<chunks, NW * 64, dyn, st>>>(x, 0, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k,
+                                                                           smp, seed_lo, seed_hi);
     return hipGetLastError();
 }
 
 template <typename WT>
 static hipError_t launch_stream_rows(const float *x, int nds, const WT *M, float2 *ms, float *pv, int *pi,
-                                     int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st)
+                                     int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k,
+                                     float4 *smp, uint32_t seed_lo, uint32_t seed_hi, hipStream_t st)
 {
-#define SLIMSPEC_STREAM(R, NW) launch_stream<R, NW, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k, st)
+#define SLIMSPEC_STREAM(R, NW) launch_stream<R, NW, WT>(x, nds, M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, k, smp, seed_lo, seed_hi, st)
 #define SLIMSPEC_FITS(R, NW) (stream_lds_bytes<R, NW>(nds > 0, K) <= kStreamLdsLimit)
     // One row: the block size the chunk geometry asks for.  More rows: as many wavefronts as the shared memory of
     // the partial sums (NW * R * 2 KB) allows; they split the contraction, and every one of them keeps loads in flight.
@@ -263,11 +268,12 @@ static hipError_t launch_stream_rows(const float *x, int nds, const WT *M, float
 
 // nds > 0: x holds nds slices [nds][R][K] of the contraction input (R = 1, 2, 4 or 8 as chosen for rows_here)
 hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_f32, float2 *ms, float *pv, int *pi,
-                              int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st)
+                              int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k,
+                              float4 *smp, uint32_t seed_lo, uint32_t seed_hi, hipStream_t st)
 {
     if (m_is_f32)
-        return launch_stream_rows<float>(x, nds, (const float *)M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, nw1, k, st);
-    return launch_stream_rows<uint16_t>(x, nds, (const uint16_t *)M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, nw1, k, st);
+        return launch_stream_rows<float>(x, nds, (const float *)M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, nw1, k, smp, seed_lo, seed_hi, st);
+    return launch_stream_rows<uint16_t>(x, nds, (const uint16_t *)M, ms, pv, pi, rows_here, row0, K, V, chunks, lanes, nw1, k, smp, seed_lo, seed_hi, st);
 }
 
 }  // namespace slimspec

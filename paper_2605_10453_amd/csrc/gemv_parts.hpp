@@ -123,11 +123,14 @@ struct ChunkLds {
 // T is preceded by k lane maxima, so it cannot be in the top-k.  (2) The elements >= T (k or a few more; all of
 // them when values tie) are compacted into shared memory through ballots and lane prefix counts.  (3) They are
 // ranked among themselves by (logit desc, id asc) by counting.
+// part_smp (may be null): the chunk's best z_v + g_v with standard Gumbel noise g (Gumbel-max sampling), as
+// (z + g, id, z, -) of the winner; gk: the noise key of this row.
 template <int R, int NW>
 __device__ __forceinline__ void chunk_row_epilogue(ChunkLds<R, NW> &L, int i, int wave, int lane, bool active,
                                                    int col, int k, size_t slot,
                                                    float2 *__restrict__ part_ms, float *__restrict__ part_val,
-                                                   int *__restrict__ part_id)
+                                                   int *__restrict__ part_id,
+                                                   float4 *__restrict__ part_smp, const GumbelKey &gk)
 {
     float z[8];
 #pragma unroll
@@ -142,6 +145,21 @@ __device__ __forceinline__ void chunk_row_epilogue(ChunkLds<R, NW> &L, int i, in
 #pragma unroll
     for (int e = 0; e < 8; ++e) z[e] = active ? z[e] : kNegInf;
 
+    if (part_smp) {
+        // keys are unique (one per id), so exactly one lane holds the wavefront's largest
+        uint64_t best = kNoKey;
+        float zb = 0.f;
+        if (active) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint64_t key = make_key(z[e] + gumbel_base2(gk, (uint32_t)(col + e)) * kLn2, (uint32_t)(col + e));
+                if (key > best) { best = key; zb = z[e]; }
+            }
+        }
+        const uint64_t top = wave_max_key(best);
+        if (active && best == top)
+            part_smp[slot] = make_float4(key_value(top), __int_as_float((int)key_tiebreak(top)), zb, 0.f);
+    }
     float lm = z[0];
 #pragma unroll
     for (int e = 1; e < 8; ++e) lm = fmaxf(lm, z[e]);
@@ -208,6 +226,8 @@ struct MergeSmall {
     uint64_t bound;
     uint32_t cnt;
     uint32_t winners[SLIMSPEC_KMAX_INTERNAL];
+    uint64_t smp_key[16];
+    float smp_z[16];
 };
 
 template <int NT>
@@ -215,7 +235,9 @@ __device__ __forceinline__ void merge_row(unsigned char *dyn, bool cache_ids, Me
                                           const float2 *__restrict__ ms, const float *__restrict__ pv,
                                           const int *__restrict__ pi, int chunks, int k,
                                           int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
-                                          const int32_t *__restrict__ id_map)
+                                          const int32_t *__restrict__ id_map,
+                                          const float4 *__restrict__ smp, float *__restrict__ out_lse,
+                                          int32_t *__restrict__ out_sample_id, float *__restrict__ out_sample_lp)
 {
     constexpr int NWAVES = NT / 64;
     uint64_t *heads = reinterpret_cast<uint64_t *>(dyn);                      // [chunks]
@@ -273,6 +295,28 @@ __device__ __forceinline__ void merge_row(unsigned char *dyn, bool cache_ids, Me
 #pragma unroll
     for (int w = 0; w < NWAVES; ++w) Ssum += (S.red_m[w] == kNegInf) ? 0.f : S.red_s[w] * fast_exp(S.red_m[w] - M);
     const float lse = M + fast_log(Ssum);
+    if (smp) {
+        // stochastic-decoding outputs: the row's log-sum-exp and the Gumbel-max draw (largest z + g over the chunks)
+        uint64_t best = kNoKey;
+        float zb = 0.f;
+        for (int c = tid; c < chunks; c += NT) {
+            const float4 e = smp[c];
+            const uint64_t key = make_key(e.x, (uint32_t)__float_as_int(e.y));
+            if (key > best) { best = key; zb = e.z; }
+        }
+        const uint64_t top_w = wave_max_key(best);
+        if (lane == 0) S.smp_key[wave] = top_w;
+        if (best == top_w && best != kNoKey) S.smp_z[wave] = zb;
+        __syncthreads();
+        if (tid == 0) {
+            int wb = 0;
+            for (int w = 1; w < NWAVES; ++w) if (S.smp_key[w] > S.smp_key[wb]) wb = w;
+            const int id = (int)key_tiebreak(S.smp_key[wb]);
+            *out_lse = lse;
+            *out_sample_id = id_map ? id_map[id] : id;
+            *out_sample_lp = S.smp_z[wb] - lse;
+        }
+    }
 
     // (1) the k-th largest head: four adjacent lanes share one head, each counts a quarter of the others
     {

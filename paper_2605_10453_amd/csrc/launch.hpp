@@ -35,15 +35,28 @@ hipError_t launch_widen_rows(const uint16_t *h, float *x, int n, hipStream_t st)
 
 // One partial (max, sum of exp, top-k) per (row, 512-column chunk) from x [rows_here, K] (nds = 0) or
 // from nds slices of it (the output of launch_down_projection), and M [K, V].
+// part_smp (null: off): one Gumbel-max winner per (row, chunk) for sampling with the seed (seed_lo, seed_hi)
 hipError_t launch_stream_topk(const float *x, int nds, const void *M, bool m_is_f32,
                               float2 *part_ms, float *part_val, int *part_id,
-                              int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k, hipStream_t st);
+                              int rows_here, int row0, int K, int V, int chunks, int lanes, int nw1, int k,
+                              float4 *part_smp, uint32_t seed_lo, uint32_t seed_hi, hipStream_t st);
 
 // Combine the partials of every row into the final ids and log-probabilities.
+// Outputs of stochastic decoding (on: asked for): the noise seed, and per row the log-sum-exp over the vocabulary
+// and one Gumbel-max draw from the softmax with its log-probability.
+struct SampleOut {
+    int on = 0;
+    uint32_t seed_lo = 0, seed_hi = 0;
+    float *lse = nullptr;
+    int32_t *sample_ids = nullptr;
+    float *sample_logprobs = nullptr;
+};
+
 // id_map (may be null): the vocabulary id of every column, for heads over a kept subset of the vocabulary
+// part_smp [rows, chunks]: the chunks' Gumbel-max winners (when so.on)
 hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int *part_id,
                         int rows, int chunks, int k, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
-                        hipStream_t st);
+                        const SampleOut &so, const float4 *part_smp, hipStream_t st);
 
 // ---- matrix-core path (rows > kGemvMaxRows, bf16 weights) ----
 constexpr int kStreamList = 3;          // groups kept per lane stream

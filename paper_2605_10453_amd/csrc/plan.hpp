@@ -68,6 +68,7 @@ struct Plan {
     size_t off_part_ms = 0;    // float2 [rows, chunks]      running max, sum of exp
     size_t off_part_val = 0;   // float  [rows, chunks, k]   per-chunk top-k logits
     size_t off_part_id = 0;    // int32  [rows, chunks, k]   per-chunk top-k ids
+    size_t off_part_smp = 0;   // float4 [rows, chunks]      per-chunk Gumbel-max winners (sampling calls)
     size_t bytes = 0;
 };
 
@@ -88,6 +89,7 @@ inline Plan make_plan(HeadKind kind, int rows, int d, int r, int V, int k) {
     p.off_part_ms = off;    off = align_up(off + 2 * sizeof(float) * (size_t)rows * p.chunks);
     p.off_part_val = off;   off = align_up(off + sizeof(float) * (size_t)rows * p.chunks * k);
     p.off_part_id = off;    off = align_up(off + sizeof(int32_t) * (size_t)rows * p.chunks * k);
+    p.off_part_smp = off;   off = align_up(off + 16 * (size_t)rows * p.chunks);
     p.bytes = off;
     p.ok = true;
     return p;

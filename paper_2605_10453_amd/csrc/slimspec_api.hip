@@ -167,7 +167,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
 int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_is_f32,
              const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
              void *workspace, size_t workspace_bytes, void *stream, const int32_t *id_map = nullptr,
-             const Positions &pos = Positions())
+             const Positions &pos = Positions(), const SampleOut &so = SampleOut())
 {
     int st = check_shape(kind, shape, k);
     if (st != SLIMSPEC_OK) return st;
@@ -177,7 +177,8 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         return SLIMSPEC_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(out_ids) & 3u) || (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
         return SLIMSPEC_UNSUPPORTED;
-    const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK;
+    if (so.on && (!so.lse || !so.sample_ids || !so.sample_logprobs)) return SLIMSPEC_INVALID_ARGUMENT;
+    const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK && !so.on;
     if (use_mfma)
         return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, id_map, pos, workspace, workspace_bytes, stream);
     const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
@@ -189,6 +190,7 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     float2 *part_ms = reinterpret_cast<float2 *>(ws + p.off_part_ms);
     float *part_val = reinterpret_cast<float *>(ws + p.off_part_val);
     int *part_id = reinterpret_cast<int *>(ws + p.off_part_id);
+    float4 *part_smp = so.on ? reinterpret_cast<float4 *>(ws + p.off_part_smp) : nullptr;
     const uint16_t *hb = static_cast<const uint16_t *>(h);
 
     // Rows are processed in groups of kGemvMaxRows by the streaming kernels; the groups reuse the small
@@ -211,13 +213,23 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
         if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
         e = launch_stream_topk(kind == HeadKind::LowRank ? tpart : x, kind == HeadKind::LowRank ? dp.nds : 0, M, m_is_f32,
                                part_ms, part_val, part_id,
-                               rows_here, row0, p.K, p.V, p.chunks, p.lanes, p.nw1, k, s);
+                               rows_here, row0, p.K, p.V, p.chunks, p.lanes, p.nw1, k, part_smp, so.seed_lo, so.seed_hi, s);
         if (e != hipSuccess) return fail_hip(e);
         if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
     }
-    hipError_t e = launch_merge(part_ms, part_val, part_id, p.rows, p.chunks, k, out_ids, out_logprobs, id_map, s);
+    hipError_t e = launch_merge(part_ms, part_val, part_id, p.rows, p.chunks, k, out_ids, out_logprobs, id_map, so, part_smp, s);
     if (e != hipSuccess) return fail_hip(e);
     return SLIMSPEC_OK;
+}
+
+SampleOut sample_out(uint64_t seed, float *out_lse, int32_t *out_sample_ids, float *out_sample_logprobs)
+{
+    SampleOut so;
+    so.on = 1;
+    so.seed_lo = (uint32_t)(seed & 0xffffffffu);
+    so.seed_hi = (uint32_t)(seed >> 32);
+    so.lse = out_lse; so.sample_ids = out_sample_ids; so.sample_logprobs = out_sample_logprobs;
+    return so;
 }
 
 // Scratch one call of `kind` needs (the query slimspec_workspace_bytes reports the larger of the two heads).
@@ -293,6 +305,28 @@ int full_head_topk(const void *h, const void *W, slimspec_dtype w_dtype,
     if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
     return run_head(HeadKind::Full, h, nullptr, W, w_dtype == SLIMSPEC_F32, shape, k, out_ids, out_logprobs,
                     workspace, workspace_bytes, stream);
+}
+
+int slimspec_head_sample(const void *h, const void *A, const void *B,
+                         const slimspec_shape *shape, int32_t k, uint64_t seed,
+                         int32_t *out_ids, float *out_logprobs,
+                         float *out_lse, int32_t *out_sample_ids, float *out_sample_logprobs,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_head(HeadKind::LowRank, h, A, B, false, shape, k, out_ids, out_logprobs, workspace, workspace_bytes, stream,
+                    nullptr, Positions(), sample_out(seed, out_lse, out_sample_ids, out_sample_logprobs));
+}
+
+int full_head_sample(const void *h, const void *W, slimspec_dtype w_dtype,
+                     const slimspec_shape *shape, int32_t k, uint64_t seed,
+                     int32_t *out_ids, float *out_logprobs,
+                     float *out_lse, int32_t *out_sample_ids, float *out_sample_logprobs,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
+    return run_head(HeadKind::Full, h, nullptr, W, w_dtype == SLIMSPEC_F32, shape, k, out_ids, out_logprobs,
+                    workspace, workspace_bytes, stream, nullptr, Positions(),
+                    sample_out(seed, out_lse, out_sample_ids, out_sample_logprobs));
 }
 
 int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,

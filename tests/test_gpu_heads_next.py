@@ -103,3 +103,72 @@ def test_positions_with_one_matrix_equal_the_plain_head(gpu):
         p_ids, p_lp = b.slimspec_head_topk_positions(h, A.view(1, 128, 32), [0, rows], B, 6)
         torch.cuda.synchronize()
         assert torch.equal(a_ids, p_ids) and torch.equal(a_lp.view(torch.int32), p_lp.view(torch.int32))
+
+
+# ------------------------------------------------------------------ stochastic-decoding outputs
+
+def check_sample_outputs(torch, out, ora, seed, V, z_rows, oracle_mod):
+    """out: the library's five outputs; ora: the checker's SampleResult with z.  The drawn id must be the checker's,
+    or one whose z + g (checker's arithmetic) is within the tie tolerance of the checker's largest."""
+    ids, lp, lse, sid, slp = [t.cpu().numpy() for t in out]
+    rows = ids.shape[0]
+    z_at = lambda ri, ci: z_rows[ri, ci]
+    compare_with_oracle(ids, lp, ora.ids, ora.lse, z_at, V)
+    assert np.abs(lse - ora.lse).max() <= 2e-2, np.abs(lse - ora.lse).max()
+    n_other = 0
+    for i in range(rows):
+        assert 0 <= sid[i] < V
+        if sid[i] != ora.sample_ids[i]:
+            g = oracle_mod.gumbel_noise(seed, i, [sid[i], ora.sample_ids[i]])
+            w_gpu, w_ora = z_rows[i, sid[i]] + g[0], z_rows[i, ora.sample_ids[i]] + g[1]
+            assert w_ora - w_gpu <= 1e-3, (i, sid[i], ora.sample_ids[i], w_gpu, w_ora)
+            n_other += 1
+        assert abs(slp[i] - (z_rows[i, sid[i]] - ora.lse[i])) <= 2e-2
+    return n_other
+
+
+@pytest.mark.parametrize("rows,d,r,V,k,seed", [
+    (1, 256, 32, 8200, 8, 1), (1, 64, 16, 140000, 5, 2 ** 40 + 17), (3, 128, 16, 5000, 6, 3), (4, 512, 64, 10248, 10, 4),
+    (9, 96, 24, 2056, 7, 5), (40, 256, 32, 4104, 12, 6), (130, 64, 40, 2056, 5, 7), (20, 128, 32, 3080, 20, 8),
+    (12, 64, 24, 2056, 16, 9),
+])
+def test_low_rank_head_sample(gpu, oracle_mod, rows, d, r, V, k, seed):
+    torch, b = gpu
+    print(f"sample case rows={rows} d={d} r={r} V={V} k={k} seed={seed}", flush=True)
+    x = synth.make_inputs(synth.small_config(rows, d, r, V, k, peaked_every=4), seed=200 + rows)
+    out = b.slimspec_head_sample(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), k, seed)
+    torch.cuda.synchronize()
+    ora = oracle_mod.head_sample(x.h, x.A, x.B, k, seed, return_logits=True)
+    check_sample_outputs(torch, out, ora, seed, V, ora.z, oracle_mod)
+    # the top-k of a sampling call is the top-k of the plain call
+    ids, lp = b.slimspec_head_topk(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), k)
+    torch.cuda.synchronize()
+    assert torch.equal(ids, out[0])
+
+
+@pytest.mark.parametrize("rows,w_f32", [(2, False), (3, True), (33, False)])
+def test_full_head_sample(gpu, oracle_mod, rows, w_f32):
+    torch, b = gpu
+    x = synth.make_inputs(synth.small_config(rows, 128, 8, 6152, 9, peaked_every=3), seed=300 + rows, with_full_head=True)
+    W = synth.bf16_bits_to_f32(x.W) if w_f32 else x.W
+    out = b.full_head_sample(to_dev_bf16(x.h), to_dev_f32(W) if w_f32 else to_dev_bf16(W), 9, 77)
+    torch.cuda.synchronize()
+    ora = oracle_mod.head_sample(x.h, None, W, 9, 77, return_logits=True)
+    check_sample_outputs(torch, out, ora, 77, 6152, ora.z, oracle_mod)
+
+
+def test_sample_frequencies_on_the_gpu(gpu, oracle_mod):
+    """Many seeds on one row: the drawn ids follow the checker's softmax (binomial bound on the most likely tokens)."""
+    torch, b = gpu
+    x = synth.make_inputs(synth.small_config(1, 64, 8, 520, 5), seed=12)
+    hf = synth.bf16_bits_to_f32(x.h) * np.float32(2.0)                 # a sharper row: a few tokens carry most of the mass
+    x.h = synth.f32_to_bf16_bits(hf)
+    h, A, B = to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B)
+    ora = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, 5, return_logits=True)
+    p = np.exp(ora.z[0] - ora.lse[0])
+    n = 3000
+    counts = np.zeros(520)
+    for seed in range(n):
+        counts[int(b.slimspec_head_sample(h, A, B, 5, seed)[3][0])] += 1
+    for v in np.argsort(-p)[:4]:
+        assert abs(counts[v] / n - p[v]) < 5 * np.sqrt(p[v] * (1 - p[v]) / n), (v, counts[v] / n, p[v])
