@@ -325,6 +325,18 @@ def main():
                                "us_per_call_event_pairs": wcall, "weight_copies": 1,
                                "note": "the weights (135 MB at C2) stay in the 256 MB last-level cache between calls"}
 
+        # the same workload with the outputs of stochastic decoding (log-sum-exp and one Gumbel-max draw per row)
+        try:
+            hs_, As_, Bs_ = upload(x.h), [upload(x.A) for _ in range(copies)], [upload(x.B) for _ in range(copies)]
+            ws_s = torch.empty(binding.slimspec_workspace_bytes(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k), dtype=torch.uint8, device=dev)
+            sdt, _, scall = _timed(lambda i: binding.slimspec_head_sample(hs_, As_[i % copies], Bs_[i % copies], cfg.k, i, workspace=ws_s),
+                                   args.steps, args.warmup, with_events=False)
+            extra["with_sampling_outputs"] = {"us_per_call": sdt / args.steps * 1e6,
+                                              "note": "slimspec_head_sample: top-k, lse and one draw per row (the binding allocates "
+                                                      "five small output tensors per call here)"}
+            del hs_, As_, Bs_, ws_s
+        except Exception as exc:
+            extra["with_sampling_outputs"] = {"error": repr(exc)[:200]}
         log("[bench] full head on the same shape")
         g = torch.Generator(device=dev)
         g.manual_seed(1)
@@ -420,6 +432,12 @@ def main():
                     edt, ek, ecall = time_low_rank_tensors(h, As, Bs, k, nsteps, 8)
                     extra[name] = low_rank_entry(name, rows, d, r, V, k, edt, nsteps, ek, ecall, null_ms)
                     extra[name]["weight_copies"] = ncopies
+                    if name == "C4_512_rows":
+                        ws_s = torch.empty(binding.slimspec_workspace_bytes(rows, d, r, V, k), dtype=torch.uint8, device=dev)
+                        sdt, _, _ = _timed(lambda i: binding.slimspec_head_sample(h, As[i % ncopies], Bs[i % ncopies], k, i, workspace=ws_s),
+                                           20, 3, with_events=False)
+                        extra[name]["with_sampling_outputs_us_per_call"] = sdt / 20 * 1e6
+                        del ws_s
                     del h, As, Bs
                     torch.cuda.empty_cache()
                 except Exception as exc:

@@ -102,6 +102,51 @@ __device__ __forceinline__ void stream_combine(Stream<L> &a, const Stream<L> &b)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Gumbel-max sampling next to a stream: the two largest z_v + g_v the lane has seen for the row (in the records'
+// units) with their vocabulary ids, and the third largest (a bound for everything else the lane saw).
+struct SampleTrack { float w1, w2, w3; int id1, id2; };
+__device__ __forceinline__ void sample_init(SampleTrack &s) { s.w1 = kNegBig; s.w2 = kNegBig; s.w3 = kNegBig; s.id1 = 0; s.id2 = 0; }
+
+// The 16 values of one group (relative to `ref`, as in stream_group_rel); id0: the vocabulary id of element 0, element
+// i sits at id0 + 8 (i / 4) + i % 4.  Ids rise with i and from group to group, so "strictly larger" keeps the smaller
+// id among equal sums.
+template <bool NAT>
+__device__ __forceinline__ void sample_group(SampleTrack &s, const float (&v)[16], float ref, const GumbelKey &gk, int id0)
+{
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int id = id0 + 8 * (i >> 2) + (i & 3);
+        const float g2 = gumbel_base2(gk, (uint32_t)id);
+        const float w = (v[i] + ref) + (NAT ? g2 * kLn2 : g2);
+        const bool first = w > s.w1, second = w > s.w2;
+        s.w3 = second ? s.w2 : vmax(s.w3, w);
+        s.w2 = first ? s.w1 : (second ? w : s.w2);
+        s.id2 = first ? s.id1 : (second ? id : s.id2);
+        s.id1 = first ? id : s.id1;
+        s.w1 = first ? w : s.w1;
+    }
+}
+
+// fold track b into a (both saw different logits of the same row)
+__device__ __forceinline__ void sample_combine(SampleTrack &a, const SampleTrack &b)
+{
+    // merge of two sorted pairs (ties: smaller id first); the third place takes what is left
+    const auto before = [](float wa, int ia, float wb, int ib) { return wa > wb || (wa == wb && ia < ib); };
+    SampleTrack r;
+    const bool a1 = before(a.w1, a.id1, b.w1, b.id1);
+    r.w1 = a1 ? a.w1 : b.w1; r.id1 = a1 ? a.id1 : b.id1;
+    // candidates for second: the loser of the heads, and the winner's own second
+    const float lw = a1 ? b.w1 : a.w1, ow = a1 ? a.w2 : b.w2;
+    const int li = a1 ? b.id1 : a.id1, oi = a1 ? a.id2 : b.id2;
+    const bool l2 = before(lw, li, ow, oi);
+    r.w2 = l2 ? lw : ow; r.id2 = l2 ? li : oi;
+    // third: the larger of what was not taken (values only)
+    const float rest = l2 ? fmaxf(ow, a1 ? b.w2 : a.w2) : fmaxf(lw, a1 ? a.w3 : b.w3);
+    r.w3 = fmaxf(rest, fmaxf(a.w3, b.w3));
+    a = r;
+}
+
 // Work of block g: row block rb and the vocabulary tiles col, col + gw, col + 2 gw, ...
 // Blocks are dealt round-robin to the 8 XCDs, so blocks g and g + 8 share an L2: they get the same
 // vocabulary tiles and different row blocks, and so read each tile of M from HBM once.

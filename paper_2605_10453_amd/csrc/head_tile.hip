@@ -88,10 +88,16 @@ __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)
 // part: [rows][gw][3 + 3 L] stream records (values in base-2 units): one per row and block
 // DBG != 0 (experiment builds only, -DSLIMSPEC_DIAG_DBG=n): timing experiments (1 no epilogue, 2 loads only, 3 no loads);
 // their results are meaningless
-template <int L, int WR, bool F16, bool NAT, int DBG>
+// SAMPLE: every lane also keeps, per row, the largest logit + Gumbel noise it has seen (Gumbel-max sampling with the
+//         seed in `sd`; the noise's row index is sd.row_base + the row of this launch); records then have 20 floats:
+//         [12] the largest sum (in the record's units), [13] its id, [14] the second largest, [15] its id,
+//         [16] the third largest, [17..19] unused.
+struct SampleSeed { uint32_t seed_lo, seed_hi; int row_base; };
+
+template <int L, int WR, bool F16, bool NAT, int DBG, bool SAMPLE>
 __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
     const uint4 *__restrict__ X, const uint16_t *__restrict__ M, float *__restrict__ part,
-    int rows, int rows_pad, int K, int V, HeadGrid hg)
+    int rows, int rows_pad, int K, int V, HeadGrid hg, SampleSeed sd)
 {
     using S = TileShape<WR>;
     extern __shared__ __align__(1024) unsigned char lds_raw[];
@@ -179,6 +185,9 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
     Stream<L> st[2];
     stream_init(st[0]);
     stream_init(st[1]);
+    SampleTrack smp[2];
+    sample_init(smp[0]);
+    sample_init(smp[1]);
     f32x16 acc[2][4];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
@@ -348,6 +357,12 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
 #pragma unroll
                         for (int i = 0; i < 16; ++i) v[i] = acc[rt][jj][i];
                         stream_group_rel<L, NAT>(st[rt], v, ref, tile_max, c_vt * 8 + 4 * wv + jj);
+                        if constexpr (SAMPLE) {
+                            const uint32_t ln = lane_id_now();
+                            const int srow = sd.row_base + row0 + (wr * 2 + rt) * 32 + (int)(ln & 31);
+                            sample_group<NAT>(smp[rt], v, ref, gumbel_key(sd.seed_lo, sd.seed_hi, (uint32_t)srow),
+                                              n0 + 32 * (4 * wv + jj) + 4 * (int)(ln >> 5));
+                        }
                         __builtin_amdgcn_sched_barrier(0);
                     }
                     // the first tile's reference is its own maximum (-1e30 and an empty sum if every column was
@@ -381,7 +396,7 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
 
     // ---- one record per (row, block): the four streams of a row (two half-wavefronts x two column halves)
     // are folded into one, in a fixed order.  From here on a tag also names the half: tag * 2 + half.
-    constexpr int REC = 3 + 3 * L;
+    constexpr int REC = 3 + 3 * L + (SAMPLE ? 8 : 0);
     float *xchg = reinterpret_cast<float *>(lds_raw);                      // [RT][REC + 1], free after the last barrier
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
@@ -394,6 +409,12 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
 #pragma unroll
         for (int l = 0; l < L; ++l) { o.x[l] = __shfl_xor(a.x[l], 32); o.y[l] = __shfl_xor(a.y[l], 32); o.tag[l] = __shfl_xor(a.tag[l], 32); }
         if (half == 0) stream_combine(a, o);                                // lanes 0..31 now hold both halves
+        if constexpr (SAMPLE) {
+            SampleTrack so;
+            so.w1 = __shfl_xor(smp[rt].w1, 32); so.w2 = __shfl_xor(smp[rt].w2, 32); so.w3 = __shfl_xor(smp[rt].w3, 32);
+            so.id1 = __shfl_xor(smp[rt].id1, 32); so.id2 = __shfl_xor(smp[rt].id2, 32);
+            if (half == 0) sample_combine(smp[rt], so);
+        }
     }
     __syncthreads();                                                        // every wavefront is past its last operand read
     if (wv == 1 && half == 0) {
@@ -403,6 +424,10 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
             o[0] = st[rt].mc; o[1] = st[rt].s; o[2] = st[rt].U;
 #pragma unroll
             for (int l = 0; l < L; ++l) { o[3 + 3 * l] = st[rt].x[l]; o[4 + 3 * l] = st[rt].y[l]; o[5 + 3 * l] = __int_as_float(st[rt].tag[l]); }
+            if constexpr (SAMPLE) {
+                o[3 + 3 * L] = smp[rt].w1; o[4 + 3 * L] = __int_as_float(smp[rt].id1); o[5 + 3 * L] = smp[rt].w2;
+                o[6 + 3 * L] = __int_as_float(smp[rt].id2); o[7 + 3 * L] = smp[rt].w3;
+            }
         }
     }
     __syncthreads();
@@ -416,11 +441,21 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
 #pragma unroll
             for (int l = 0; l < L; ++l) { o.x[l] = i[3 + 3 * l]; o.y[l] = i[4 + 3 * l]; o.tag[l] = __float_as_int(i[5 + 3 * l]); }
             stream_combine(st[rt], o);
+            if constexpr (SAMPLE) {
+                SampleTrack so;
+                so.w1 = i[3 + 3 * L]; so.id1 = __float_as_int(i[4 + 3 * L]); so.w2 = i[5 + 3 * L];
+                so.id2 = __float_as_int(i[6 + 3 * L]); so.w3 = i[7 + 3 * L];
+                sample_combine(smp[rt], so);
+            }
             if (row >= rows) continue;
             float *w = part + ((size_t)row * hg.gw + col) * REC;
             w[0] = st[rt].mc; w[1] = st[rt].s; w[2] = st[rt].U;
 #pragma unroll
             for (int l = 0; l < L; ++l) { w[3 + 3 * l] = st[rt].x[l]; w[4 + 3 * l] = st[rt].y[l]; w[5 + 3 * l] = __int_as_float(st[rt].tag[l]); }
+            if constexpr (SAMPLE) {
+                w[3 + 3 * L] = smp[rt].w1; w[4 + 3 * L] = __int_as_float(smp[rt].id1); w[5 + 3 * L] = smp[rt].w2;
+                w[6 + 3 * L] = __int_as_float(smp[rt].id2); w[7 + 3 * L] = smp[rt].w3;
+            }
         }
     }
 }
@@ -450,17 +485,17 @@ int head_tile_rows_per_block(int rows) {
     return rows > 128 ? 256 : 128;
 }
 
-template <int WR, bool F16, bool NAT, int DBG>
+template <int WR, bool F16, bool NAT, int DBG, bool SAMPLE>
 static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part, int rows, int rows_pad,
-                                  int K, int V, int n_rb, int gw, hipStream_t st)
+                                  int K, int V, int n_rb, int gw, const SampleSeed &sd, hipStream_t st)
 {
     using S = TileShape<WR>;
-    auto fn = head_tile_kernel<kStreamList, WR, F16, NAT, DBG>;
+    auto fn = head_tile_kernel<kStreamList, WR, F16, NAT, DBG, SAMPLE>;
     static LdsLimit lds_limit;
     hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(fn), S::LDS);
     if (e != hipSuccess) return e;
     HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT};
-    fn<<<n_rb * gw, 64 * S::NW, S::LDS, st>>>(static_cast<const uint4 *>(X), M, part, rows, rows_pad, K, V, hg);
+    fn<<<n_rb * gw, 64 * S::NW, S::LDS, st>>>(static_cast<const uint4 *>(X), M, part, rows, rows_pad, K, V, hg, sd);
     return hipGetLastError();
 }
 
@@ -472,16 +507,19 @@ static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part,
 bool head_tile_timing_only() { return SLIMSPEC_DIAG_DBG != 0; }
 
 hipError_t launch_head_tile(const void *X, bool x_is_f16, bool natural_units, const uint16_t *M, float *part, int rows, int rows_pad,
-                            int K, int V, int n_rb, int gw, hipStream_t st)
+                            int K, int V, int n_rb, int gw, const SampleOut &so, int row_base, hipStream_t st)
 {
     const bool big = head_tile_rows_per_block(rows) == 256;
-#define SLIMSPEC_TILE_F(F16, NAT, DBG) (big ? launch_tile_cfg<4, F16, NAT, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st) \
-                                            : launch_tile_cfg<2, F16, NAT, DBG>(X, M, part, rows, rows_pad, K, V, n_rb, gw, st))
+    const SampleSeed sd{so.seed_lo, so.seed_hi, row_base};
+#define SLIMSPEC_TILE_S(F16, NAT, DBG, SMP) (big ? launch_tile_cfg<4, F16, NAT, DBG, SMP>(X, M, part, rows, rows_pad, K, V, n_rb, gw, sd, st) \
+                                                 : launch_tile_cfg<2, F16, NAT, DBG, SMP>(X, M, part, rows, rows_pad, K, V, n_rb, gw, sd, st))
+#define SLIMSPEC_TILE_F(F16, NAT, DBG) (so.on ? SLIMSPEC_TILE_S(F16, NAT, 0, true) : SLIMSPEC_TILE_S(F16, NAT, DBG, false))
 #define SLIMSPEC_TILE(DBG) (natural_units ? SLIMSPEC_TILE_F(false, true, DBG) \
                                           : (x_is_f16 ? SLIMSPEC_TILE_F(true, false, DBG) : SLIMSPEC_TILE_F(false, false, DBG)))
     return SLIMSPEC_TILE(SLIMSPEC_DIAG_DBG);
 #undef SLIMSPEC_TILE
 #undef SLIMSPEC_TILE_F
+#undef SLIMSPEC_TILE_S
 }
 
 }  // namespace slimspec

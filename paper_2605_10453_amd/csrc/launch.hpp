@@ -61,6 +61,7 @@ hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int 
 // ---- matrix-core path (rows > kGemvMaxRows, bf16 weights) ----
 constexpr int kStreamList = 3;          // groups kept per lane stream
 constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial
+constexpr int kStreamRecSample = kStreamRec + 8;  // ... of a sampling call
 
 // t = h A for up to 512 rows: 64 x 64 tiles over slices of the contraction (partial tiles in `part`), then the
 // fixed-order sum of the slices: fp32 t, the 16-bit operand t log2(e) (bf16, or f16 when as_f16) in the k-grouped
@@ -78,8 +79,10 @@ hipError_t launch_down_projection_tiles(const uint16_t *h, const uint16_t *A, fl
 // x_is_f16: X holds f16 t log2(e) and the kernel turns the M tiles into f16 inside LDS (an 8 times
 // finer operand than bf16); otherwise X holds bf16 t log2(e)
 // natural_units: X holds the bf16 contraction input itself (full head) and the records carry natural-log values
+// so.on: the records also carry every stream's Gumbel-max candidates (kStreamRecSample floats per record); row_base:
+// index of the launch's first row in the call (the noise is a function of the row's index in the call)
 hipError_t launch_head_tile(const void *X, bool x_is_f16, bool natural_units, const uint16_t *M, float *part, int rows, int rows_pad,
-                            int K, int V, int n_rb, int gw, hipStream_t st);
+                            int K, int V, int n_rb, int gw, const SampleOut &so, int row_base, hipStream_t st);
 // true only in an experiment build (-DSLIMSPEC_DIAG_DBG=n) where a timing-only variant replaces the kernel: its
 // output is not a result and the calls then return SLIMSPEC_UNSUPPORTED
 bool head_tile_timing_only();
@@ -95,6 +98,6 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
-                                void *defer_buf, hipStream_t st);
+                                void *defer_buf, const SampleOut &so, int row_base, hipStream_t st);
 
 }  // namespace slimspec

@@ -33,10 +33,12 @@ static_assert(kMergeThreads * 4 <= kWorkCap, "a step of the exhaustive pass appe
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
 constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
 constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes the exhaustive exact pass
-constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
+constexpr int kListedBit = 1 << 30;
+constexpr int kSampleBit = 1 << 29;     // ... an entry of the sampling contenders' list (smp_id / smp_z) instead     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
 constexpr float kEpsSigmas = 4.0f;      // eps_v = this many standard deviations of the rounding error of t in column v
                                         // (values are re-evaluated when within eps_a + eps_b = 5.6 sigma of their difference)
 constexpr float kTileMaxBias = 1.35f;   // expected largest / true of 256 column rms estimates from 32 samples each
+constexpr int kSampleCap = 32;          // streams whose best z + g may be the row's Gumbel-max draw, at most
 constexpr int kTsCap = 4096;            // vocabulary tiles whose column scale is kept in shared memory (1 M columns)
 constexpr float kEpsViolation = 1.5f;   // a re-evaluated value further than this many eps_v from its computed value
                                         // shows that the bound does not hold for this input: the row is done exhaustively
@@ -94,13 +96,16 @@ __device__ __forceinline__ void rank_all_pairs(const uint64_t *keys, int n, int 
 
 }  // namespace
 
+// so.on (sampling calls): the records have rec_stride = kStreamRecSample floats and also carry every stream's best
+// and second best z + g (Gumbel noise); the row's draw is the largest over the streams, decided on exact logits
+// for every stream whose best is within the rounding bound of the largest.
 __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
-    const float *__restrict__ part, int nsr, int gw, int n_vt,
+    const float *__restrict__ part, int rec_stride, int nsr, int gw, int n_vt,
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float2 *__restrict__ tilescale,
     int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
-    const int32_t *__restrict__ id_map, int *__restrict__ defer, int resume)
+    const int32_t *__restrict__ id_map, int *__restrict__ defer, int resume, SampleOut so, int row_base)
 {
     constexpr int L = kStreamList, REC = kStreamRec, NT = kMergeThreads, NWAVES = kMergeThreads / 64;
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -122,13 +127,40 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __shared__ uint64_t tau_key;
     __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden, cnt_need;
     __shared__ int tau_slot, eps_violated;
+    __shared__ uint64_t smp_wkey[NWAVES];                               // sampling: per-wavefront reductions
+    __shared__ float smp_wz[NWAVES], smp_w2[NWAVES], lse_out_sh;
+    __shared__ int smp_id[kSampleCap];
+    __shared__ float smp_z[kSampleCap];
+    __shared__ uint32_t smp_cnt;
     __shared__ uint64_t thr_key;
     __shared__ uint32_t cnt_buf;
     __shared__ uint32_t winners[SLIMSPEC_KMAX_INTERNAL];
 
     const int row = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const float *rec = part + (size_t)row * nsr * REC;
+    const float *rec = part + (size_t)row * nsr * rec_stride;
+    const GumbelKey gk = gumbel_key(so.seed_lo, so.seed_hi, (uint32_t)(row_base + row));
+    // The block's largest key and the z that goes with it, in every thread (keys are unique or kNoKey).
+    const auto block_best = [&](uint64_t key, float z, float &z_out) {
+        const uint64_t top_w = wave_max_key(key);
+        __syncthreads();
+        if (lane == 0) smp_wkey[wave] = top_w;
+        if (key == top_w && key != kNoKey) smp_wz[wave] = z;
+        __syncthreads();
+        int wb = 0;
+#pragma unroll
+        for (int w = 1; w < NWAVES; ++w) if (smp_wkey[w] > smp_wkey[wb]) wb = w;
+        z_out = smp_wz[wb];
+        return smp_wkey[wb];
+    };
+    const auto write_sample = [&](uint64_t key, float z, float lse_final) {
+        if (tid == 0) {
+            const int id = (int)key_tiebreak(key);
+            so.lse[row_base + row] = lse_final;
+            so.sample_ids[row_base + row] = id_map ? id_map[id] : id;
+            so.sample_logprobs[row_base + row] = z - lse_final;
+        }
+    };
     RowCtx ctx;
     ctx.x = x_is_bf16 ? static_cast<const void *>(static_cast<const uint16_t *>(xexact) + (size_t)row * ldx)
                       : static_cast<const void *>(static_cast<const float *>(xexact) + (size_t)row * ldx);
@@ -152,6 +184,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         for (int q = 0; q < n_work; ++q) corr += by_rank[q];
         const float s_fixed = S + corr;
         const float lse_fixed = (s_fixed > 0.f) ? (Mx + __builtin_amdgcn_logf(s_fixed)) * kLn2 : lse;
+        if (tid == 0) lse_out_sh = lse_fixed;
         if (tid < k) {
             const uint32_t c = winners[tid];
             out_ids[(size_t)row * k + tid] = id_map ? id_map[w_id[c]] : w_id[c];
@@ -176,15 +209,23 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     if (tid == 0) { thr_key = kNoKey; cnt_buf = 0u; }
     __syncthreads();
     float em = kNegInf, es = 0.f;
+    uint64_t sbest = kNoKey;                                  // sampling: this thread's largest z + g and its z
+    float sbest_z = 0.f;
     for (int c0 = 0; c0 < V; c0 += NT * 4) {
         const int col = c0 + tid * 4;
         if (col < V) {
             float z[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int j = 0; j < K; ++j) {
-                const uint2 w = *reinterpret_cast<const uint2 *>(M + (size_t)j * V + col);
-                const float xj = x_at(ctx, j);
-                z[0] = fmaf(xj, bf16_lo(w.x), z[0]); z[1] = fmaf(xj, bf16_hi(w.x), z[1]);
-                z[2] = fmaf(xj, bf16_lo(w.y), z[2]); z[3] = fmaf(xj, bf16_hi(w.y), z[3]);
+            constexpr int NJ = 8;                              // rows of M in flight per thread (summed in row order)
+            for (int j0 = 0; j0 < K; j0 += NJ) {
+                uint2 w[NJ];
+#pragma unroll
+                for (int u = 0; u < NJ; ++u) w[u] = *reinterpret_cast<const uint2 *>(M + (size_t)min(j0 + u, K - 1) * V + col);
+#pragma unroll
+                for (int u = 0; u < NJ; ++u) {
+                    const float xj = (j0 + u < K) ? x_at(ctx, j0 + u) : 0.f;
+                    z[0] = fmaf(xj, bf16_lo(w[u].x), z[0]); z[1] = fmaf(xj, bf16_hi(w[u].x), z[1]);
+                    z[2] = fmaf(xj, bf16_lo(w[u].y), z[2]); z[3] = fmaf(xj, bf16_hi(w[u].y), z[3]);
+                }
             }
             const uint64_t thr = thr_key;
 #pragma unroll
@@ -194,6 +235,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 em = m_new;
                 const uint64_t key = make_key(z[e], (uint32_t)(col + e));
                 if (key > thr) work[atomicAdd(&cnt_buf, 1u)] = key;     // at most k + 4 NT = kExhaustCap entries: fits
+                if (so.on) {
+                    const uint64_t skey = make_key(z[e] + gumbel_base2(gk, (uint32_t)(col + e)) * kLn2, (uint32_t)(col + e));
+                    if (skey > sbest) { sbest = skey; sbest_z = z[e]; }
+                }
             }
         }
         __syncthreads();
@@ -228,6 +273,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         out_ids[(size_t)row * k + tid] = id_map ? id_map[id] : id;
         out_logprobs[(size_t)row * k + tid] = key_value(work[tid]) - lse_exact;
     }
+    if (so.on) {
+        float zs;
+        const uint64_t top = block_best(sbest, sbest_z, zs);
+        write_sample(top, zs, lse_exact);
+    }
     };
 
     if (resume) {
@@ -258,12 +308,12 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     // a stream record as three 16-byte loads; the thread's first stream stays in registers
     static_assert(REC == 12, "three float4 per record");
     typedef float f32x4 __attribute__((ext_vector_type(4)));      // native vectors stay in registers (a float4 array did not)
-    const f32x4 *mine_src = reinterpret_cast<const f32x4 *>(rec + (size_t)min(tid, nsr - 1) * REC);
+    const f32x4 *mine_src = reinterpret_cast<const f32x4 *>(rec + (size_t)min(tid, nsr - 1) * rec_stride);
     const f32x4 mine0 = mine_src[0], mine1 = mine_src[1], mine2 = mine_src[2];
     auto load_rec = [&](int sidx, float (&f)[REC]) {
         f32x4 a = mine0, b = mine1, c = mine2;
         if (sidx != tid) {
-            const f32x4 *src = reinterpret_cast<const f32x4 *>(rec + (size_t)sidx * REC);
+            const f32x4 *src = reinterpret_cast<const f32x4 *>(rec + (size_t)sidx * rec_stride);
             a = src[0]; b = src[1]; c = src[2];
         }
         f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
@@ -342,6 +392,16 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             out_ids[(size_t)row * k + tid] = id_map ? id_map[tid] : tid;
             out_logprobs[(size_t)row * k + tid] = -__builtin_amdgcn_logf((float)V) * kLn2;
         }
+        if (so.on) {                                        // the draw: the largest noise alone
+            uint64_t best = kNoKey;
+            for (int v = tid; v < V; v += NT) {
+                const uint64_t key = make_key(gumbel_base2(gk, (uint32_t)v) * kLn2, (uint32_t)v);
+                if (key > best) best = key;
+            }
+            float zs;
+            const uint64_t top = block_best(best, 0.f, zs);
+            write_sample(top, 0.f, __builtin_amdgcn_logf((float)V) * kLn2);
+        }
         return;
     }
     // ---- tau: the k-th largest listed maximum.  The lists are sorted, so first T = the k-th largest of the
@@ -404,6 +464,42 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     // are off by up to a factor e^eps) no longer gives the log-sum-exp to the reported precision, and the
     // correction by the re-evaluated terms could itself overflow.
     bool exhaustive = !(eps < kExhaustiveEps) || !(lse == lse) || !(fabsf(lse) < 1e30f);
+
+    // ---- sampling: the streams whose best z + g could be the row's largest once the logits are exact
+    if (so.on) {
+        uint64_t best = kNoKey;
+        float w2m = kNegInf;
+        for (int sidx = tid; sidx < nsr; sidx += NT) {
+            const float *sp = rec + (size_t)sidx * rec_stride + REC;
+            const float w1 = sp[0], w3 = sp[4];
+            if (w1 > kNoValue) best = u64_max(best, make_key(w1 * unit, (uint32_t)__float_as_int(sp[1])));
+            if (w3 > kNoValue) w2m = fmaxf(w2m, w3 * unit);        // bounds what the stream saw beyond its two recorded ids
+        }
+        float unused;
+        const uint64_t top = block_best(best, 0.f, unused);
+        w2m = wave_max(w2m);
+        if (tid == 0) smp_cnt = 0u;
+        if (lane == 0) smp_w2[wave] = w2m;
+        __syncthreads();
+        float W2 = smp_w2[0];
+#pragma unroll
+        for (int w = 1; w < NWAVES; ++w) W2 = fmaxf(W2, smp_w2[w]);
+        const float thr_s = key_value(top) - 2.f * eps;
+        for (int sidx = tid; sidx < nsr; sidx += NT) {
+            const float *sp = rec + (size_t)sidx * rec_stride + REC;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {                    // the stream's best and second best
+                const int idq = __float_as_int(sp[2 * q + 1]);
+                if (sp[2 * q] > kNoValue && sp[2 * q] * unit >= thr_s && (unsigned)idq < (unsigned)V) {
+                    const uint32_t slot = atomicAdd(&smp_cnt, 1u);
+                    if (slot < (uint32_t)kSampleCap) smp_id[slot] = idq;
+                }
+            }
+        }
+        __syncthreads();
+        // a stream's third best within the bound (its id is not recorded), too many contenders, or none: whole row exact
+        if (top == kNoKey || smp_cnt == 0u || smp_cnt > (uint32_t)kSampleCap || W2 >= thr_s) exhaustive = true;
+    }
 
     // ---- collect
     auto push = [&](int id, float val, int need, float e_item) {
@@ -502,6 +598,15 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             if (tid == 0) { w_need[0] = tau_slot | kListedBit; cnt_need = 1u; }
             __syncthreads();
         }
+        if (so.on) {                                         // the sampling contenders join the list of columns to evaluate
+            const uint32_t base_n = cnt_need;
+            __syncthreads();
+            if (base_n + smp_cnt <= (uint32_t)kWorkCap) {
+                if (tid < (int)smp_cnt) w_need[base_n + tid] = tid | kSampleBit;
+                if (tid == 0) cnt_need = base_n + smp_cnt;
+            } else if (tid == 0) eps_violated = 1;          // no room (thousands of near-ties): exhaustive pass
+            __syncthreads();
+        }
         if (park && cnt_need != 0u && cnt_need <= (uint32_t)kDeferNeed && n_work <= kDeferWork) {
             // park the row: collected set, list of columns, the streams' log-sum-exp
             const int n_need = (int)cnt_need;
@@ -521,8 +626,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         for (int g0 = 0; g0 < n_need; g0 += 16) {
             const int u = lane & 15, jsub = lane >> 4;
             const int entry = w_need[min(g0 + u, n_need - 1)];
-            const int item = entry & (kListedBit - 1);
-            const int id = w_id[item];
+            const int item = entry & (kSampleBit - 1);
+            const int id = (entry & kSampleBit) ? smp_id[item] : w_id[item];
             float acc = 0.f;
             // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 16 independent loads per lane (K = 512: one round trip)
             const uint16_t *mcol = M + id;
@@ -548,13 +653,29 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 float z = red_ex[0][tid];
 #pragma unroll
                 for (int w = 1; w < NWAVES; ++w) z += red_ex[w][tid];
-                take_exact(entry, z, Mx);                 // tid < 16: u == tid, so `entry` is this column's
+                if (entry & kSampleBit) smp_z[item] = z;
+                else take_exact(entry, z, Mx);            // tid < 16: u == tid, so `entry` is this column's
             }
             __syncthreads();
         }
         __syncthreads();
         if (!eps_violated) {
+            uint64_t skey = kNoKey;
+            float sz = 0.f;
+            if (so.on) {                                     // the draw: the contenders' exact logits plus their noise
+                uint64_t mine = kNoKey;
+                float zm = 0.f;
+                if (tid < (int)smp_cnt) {
+                    zm = smp_z[tid];
+                    mine = make_key(zm + gumbel_base2(gk, (uint32_t)smp_id[tid]) * kLn2, (uint32_t)smp_id[tid]);
+                }
+                skey = block_best(mine, zm, sz);
+            }
             finish(n_work, S, Mx, lse);
+            if (so.on) {
+                __syncthreads();
+                write_sample(skey, sz, lse_out_sh);
+            }
             return;
         }
     }
@@ -624,23 +745,24 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
                                 const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
-                                void *defer_buf, hipStream_t st)
+                                void *defer_buf, const SampleOut &so, int row_base, hipStream_t st)
 {
     const size_t lds = merge_streams_lds_bytes(nsr, k, n_vt) + sizeof(float) * (size_t)K;      // + the row's contraction input
     static LdsLimit lds_limit;
     hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(merge_streams_kernel), (int)lds);
     if (e != hipSuccess) return e;
-    int *defer = static_cast<int *>(defer_buf);
-    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
+    int *defer = so.on ? nullptr : static_cast<int *>(defer_buf);      // sampling calls evaluate in place
+    const int rec_stride = so.on ? kStreamRecSample : kStreamRec;
+    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, rec_stride, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
                                                            M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
-                                                           defer, 0);
+                                                           defer, 0, so, row_base);
     if ((e = hipGetLastError()) != hipSuccess || !defer) return e;
     // parked rows: their exact columns on many CUs, then the rest of their merge
     exact_cols_kernel<<<dim3(kDeferSlices, rows), 256, 0, st>>>(defer, xexact, x_is_bf16 ? 1 : 0, ldx, M, K, V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
+    merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, rec_stride, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
                                                            M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
-                                                           defer, 1);
+                                                           defer, 1, so, row_base);
     return hipGetLastError();
 }
 

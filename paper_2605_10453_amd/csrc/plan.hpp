@@ -105,7 +105,7 @@ constexpr size_t kMergeLdsLimit = 160 * 1024 - 1024;
 // ---- matrix-core path -------------------------------------------------------------------
 constexpr int kPlanSlotsPerXcd = 32;     // blocks per XCD of the persistent kernel (256 CUs / 8 XCDs)
 constexpr int kStreamListPlan = 3;       // must equal kStreamList (launch.hpp)
-constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan;
+constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan + 8;      // sized for sampling calls (kStreamRecSample, launch.hpp)
 
 int head_tile_rows_per_block(int rows);
 size_t merge_defer_bytes(int rows);

@@ -99,7 +99,7 @@ int position_of_row(const Positions &pos, int row)
 
 int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
                   const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
-                  const Positions &pos, void *workspace, size_t workspace_bytes, void *stream)
+                  const Positions &pos, const SampleOut &so, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (workspace_bytes < mfma_workspace_bytes(kind, shape)) return SLIMSPEC_WORKSPACE_TOO_SMALL;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -137,27 +137,27 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
                                              p.rows_pad, d, r, t32, t16, stat, Mb, V, tilescale, tile_f16, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-            e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, s);
+            e = launch_head_tile(t16, tile_f16, false, Mb, streams, rows, p.rows_pad, r, V, p.n_rb, p.gw, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;      // diagnostic build, timing-only kernel: no result
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, tilescale, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
-                                     (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, s);
+                                     (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);
         } else {
             // the full head runs the same kernel on h itself (bf16 exact, natural units): no rounding statistics
             void *hx = ws + p.off_t16;
             if ((e = launch_regroup_rows(hrow, hx, rows, p.rows_pad, d, s)) != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_start, s)) != hipSuccess) return fail_hip(e);
-            e = launch_head_tile(hx, false, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, s);
+            e = launch_head_tile(hx, false, true, Mb, streams, rows, p.rows_pad, d, V, p.n_rb, p.gw, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;
             e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
-                                     (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, s);
+                                     (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);
         }
     }
@@ -178,9 +178,9 @@ int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_
     if ((reinterpret_cast<uintptr_t>(out_ids) & 3u) || (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
         return SLIMSPEC_UNSUPPORTED;
     if (so.on && (!so.lse || !so.sample_ids || !so.sample_logprobs)) return SLIMSPEC_INVALID_ARGUMENT;
-    const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK && !so.on;
+    const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK;
     if (use_mfma)
-        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, id_map, pos, workspace, workspace_bytes, stream);
+        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, id_map, pos, so, workspace, workspace_bytes, stream);
     const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
     if (workspace_bytes < p.bytes) return SLIMSPEC_WORKSPACE_TOO_SMALL;
 

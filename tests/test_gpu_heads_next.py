@@ -172,3 +172,29 @@ def test_sample_frequencies_on_the_gpu(gpu, oracle_mod):
         counts[int(b.slimspec_head_sample(h, A, B, 5, seed)[3][0])] += 1
     for v in np.argsort(-p)[:4]:
         assert abs(counts[v] / n - p[v]) < 5 * np.sqrt(p[v] * (1 - p[v]) / n), (v, counts[v] / n, p[v])
+
+
+def test_config2_sample(gpu, oracle_mod):
+    """The single-row latency workload with the outputs of stochastic decoding, three seeds."""
+    torch, b = gpu
+    cfg = synth.CONFIGS["C2"]
+    x = synth.make_inputs(cfg, 0)
+    h, A, B = to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B)
+    for seed in (0, 1, 2 ** 33 + 5):
+        out = b.slimspec_head_sample(h, A, B, cfg.k, seed)
+        torch.cuda.synchronize()
+        ora = oracle_mod.head_sample(x.h, x.A, x.B, cfg.k, seed, return_logits=True)
+        check_sample_outputs(torch, out, ora, seed, cfg.V, ora.z, oracle_mod)
+
+
+def test_config4_sample(gpu, oracle_mod):
+    """The 512-row throughput workload (matrix-core path, peaked rows) with the outputs of stochastic decoding."""
+    torch, b = gpu
+    cfg = synth.CONFIGS["C4"]
+    x = synth.make_inputs(cfg, 0)
+    out = b.slimspec_head_sample(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), cfg.k, 12345)
+    torch.cuda.synchronize()
+    ora = oracle_mod.head_sample(x.h, x.A, x.B, cfg.k, 12345, return_logits=True)
+    n_other = check_sample_outputs(torch, out, ora, 12345, cfg.V, ora.z, oracle_mod)
+    print(f"C4 sampling: {n_other} of {cfg.rows} rows drew another id within the tolerance", flush=True)
+    assert n_other <= 2
