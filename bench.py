@@ -374,6 +374,24 @@ def main():
             extra["truncated_head"] = trunc
         except Exception as exc:
             extra["truncated_head"] = {"error": repr(exc)[:200]}
+        # the dynamic-selection comparator of Appendix C: low-rank router, exact full-head logits on the routed ids
+        try:
+            k_route = 64
+            hr_, Ar_, Br_ = upload(x.h), [upload(x.A) for _ in range(2)], [upload(x.B) for _ in range(2)]
+            idr, lpr, _ = out_buffers(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k)
+            shape_r = binding.SlimspecShape(cfg.rows, cfg.d, cfg.r, cfg.V)
+            import ctypes as _ct
+            wsr = torch.empty(int(binding.load_library().routed_workspace_bytes(_ct.byref(shape_r), k_route)), dtype=torch.uint8, device=dev)
+            step_r = lambda i: binding.routed_head_topk(hr_, Ar_[i % 2], Br_[i % 2], Ws[i % 2], k_route, cfg.k,
+                                                        out_ids=idr, out_logprobs=lpr, workspace=wsr)
+            rdt, _, _ = _timed(step_r, nf, 5, with_events=False)
+            extra["routed_head"] = {"us_per_call": rdt / nf * 1e6, "k_route": k_route, "relative_to_full_head": rdt / fdt,
+                                    "paper_relative_head_time_r_d8": 0.46,
+                                    "note": "routed_head_topk: low-rank router (k_route ids per row), exact logits on those, softmax "
+                                            "over them; the paper's ratio is SpecVocab at r = d/8 on H200 in vLLM (context only)"}
+            del hr_, Ar_, Br_, wsr
+        except Exception as exc:
+            extra["routed_head"] = {"error": repr(exc)[:200]}
         # six head calls (the paper's six draft steps, section 5.1) captured in one HIP graph: no host launch jitter
         try:
             hg = upload(x.h)

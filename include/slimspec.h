@@ -178,6 +178,22 @@ int truncated_head_topk(const void *h, const void *W_tr, slimspec_dtype w_dtype,
                         void *workspace, size_t workspace_bytes,
                         void *stream);
 
+/* Router-then-exact head (section 2, "Dynamic vocabulary selection": a low-rank router scores
+ * the vocabulary, the best-scoring tokens are kept and the full head is evaluated on those only;
+ * the shape of the SpecVocab baseline of Appendix C):
+ *     q = (h A) B over all V          (the router: slimspec_head_topk with k = k_route)
+ *     S = the k_route ids of the largest q of the row
+ *     y_v = h W[:, v] for v in S       (exact full-head logits, fp32 accumulation)
+ *     outputs: the k best of S by y (equal y: smaller id) with y_v - log sum_{u in S} exp(y_u)
+ * W [d, V] bf16 or fp32; 1 <= k <= k_route <= SLIMSPEC_KMAX.  Workspace: routed_workspace_bytes.
+ * (A router k above 16 takes the streaming kernels in groups of 8 rows: meant for few rows.) */
+size_t routed_workspace_bytes(const slimspec_shape *shape, int32_t k_route);
+int routed_head_topk(const void *h, const void *A, const void *B, const void *W, slimspec_dtype w_dtype,
+                     const slimspec_shape *shape, int32_t k_route, int32_t k,
+                     int32_t *out_ids, float *out_logprobs,
+                     void *workspace, size_t workspace_bytes,
+                     void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *slimspec_status_string(int status);
 

@@ -100,4 +100,10 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
                                 void *defer_buf, const SampleOut &so, int row_base, hipStream_t st);
 
+// ---- router-then-exact head: exact full-head logits on each row's k_route routed ids, softmax and top-k over them
+// part: rows * routed_slices(d) * k_route floats of scratch
+int routed_slices(int d);
+hipError_t launch_routed_exact(const uint16_t *h, const void *W, bool w_is_f32, const int32_t *route_ids, float *part,
+                               int rows, int d, int V, int k_route, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st);
+
 }  // namespace slimspec

@@ -329,6 +329,42 @@ int full_head_sample(const void *h, const void *W, slimspec_dtype w_dtype,
                     sample_out(seed, out_lse, out_sample_ids, out_sample_logprobs));
 }
 
+size_t routed_workspace_bytes(const slimspec_shape *shape, int32_t k_route)
+{
+    if (!shape) return 0;
+    const size_t router = head_workspace_bytes(HeadKind::LowRank, shape, k_route);
+    if (router == 0) return 0;
+    const size_t n = (size_t)shape->rows * k_route;
+    return align_up(router) + align_up(4 * n) + align_up(4 * n) + align_up(4 * n * routed_slices(shape->d));
+}
+
+int routed_head_topk(const void *h, const void *A, const void *B, const void *W, slimspec_dtype w_dtype,
+                     const slimspec_shape *shape, int32_t k_route, int32_t k,
+                     int32_t *out_ids, float *out_logprobs,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
+    const int st = check_shape(HeadKind::LowRank, shape, k_route);
+    if (st != SLIMSPEC_OK) return st;
+    if (k < 1 || k > k_route) return SLIMSPEC_INVALID_ARGUMENT;
+    if (!W || !out_ids || !out_logprobs || !workspace) return SLIMSPEC_INVALID_ARGUMENT;
+    if (!aligned16(W)) return SLIMSPEC_UNSUPPORTED;
+    if (workspace_bytes < routed_workspace_bytes(shape, k_route)) return SLIMSPEC_WORKSPACE_TOO_SMALL;
+    char *ws = static_cast<char *>(workspace);
+    const size_t router = align_up(head_workspace_bytes(HeadKind::LowRank, shape, k_route));
+    const size_t n = (size_t)shape->rows * k_route;
+    int32_t *route_ids = reinterpret_cast<int32_t *>(ws + router);
+    float *route_lp = reinterpret_cast<float *>(ws + router + align_up(4 * n));
+    float *part = reinterpret_cast<float *>(ws + router + 2 * align_up(4 * n));
+    // the router: the low-rank head's k_route best ids of every row
+    const int rs = run_head(HeadKind::LowRank, h, A, B, false, shape, k_route, route_ids, route_lp, workspace, router, stream);
+    if (rs != SLIMSPEC_OK) return rs;
+    const hipError_t e = launch_routed_exact(static_cast<const uint16_t *>(h), W, w_dtype == SLIMSPEC_F32, route_ids, part,
+                                             shape->rows, shape->d, shape->V, k_route, k, out_ids, out_logprobs,
+                                             static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SLIMSPEC_OK : fail_hip(e);
+}
+
 int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,
                                  const void *B, const slimspec_shape *shape, int32_t k,
                                  int32_t *out_ids, float *out_logprobs,

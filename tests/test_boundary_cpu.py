@@ -185,3 +185,22 @@ def test_positions_argument_validation(lib):
     assert call(3, [0, 6, 4, 8]) == b.STATUS_INVALID_ARGUMENT         # decreasing
     assert call(2, [0, 4, 8], k=0) == b.STATUS_INVALID_ARGUMENT
     assert call(2, [0, 4, 8], wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
+
+
+def test_routed_head_argument_validation(lib):
+    l, b = lib
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    good = b.SlimspecShape(1, 4096, 512, 128256)
+
+    def call(shape, k_route, k, W=fake, dtype=0, wsb=1 << 40):
+        return l.routed_head_topk(fake, fake, fake, W, dtype, ctypes.byref(shape), k_route, k, fake, fake, fake, wsb, None)
+
+    need = l.routed_workspace_bytes(ctypes.byref(good), 64)
+    assert need > b.slimspec_workspace_bytes(1, 4096, 512, 128256, 64) > 0
+    assert l.routed_workspace_bytes(ctypes.byref(good), 65) == 0
+    assert call(good, 64, 65) == b.STATUS_INVALID_ARGUMENT            # k > k_route
+    assert call(good, 64, 0) == b.STATUS_INVALID_ARGUMENT
+    assert call(good, 65, 10) == b.STATUS_UNSUPPORTED                 # k_route > KMAX
+    assert call(good, 64, 10, W=null) == b.STATUS_INVALID_ARGUMENT
+    assert call(good, 64, 10, dtype=3) == b.STATUS_INVALID_ARGUMENT
+    assert call(good, 64, 10, wsb=need - 1) == b.STATUS_WORKSPACE_TOO_SMALL

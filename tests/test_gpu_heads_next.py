@@ -198,3 +198,32 @@ def test_config4_sample(gpu, oracle_mod):
     n_other = check_sample_outputs(torch, out, ora, 12345, cfg.V, ora.z, oracle_mod)
     print(f"C4 sampling: {n_other} of {cfg.rows} rows drew another id within the tolerance", flush=True)
     assert n_other <= 2
+
+
+# ------------------------------------------------------------------ router-then-exact head
+
+@pytest.mark.parametrize("rows,d,r,V,k_route,k,w_f32", [
+    (1, 256, 32, 8200, 32, 8, False), (1, 4096, 512, 20000, 64, 10, False), (3, 128, 16, 5000, 16, 16, True),
+    (9, 96, 24, 2056, 12, 5, False), (20, 136, 32, 3080, 40, 7, False),
+])
+def test_routed_head(gpu, oracle_mod, rows, d, r, V, k_route, k, w_f32):
+    torch, b = gpu
+    print(f"routed head rows={rows} d={d} r={r} V={V} k_route={k_route} k={k} f32={w_f32}", flush=True)
+    x = synth.make_inputs(synth.small_config(rows, d, r, V, k, peaked_every=4), seed=400 + rows, with_full_head=True)
+    # a full head that agrees with the router on the whole but not in detail (as a trained router would)
+    zr = synth.bf16_bits_to_f64(x.A) @ synth.bf16_bits_to_f64(x.B)
+    W = synth.f32_to_bf16_bits((zr + 0.3 * synth.bf16_bits_to_f64(x.W)).astype(np.float32))
+    Wh = synth.bf16_bits_to_f32(W) if w_f32 else W
+    ids, lp = b.routed_head_topk(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B),
+                                 to_dev_f32(Wh) if w_f32 else to_dev_bf16(Wh), k_route, k)
+    torch.cuda.synchronize()
+    ids, lp = ids.cpu().numpy(), lp.cpu().numpy()
+    o_ids, o_lp, o_lse, o_route = oracle_mod.routed_head_topk(x.h, x.A, x.B, Wh, k_route, k)
+    # The routed subset itself is a top-k of the router and may differ from the checker's at near-ties of the router's
+    # k_route-th place; the comparison below therefore runs over the checker's exact logits of whatever was returned.
+    y_at = lambda ri, ci: oracle_mod.full_logits_at(x.h, Wh, ri, ci)
+    router = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, k_route, return_logits=True)
+    for i in range(rows):
+        kth = router.z[i, router.ids[i, -1]]
+        assert np.all(router.z[i, ids[i]] >= kth - 1e-3), "an id the router would not have kept"
+    compare_with_oracle(ids, lp, o_ids, o_lse, y_at, V)
