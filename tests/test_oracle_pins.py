@@ -305,3 +305,16 @@ def test_cost_ratio_identity():
     e = g["paper_eq4_case"]
     gain = e["rho_tau"] * (1 + e["kappa"]) / (1 + e["nu"] * e["kappa"])
     assert abs(gain - e["printed_gain"]) < 0.02
+
+
+def test_full_logits_at_fp32_weights_equal_the_full_rows(oracle_mod):
+    """The pairwise evaluator's fp32-weight branch (the z_at of the fp32 GPU tests) against the pinned full-row head."""
+    cfg = synth.small_config(rows=4, d=40, r=8, V=96, k=5)
+    x = synth.make_inputs(cfg, seed=17, with_full_head=True)
+    W = synth.bf16_bits_to_f32(x.W) * np.float32(1.0009765625)           # not representable in bf16 any more
+    full = oracle_mod.full_head_topk(x.h, W, 5, return_logits=True)
+    ri, ci = np.meshgrid(np.arange(4), np.arange(96), indexing="ij")
+    z = oracle_mod.full_logits_at(x.h, W, ri.ravel(), ci.ravel()).reshape(4, 96)
+    assert np.array_equal(z, full.z)
+    ref = synth.bf16_bits_to_f64(x.h) @ W.astype(np.float64)
+    assert np.allclose(z, ref, rtol=0, atol=1e-12)
