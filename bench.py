@@ -9,7 +9,7 @@ the single-row latency shape d=4096, r=512, V=128256, k=10 (C2); the other workl
 a warm-cache run, six calls in one HIP graph) are reported in the "extra" object of the same
 JSON line, each with its own roofline entry.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C5] [--quick]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C5] [--head low_rank|full] [--quick]
 
 Prints exactly one JSON line on stdout (progress goes to stderr).
 """
@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--copies", type=int, default=4,
                     help="distinct device copies of the weights rotated between steps so that every step "
                          "streams them from HBM rather than from the 256 MB last-level cache")
+    ap.add_argument("--head", default="low_rank", choices=("low_rank", "full"),
+                    help="full: time full_head_topk on the workload's shape instead (a profiling aid: the comparator "
+                         "alone in the run; implies --quick)")
     ap.add_argument("--quick", action="store_true", help="skip the extra workloads and the CPU baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra workloads only")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -256,8 +259,21 @@ def main():
     x = synth.make_inputs(cfg, seed=0)
     copies = max(1, args.copies)
     null_ms = null_event_pair_ms()
-    log(f"[bench] timing low-rank head: {args.warmup} warm-up + {args.steps} steps, {copies} weight copies")
-    dt, kern_ms, call_us = time_low_rank(cfg, x, args.steps, args.warmup, copies)
+    full_only = args.head == "full"
+    if full_only:
+        args.quick = True
+        log(f"[bench] timing the FULL head on this shape: {args.warmup} warm-up + {args.steps} steps, {copies} weight copies")
+        gw_ = torch.Generator(device=dev)
+        gw_.manual_seed(1)
+        W0 = torch.empty((cfg.d, cfg.V), device=dev, dtype=torch.bfloat16)
+        for j0 in range(0, cfg.d, 256):
+            W0[j0:j0 + 256] = (torch.randn((min(256, cfg.d - j0), cfg.V), generator=gw_, device=dev) * cfg.d ** -0.5).to(torch.bfloat16)
+        dt, kern_ms, call_us = time_full_tensors(upload(x.h), [W0] + [W0.clone() for _ in range(copies - 1)], cfg.k,
+                                                 args.steps, args.warmup)
+        del W0
+    else:
+        log(f"[bench] timing low-rank head: {args.warmup} warm-up + {args.steps} steps, {copies} weight copies")
+        dt, kern_ms, call_us = time_low_rank(cfg, x, args.steps, args.warmup, copies)
     ms_per_step = dt / args.steps * 1e3
     rows_per_s = cfg.rows * args.steps / dt
     log(f"[bench] {ms_per_step * 1e3:.2f} us/call, {rows_per_s:.1f} rows/s, projection kernel {kern_ms * 1e3:.2f} us "
@@ -273,11 +289,13 @@ def main():
         "dtype": "bf16 weights and hidden states, fp32 accumulate",
         "data": "synthetic (seeded host generator for the headline workload; the extra workloads draw the same "
                 "distributions on the device)",
-        "config": {"workload": f"{cfg.name}: low-rank head rows={cfg.rows} d={cfg.d} r={cfg.r} V={cfg.V} k={cfg.k}, "
+        "config": {"workload": f"{cfg.name}: {'FULL head (comparator, not the headline metric)' if full_only else 'low-rank head'} "
+                               f"rows={cfg.rows} d={cfg.d} r={cfg.r} V={cfg.V} k={cfg.k}, "
                                f"{copies} rotating weight copies (cold last-level cache)",
                    "rows": cfg.rows, "d": cfg.d, "r": cfg.r, "V": cfg.V, "k": cfg.k},
-        "roofline": roofline_of(cfg.name, cfg.rows, cfg.r, cfg.V, kern_ms, null_ms),
-        "call_hbm_frac": algorithmic_bytes_low_rank(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k)
+        "roofline": roofline_of(cfg.name + ("_full" if full_only else ""), cfg.rows, cfg.d if full_only else cfg.r, cfg.V,
+                                kern_ms, null_ms),
+        "call_hbm_frac": (2.0 * cfg.d * cfg.V if full_only else algorithmic_bytes_low_rank(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k))
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_sources_sha256": kernel_sources_digest(),
     }
