@@ -94,6 +94,55 @@ __device__ __forceinline__ void rank_all_pairs(const uint64_t *keys, int n, int 
     }
 }
 
+// Sum of v over every aligned group of P adjacent lanes (P a power of two, at most 64; the same in all lanes of the
+// group).  All lanes of the wavefront must be active at the call.
+__device__ __forceinline__ int lanes_sum(int v, int P) {
+    if (P > 1) v += (int)dpp_u32<0xB1>((uint32_t)v);
+    if (P > 2) v += (int)dpp_u32<0x4E>((uint32_t)v);
+    if (P > 4) v += (int)dpp_u32<0x141>((uint32_t)v);
+    if (P > 8) v += (int)dpp_u32<0x140>((uint32_t)v);
+    uint32_t a, b;
+    if (P > 16) { swap_pair<16>((uint32_t)v, a, b); v = (int)(a + b); }
+    if (P > 32) { swap_pair<32>((uint32_t)v, a, b); v = (int)(a + b); }
+    return v;
+}
+// Lanes that share the scan for one of n items when nthreads threads work on them: the largest power of two P with
+// n P <= nthreads (1 when there are more items than threads); returns log2 P.
+__device__ __forceinline__ int lanes_per_item_log2(int n, int nthreads) {
+    int p = 0;
+    while (p < 6 && (2 * n << p) <= nthreads) ++p;
+    return p;
+}
+// rank_all_pairs with the scan for every key shared by P adjacent lanes (few keys, many threads: the ranking is a
+// chain of shared-memory reads, and P lanes make it P times shorter).  Every thread of the block must call it.
+template <class F>
+__device__ __forceinline__ void rank_all_pairs_wide(const uint64_t *keys, int n, int tid, int nthreads, F f) {
+    const int p = lanes_per_item_log2(n, nthreads), P = 1 << p;
+    if (p == 0) { rank_all_pairs(keys, n, tid, nthreads, f); return; }
+    const int c = tid >> p, part = tid & (P - 1);
+    const uint64_t mine = (c < n) ? keys[c] : kNoKey;
+    int rank = 0;
+    if (c < n) {
+#pragma unroll 4
+        for (int q = part; q < n; q += P) rank += (keys[q] > mine) ? 1 : 0;
+    }
+    rank = lanes_sum(rank, P);
+    if (c < n && part == 0) f(c, mine, rank);
+}
+
+// This lane's share (one of PH lanes) of the rank of `mine` among the 64 stream heads of its group
+template <int PH>
+__device__ __forceinline__ int head_rank_share(const uint64_t *group, int part, uint64_t mine) {
+    const uint4 *grp = reinterpret_cast<const uint4 *>(group);      // 64 keys, two per 16-byte read
+    int rank = 0;
+#pragma unroll
+    for (int q = 0; q < 32 / PH; ++q) {
+        const uint4 v = grp[part + q * PH];
+        rank += (u64_from(v.y, v.x) > mine ? 1 : 0) + (u64_from(v.w, v.z) > mine ? 1 : 0);
+    }
+    return rank;
+}
+
 }  // namespace
 
 // so.on (sampling calls): the records have rec_stride = kStreamRecSample floats and also carry every stream's best
@@ -175,7 +224,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         for (int c = tid; c < n_work; c += NT) work[c] = make_key(w_val[c], (uint32_t)w_id[c]);
         __syncthreads();
         float *by_rank = reinterpret_cast<float *>(w_need);
-        rank_all_pairs(work, n_work, tid, NT, [&](int c, uint64_t, int rank) {
+        rank_all_pairs_wide(work, n_work, tid, NT, [&](int c, uint64_t, int rank) {
             if (rank < k) winners[rank] = (uint32_t)c;
             by_rank[rank] = w_apx[c];
         });
@@ -308,6 +357,19 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     // a stream record as three 16-byte loads; the thread's first stream stays in registers
     static_assert(REC == 12, "three float4 per record");
     typedef float f32x4 __attribute__((ext_vector_type(4)));      // native vectors stay in registers (a float4 array did not)
+    // Every global load of the prologue is issued before the first of them is used (one trip to the memory side
+    // instead of three): the first element(s) of the contraction input, of the column scales and of the rounding
+    // statistics, then the thread's stream record.
+    const float x_first = (tid < K) ? x_at(ctx, tid) : 0.f;
+    float2 ts_first0 = make_float2(0.f, 0.f), ts_first1 = make_float2(0.f, 0.f);
+    if (tilescale != nullptr) {
+        if (tid < n_vt) ts_first0 = tilescale[tid];
+        if (tid + NT < n_vt) ts_first1 = tilescale[tid + NT];
+    }
+    // squared norm of t - rounded t: lane q of the first wavefront adds the row's entries q, q + 64, ... in order
+    float dt2_mine = 0.f;
+    if (stat != nullptr && tid < 64)
+        for (int q = tid; q < n_stat; q += 64) dt2_mine += stat[(size_t)q * rows_pad + row].x;
     const f32x4 *mine_src = reinterpret_cast<const f32x4 *>(rec + (size_t)min(tid, nsr - 1) * rec_stride);
     const f32x4 mine0 = mine_src[0], mine1 = mine_src[1], mine2 = mine_src[2];
     auto load_rec = [&](int sidx, float (&f)[REC]) {
@@ -332,20 +394,23 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             m_t = m_new;
         }
     }
-    for (int j = tid; j < K; j += NT) { const float v = x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
-    __shared__ float stat_sh[64];
+    for (int j = tid; j < K; j += NT) { const float v = (j == tid) ? x_first : x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
+    __shared__ float dt2_sh;
     // Column scale of B per vocabulary tile (asked for early: by the time eps needs it, it has arrived): the largest
     // column rms of the tile, and the rms of all of B from the tiles' mean squares (added in a fixed order).
     float ts_max = 0.f, ts_msq = 0.f;
     if (tilescale != nullptr)
         for (int i = tid; i < n_vt; i += NT) {
-            const float2 v = tilescale[i];
+            const float2 v = (i < NT) ? ts_first0 : (i < 2 * NT) ? ts_first1 : tilescale[i];
             if (ts_cached) ts[i] = v.x;
             ts_max = fmaxf(ts_max, v.x);
             ts_msq += v.y;
         }
     __shared__ float red_ts[NWAVES], red_tq[NWAVES];
-    if (stat != nullptr && tid < n_stat && tid < 64) stat_sh[tid] = stat[(size_t)tid * rows_pad + row].x;
+    if (wave == 0) {                                          // (fixed order: the lanes' sums, then the DPP tree)
+        const float dt2_w = wave_sum(dt2_mine);
+        if (lane == 0) dt2_sh = dt2_w;
+    }
     const float m_w = wave_max(m_t);
     float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
     s_w = wave_sum(s_w);
@@ -407,17 +472,19 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     // ---- tau: the k-th largest listed maximum.  The lists are sorted, so first T = the k-th largest of the
     // streams' heads (best k of every 64 heads, then all pairs); every listed maximum >= T (at most 3 k of them,
     // all of them if there are fewer than k heads) is a candidate, and tau is the k-th largest candidate.
-    for (int e = tid; e < nsr; e += NT) {
-        const uint64_t mine = hkeys[e];
-        if (mine == kNoKey) continue;
-        const uint4 *grp = reinterpret_cast<const uint4 *>(hkeys + (e & ~63));      // 64 keys, two per 16-byte read
+    // (with few streams, PH = 2 or 4 lanes share the 64 comparisons of one head)
+    const int ph = (4 * ngroups * 64 <= NT) ? 2 : (2 * ngroups * 64 <= NT) ? 1 : 0, PH = 1 << ph;
+    for (int e0 = 0; e0 < ngroups * 64; e0 += NT >> ph) {
+        const int e = e0 + (tid >> ph), part = tid & (PH - 1);
+        const uint64_t mine = (e < ngroups * 64) ? hkeys[e] : kNoKey;
         int rank = 0;
-#pragma unroll
-        for (int q = 0; q < 32; ++q) {
-            const uint4 v = grp[q];
-            rank += (u64_from(v.y, v.x) > mine ? 1 : 0) + (u64_from(v.w, v.z) > mine ? 1 : 0);
+        if (mine != kNoKey) {
+            const uint64_t *group = hkeys + (e & ~63);
+            rank = (ph == 2) ? head_rank_share<4>(group, part, mine)
+                 : (ph == 1) ? head_rank_share<2>(group, part, mine) : head_rank_share<1>(group, part, mine);
         }
-        if (rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
+        rank = lanes_sum(rank, PH);
+        if (mine != kNoKey && part == 0 && rank < k) surv[atomicAdd(&cnt_surv, 1u)] = mine;
     }
     __syncthreads();
     const int n_surv = (int)cnt_surv;
@@ -425,7 +492,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __shared__ uint32_t cnt_cand;
     if (tid == 0) { head_bound = kNoKey; cnt_cand = 0u; }
     __syncthreads();
-    rank_all_pairs(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) head_bound = key; });
+    rank_all_pairs_wide(surv, n_surv, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) head_bound = key; });
     __syncthreads();
     const uint64_t T = head_bound;                                       // kNoKey (smallest): fewer than k heads
     __syncthreads();                                                     // surv is reused below
@@ -434,7 +501,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         if (mine != kNoKey && mine >= T) surv[atomicAdd(&cnt_cand, 1u)] = mine;
     }
     __syncthreads();
-    rank_all_pairs(surv, (int)cnt_cand, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
+    rank_all_pairs_wide(surv, (int)cnt_cand, tid, NT, [&](int, uint64_t key, int rank) { if (rank == k - 1) tau_key = key; });
     __syncthreads();
     const bool have_tau = tau_key != kNoKey;
     const float tau = have_tau ? key_value(tau_key) : kNegInf;
@@ -444,9 +511,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     // zero (magnitude below tiny_w, times the 1-norm of the contraction input).
     float dt_scale = 0.f, eps_abs;
     if (stat != nullptr) {
-        float dt2 = 0.f;                                     // squared norm of t - rounded t, summed in a fixed order
-        for (int q = 0; q < n_stat; ++q) dt2 += (q < 64) ? stat_sh[q] : stat[(size_t)q * rows_pad + row].x;
-        dt_scale = kEpsSigmas * sqrtf(dt2);
+        dt_scale = kEpsSigmas * sqrtf(dt2_sh);
         eps_abs = fabsf(tau) * 1.2e-5f + tiny_w * X1 + 1e-30f;
     }
     else eps_abs = fabsf(tau) * 1.6e-5f + 1e-6f;
@@ -568,14 +633,24 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     if (!exhaustive) {
         // ---- which listed maxima need the exact value
         const bool any_hidden = cnt_hidden != 0u;
-        for (int c = tid; c < n_work; c += NT) {
-            if (w_need[c]) continue;
-            // a computed value may be off by its eps_v: beyond kExactWinnersEps a log-probability takes the exact value
-            const float mine = w_val[c], e_mine = w_eps[c];
-            bool need = any_hidden || e_mine > kExactWinnersEps;
-            for (int q = 0; q < n_work && !need; ++q)
-                if (q != c && fabsf(w_val[q] - mine) <= w_eps[q] + e_mine) need = true;
-            if (need) w_need[c] = 2;                      // 2: decided in this pass (w_val still the computed value)
+        // (PN lanes share the scan of one item: the collected set is a dozen items, the block 512 threads)
+        const int pn = lanes_per_item_log2(n_work, NT), PN = 1 << pn;
+        for (int c0 = 0; c0 < n_work; c0 += NT >> pn) {
+            const int c = c0 + (tid >> pn), part = tid & (PN - 1);
+            const bool open = c < n_work && w_need[c] == 0;
+            int need = 0;
+            if (open) {
+                // a computed value may be off by its eps_v: beyond kExactWinnersEps a log-probability takes the exact value
+                const float mine = w_val[c], e_mine = w_eps[c];
+                if (any_hidden || e_mine > kExactWinnersEps) need = 1;
+                else {
+#pragma unroll 4
+                    for (int q = part; q < n_work; q += PN)
+                        need |= (q != c && fabsf(w_val[q] - mine) <= w_eps[q] + e_mine) ? 1 : 0;
+                }
+            }
+            need = lanes_sum(need, PN);
+            if (open && part == 0 && need) w_need[c] = 2;    // 2: decided in this pass (w_val still the computed value)
         }
         __syncthreads();
         // list the items to evaluate (any order: every result goes back to its own slot)
