@@ -227,3 +227,63 @@ def test_routed_head(gpu, oracle_mod, rows, d, r, V, k_route, k, w_f32):
         kth = router.z[i, router.ids[i, -1]]
         assert np.all(router.z[i, ids[i]] >= kth - 1e-3), "an id the router would not have kept"
     compare_with_oracle(ids, lp, o_ids, o_lse, y_at, V)
+
+
+# ------------------------------------------------------------------ the same heads at the sizes bench.py times
+
+def test_truncated_and_routed_heads_at_the_single_row_workload(gpu, oracle_mod):
+    """d = 4096, V = 128256, one row (the latency workload's shape): the truncated head on 65536 and 16384 kept
+    columns in an arbitrary order, and the routed head with 64 routed ids, both against the checker."""
+    torch, b = gpu
+    cfg = synth.CONFIGS["C2"]
+    x = synth.make_inputs(cfg, seed=3, with_full_head=True)
+    h = to_dev_bf16(x.h)
+    for v_tr in (65536, 16384):
+        print(f"truncated head at d={cfg.d} V_tr={v_tr}", flush=True)
+        id_map = np.random.default_rng(v_tr).permutation(cfg.V)[:v_tr].astype(np.int32)
+        W_tr = np.ascontiguousarray(x.W[:, id_map])
+        ids, lp = b.truncated_head_topk(h, to_dev_bf16(W_tr), torch.from_numpy(id_map).cuda(), cfg.k)
+        torch.cuda.synchronize()
+        ora = oracle_mod.truncated_head_topk(x.h, W_tr, id_map, cfg.k)
+        col_of = np.full(cfg.V, -1, np.int64)
+        col_of[id_map] = np.arange(v_tr)
+        ids = ids.cpu().numpy()
+        assert (col_of[ids] >= 0).all(), "an id outside the kept subset"
+        z_at = lambda ri, ci: oracle_mod.full_logits_at(x.h, W_tr, ri, ci)
+        compare_with_oracle(col_of[ids].astype(np.int32), lp.cpu().numpy(), col_of[ora.ids].astype(np.int32), ora.lse, z_at, v_tr)
+        del W_tr
+    print("routed head at the same shape, k_route = 64", flush=True)
+    k_route = 64
+    ids, lp = b.routed_head_topk(h, to_dev_bf16(x.A), to_dev_bf16(x.B), to_dev_bf16(x.W), k_route, cfg.k)
+    torch.cuda.synchronize()
+    ids, lp = ids.cpu().numpy(), lp.cpu().numpy()
+    o_ids, o_lp, o_lse, o_route = oracle_mod.routed_head_topk(x.h, x.A, x.B, x.W, k_route, cfg.k)
+    router = oracle_mod.slimspec_head_topk(x.h, x.A, x.B, k_route, return_logits=True)
+    kth = router.z[0, router.ids[0, -1]]
+    assert np.all(router.z[0, ids[0]] >= kth - 1e-3), "an id the router would not have kept"
+    y_at = lambda ri, ci: oracle_mod.full_logits_at(x.h, x.W, ri, ci)
+    compare_with_oracle(ids, lp, o_ids, o_lse, y_at, cfg.V)
+
+
+def test_positions_at_the_512_row_workload(gpu, oracle_mod):
+    """512 rows, d = 4096, r = 512, V = 128256 (the throughput workload's shape) as six drafted positions with a
+    down-projection each: the checker runs on the first and last row of every position and on every 8th row."""
+    torch, b = gpu
+    cfg = synth.CONFIGS["C4"]
+    x = synth.make_inputs(cfg, seed=2)
+    sizes = (86, 86, 85, 85, 85, 85)
+    n_pos = len(sizes)
+    rng = np.random.default_rng(6)
+    stack = np.stack([x.A] + [synth.f32_to_bf16_bits((rng.standard_normal((cfg.d, cfg.r)) * cfg.d ** -0.5).astype(np.float32))
+                              for _ in range(n_pos - 1)])
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    print(f"positions at rows={cfg.rows} d={cfg.d} r={cfg.r} V={cfg.V}, sizes {sizes}", flush=True)
+    ids, lp = b.slimspec_head_topk_positions(to_dev_bf16(x.h), to_dev_bf16(stack.reshape(n_pos * cfg.d, cfg.r)).view(n_pos, cfg.d, cfg.r),
+                                             off.tolist(), to_dev_bf16(x.B), cfg.k)
+    torch.cuda.synchronize()
+    ids, lp = ids.cpu().numpy(), lp.cpu().numpy()
+    for p in range(n_pos):
+        sub = sorted(set([int(off[p]), int(off[p + 1]) - 1]) | set(range(int(off[p]) + (-int(off[p])) % 8, int(off[p + 1]), 8)))
+        ora = oracle_mod.slimspec_head_topk(np.ascontiguousarray(x.h[sub]), stack[p], x.B, cfg.k, return_logits=True)
+        z_at = lambda ri, ci: ora.z[ri, ci]
+        compare_with_oracle(ids[sub], lp[sub], ora.ids, ora.lse, z_at, cfg.V)
