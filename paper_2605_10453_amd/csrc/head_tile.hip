@@ -368,7 +368,12 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
                     // the first tile's reference is its own maximum (-1e30 and an empty sum if every column was
                     // masked: the vocabulary's last tile); later tiles move the reference up when they exceed it
                     const float mc_new = first ? ref : vmax(ref, tile_max);
-                    if (!first) st[rt].s *= __builtin_amdgcn_exp2f(NAT ? (ref - mc_new) * kLog2e : ref - mc_new);
+                    // (in two halves: one logit 127 binary orders above the old reference leaves s near the top of the
+                    // float range and the whole factor below its bottom, where the hardware exponential has no value)
+                    if (!first) {
+                        const float half_step = __builtin_amdgcn_exp2f(0.5f * (NAT ? (ref - mc_new) * kLog2e : ref - mc_new));
+                        st[rt].s = (st[rt].s * half_step) * half_step;
+                    }
                     st[rt].mc = mc_new;
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj)

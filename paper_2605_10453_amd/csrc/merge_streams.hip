@@ -33,6 +33,14 @@ static_assert(kMergeThreads * 4 <= kWorkCap, "a step of the exhaustive pass appe
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
 constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
 constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes the exhaustive exact pass
+// The streams' sum of exponentials is made of computed logits; the merge replaces the terms of the logits it
+// re-evaluates, so what remains of its error is the probability-weighted mean error of all the others.  With a wide
+// bound (eps above kWideEps) the row's probable tokens are therefore collected and re-evaluated as well, winners or
+// not: every listed maximum of probability >= kMassCut / eps.  If the tokens left over still hold so much mass that
+// errors of one sign at the bound would move the log-sum-exp by more than kLseGuard, the row is done exhaustively.
+constexpr float kWideEps = 1.2e-2f;
+constexpr float kMassCut = 2.0e-4f;
+constexpr float kLseGuard = 2.5e-2f;
 constexpr int kListedBit = 1 << 30;
 constexpr int kSampleBit = 1 << 29;     // ... an entry of the sampling contenders' list (smp_id / smp_z) instead     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
 constexpr float kEpsSigmas = 4.0f;      // eps_v = this many standard deviations of the rounding error of t in column v
@@ -176,6 +184,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __shared__ uint64_t tau_key;
     __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden, cnt_need;
     __shared__ int tau_slot, eps_violated;
+    __shared__ float mass_eval_sh;
     __shared__ uint64_t smp_wkey[NWAVES];                               // sampling: per-wavefront reductions
     __shared__ float smp_wz[NWAVES], smp_w2[NWAVES], lse_out_sh;
     __shared__ int smp_id[kSampleCap];
@@ -578,6 +587,9 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         const int pos = 8 * (i >> 2) + 4 * half + (i & 3);
         return (tag >> 3) * 256 + 32 * (tag & 7) + pos;
     };
+    const bool wide = eps > kWideEps;
+    // computed logits from here on belong to tokens of probability >= kMassCut / eps
+    const float v_mass = wide ? lse + __builtin_amdgcn_logf(kMassCut / eps) * kLn2 : __builtin_huge_valf();
     if (!exhaustive) {
         for (int sidx = tid; sidx < nsr; sidx += NT) {
             float r[REC];
@@ -590,13 +602,17 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 // the tag's lowest bit names the half-wavefront that held the group
                 const int half = rawtag & 1, tag = rawtag >> 1;
                 listed[l] = (x > kNoValue) ? rawtag : -1;
-                if (!(x > kNoValue) || !(mask4(x) * unit >= theta)) continue;
+                if (!(x > kNoValue) || !(mask4(x) * unit >= fminf(theta, v_mass))) continue;
                 const int imax = (int)(__float_as_uint(x) & 15u);
                 const int id_max = id_of(tag, imax, half);
                 if ((unsigned)id_max >= (unsigned)V) continue;      // cannot come from the head kernel: keeps the gathers in bounds whatever the records hold
                 // its own tile's bound decides (theta was the bound of the widest tile)
                 const float e_item = eps_of_tile(tag >> 3);
-                if (!(mask4(x) * unit >= tau - eps - e_item)) continue;
+                if (!(mask4(x) * unit >= tau - eps - e_item)) {
+                    // not a candidate for the top-k; collected all the same where the log-sum-exp needs its exact value
+                    if (mask4(x) * unit >= v_mass && e_item > kExactWinnersEps) push(id_max, mask4(x) * unit, 0, e_item);
+                    continue;
+                }
                 const uint32_t slot = push(id_max, mask4(x) * unit, 0, e_item);
                 if (keys[sidx * L + l] == tau_key) tau_slot = (int)slot;      // one writer: keys are unique
                 if (y > kNoValue && mask4(y) * unit >= tau - eps - e_item) {
@@ -653,6 +669,20 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             if (open && part == 0 && need) w_need[c] = 2;    // 2: decided in this pass (w_val still the computed value)
         }
         __syncthreads();
+        if (wide) {
+            // probability mass of the listed logits that get their exact value (fixed order: lanes, then the DPP tree)
+            if (wave == 0) {
+                float pm = 0.f;
+                for (int c = lane; c < n_work; c += 64)
+                    if (w_need[c] == 2) pm += __builtin_amdgcn_exp2f((w_val[c] - lse) * kLog2e);
+                pm = wave_sum(pm);
+                if (lane == 0) mass_eval_sh = pm;
+            }
+            __syncthreads();
+            if ((1.f - fminf(mass_eval_sh, 1.f)) * eps > kLseGuard) exhaustive = true;
+        }
+    }
+    if (!exhaustive) {
         // list the items to evaluate (any order: every result goes back to its own slot)
         constexpr int PER = (kWorkCap + NT - 1) / NT;       // fixed trip count: the array stays in registers
         int my_need[PER];

@@ -320,6 +320,34 @@ def test_matrix_core_path_weights_not_gaussian(gpu, oracle_mod, kind, k):
     print(f"{kind} k={k}: {n_exempt} positions used the tie exemption", flush=True)
 
 
+def test_wide_rounding_bound_with_few_winners(gpu, oracle_mod):
+    """Peaked rows (hidden states x 4) over a B whose every 8th row is 6 times larger, k = 2: the rounding errors of
+    the few coordinates that carry the logits then share a sign by chance in some rows, the computed logits of the
+    row's probable tokens are all off the same way, and the log-sum-exp follows them unless those tokens, winners or
+    not, are re-evaluated too (row 33 of this draw: 3.7e-2 before any correction, 2.2e-2 with the two winners exact)."""
+    cfg = synth.small_config(rows=64, d=648, r=192, V=6968, k=2, peaked_every=3)
+    x = synth.make_inputs(cfg, seed=406289933)
+    B = synth.bf16_bits_to_f32(x.B)
+    B[1::8] *= np.float32(6.0)
+    x.B = synth.f32_to_bf16_bits(B)
+    check_low_rank(gpu, oracle_mod, x, cfg.k)
+
+
+def test_logit_far_above_the_running_maximum(gpu, oracle_mod):
+    """One column per row, late in the vocabulary (in a tile that is not the first one its block works on), whose logit is 126 to 130 binary orders above everything the row has
+    seen until then (natural logits 88 ... 92 over a background of 2 ... 5): the running sum of exponentials has to be
+    rescaled by a factor at the very bottom of the float range, or, just beyond it, the row has to be redone exactly."""
+    cfg = synth.small_config(rows=512, d=256, r=144, V=36784, k=5, peaked_every=0)
+    x = synth.make_inputs(cfg, seed=77)
+    t = synth.bf16_bits_to_f64(x.h) @ synth.bf16_bits_to_f64(x.A)
+    B = synth.bf16_bits_to_f32(x.B)
+    for i in range(0, 512, 16):
+        alpha = 88.0 + 0.125 * (i // 16)
+        B[:, 32768 + 7 * i] = (alpha * t[i] / (t[i] @ t[i])).astype(np.float32)
+    x.B = synth.f32_to_bf16_bits(B)
+    check_low_rank(gpu, oracle_mod, x, cfg.k)
+
+
 # ------------------------------------------------------------------ the five workloads at full size
 
 @pytest.mark.parametrize("seed", list(range(10)))
