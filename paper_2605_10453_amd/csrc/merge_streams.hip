@@ -397,7 +397,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         float f[REC];
         load_rec(sidx, f);
         const float mc = f[0], s = f[1];
-        if (s > 0.f) {
+        if (!(s <= 0.f)) {      // (a sum that overflowed in the head kernel is +inf or NaN: it must reach the check of lse below)
             const float m_new = fmaxf(m_t, mc);
             s_t = s_t * __builtin_amdgcn_exp2f(m_t - m_new) + s * __builtin_amdgcn_exp2f(mc - m_new);
             m_t = m_new;

@@ -344,6 +344,11 @@ def test_logit_far_above_the_running_maximum(gpu, oracle_mod):
     for i in range(0, 512, 16):
         alpha = 88.0 + 0.125 * (i // 16)
         B[:, 32768 + 7 * i] = (alpha * t[i] / (t[i] @ t[i])).astype(np.float32)
+    # ... and, in other rows, 170 to 440 binary orders above: the exponential overflows, the stream's sum becomes
+    # infinite and then, rescaled by zero, not a number; such a row must end in the exact pass, not lose the stream
+    for i in range(8, 512, 16):
+        alpha = 120.0 + 6.0 * (i // 16)
+        B[:, 32768 + 7 * i] = (alpha * t[i] / (t[i] @ t[i])).astype(np.float32)
     x.B = synth.f32_to_bf16_bits(B)
     check_low_rank(gpu, oracle_mod, x, cfg.k)
 
