@@ -39,7 +39,7 @@ constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes 
 // not: every listed maximum of probability >= kMassCut / eps.  If the tokens left over still hold so much mass that
 // errors of one sign at the bound would move the log-sum-exp by more than kLseGuard, the row is done exhaustively.
 constexpr float kWideEps = 1.2e-2f;
-constexpr float kMassCut = 2.0e-4f;
+constexpr float kMassCut = 5.0e-4f;
 constexpr float kLseGuard = 2.5e-2f;
 constexpr int kListedBit = 1 << 30;
 constexpr int kSampleBit = 1 << 29;     // ... an entry of the sampling contenders' list (smp_id / smp_z) instead     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
