@@ -287,6 +287,81 @@ def test_side_stream_and_caller_buffers(gpu, oracle_mod):
     assert int((ids == -7).sum()) == ids.numel()
 
 
+def test_two_host_threads_on_two_streams(gpu):
+    """Calls from two host threads, each on a stream and a workspace of its own, overlap freely (the library keeps no
+    state but per thread); every result equals the one the same call gives alone."""
+    import threading
+    torch, b = gpu
+    jobs = []
+    for rows, seed in ((1, 11), (40, 12)):                      # the streaming path and the matrix-core path
+        cfg = synth.small_config(rows=rows, d=512, r=64, V=30000, k=10, peaked_every=7)
+        x = synth.make_inputs(cfg, seed)
+        h, A, B = to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B)
+        ref_ids, ref_lp = b.slimspec_head_topk(h, A, B, cfg.k)
+        torch.cuda.synchronize()
+        jobs.append((cfg, h, A, B, ref_ids.clone(), ref_lp.clone()))
+    errors = []
+
+    def worker(job):
+        cfg, h, A, B, ref_ids, ref_lp = job
+        try:
+            s = torch.cuda.Stream()
+            ws = torch.empty(b.slimspec_workspace_bytes(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k), dtype=torch.uint8, device="cuda")
+            ids = torch.empty((cfg.rows, cfg.k), dtype=torch.int32, device="cuda")
+            lp = torch.empty((cfg.rows, cfg.k), dtype=torch.float32, device="cuda")
+            for it in range(60):
+                ids.fill_(-1)
+                b.slimspec_head_topk(h, A, B, cfg.k, out_ids=ids, out_logprobs=lp, workspace=ws, stream=s)
+                s.synchronize()
+                if not (torch.equal(ids, ref_ids) and torch.equal(lp.view(torch.int32), ref_lp.view(torch.int32))):
+                    errors.append((cfg.rows, it))
+                    return
+        except Exception as exc:                                # reported by the main thread
+            errors.append((cfg.rows, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
+def test_graph_replays_of_the_matrix_core_path(gpu):
+    """Two calls of the many-row path captured in one HIP graph (no allocation, no synchronisation, no memset inside
+    the library): every replay, with other work of the process between them, gives the eager results."""
+    torch, b = gpu
+    cfg = synth.small_config(rows=48, d=512, r=128, V=30000, k=10, peaked_every=5)
+    xs = [synth.make_inputs(cfg, seed) for seed in (21, 22)]
+    dev = [(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B)) for x in xs]
+    outs = [(torch.empty((cfg.rows, cfg.k), dtype=torch.int32, device="cuda"),
+             torch.empty((cfg.rows, cfg.k), dtype=torch.float32, device="cuda")) for _ in xs]
+    ws = torch.empty(b.slimspec_workspace_bytes(cfg.rows, cfg.d, cfg.r, cfg.V, cfg.k), dtype=torch.uint8, device="cuda")
+    eager = []
+    for (h, A, B), (ids, lp) in zip(dev, outs):
+        b.slimspec_head_topk(h, A, B, cfg.k, out_ids=ids, out_logprobs=lp, workspace=ws)
+        torch.cuda.synchronize()
+        eager.append((ids.clone(), lp.clone()))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for (h, A, B), (ids, lp) in zip(dev, outs):
+                b.slimspec_head_topk(h, A, B, cfg.k, out_ids=ids, out_logprobs=lp, workspace=ws)
+    for rep in range(4):
+        for ids, lp in outs:
+            ids.fill_(-1)
+            lp.fill_(0.0)
+        junk = torch.randn(1 << 20, device="cuda").sum()           # the process's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (ids, lp), (e_ids, e_lp) in zip(outs, eager):
+            assert torch.equal(ids, e_ids), rep
+            assert torch.equal(lp.view(torch.int32), e_lp.view(torch.int32)), rep
+        del junk
+
+
 # ------------------------------------------------------------------ weights that are not i.i.d. Gaussian
 
 def _non_gaussian_B(kind, cfg, seed):
