@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include "plan.hpp"
 #include <atomic>
+#include <mutex>
 
 namespace slimspec {
 
@@ -19,10 +20,14 @@ struct LdsLimit {
         if (e != hipSuccess) return e;
         const bool tracked = dev >= 0 && dev < kDevices;
         if (tracked && bytes[dev].load(std::memory_order_acquire) >= need) return hipSuccess;
+        // the limit only ever grows: two host threads that raise it at the same time must not leave the smaller value
+        std::lock_guard<std::mutex> lock(raising);
+        if (tracked && bytes[dev].load(std::memory_order_acquire) >= need) return hipSuccess;
         e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, need);
         if (e == hipSuccess && tracked) bytes[dev].store(need, std::memory_order_release);
         return e;
     }
+    std::mutex raising;
 };
 
 // slices of t = h A (fp32, [nds][R][r] with R = 1, 2, 4 or 8 >= rows_here) for up to kGemvMaxRows rows
