@@ -22,6 +22,19 @@ __device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_fl
 __device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
 __device__ __forceinline__ float fast_log(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
 
+// The 16-bit row operand of the matrix-core head kernel: t log2(e) rounded to bf16 (nearest even) or to f16.  One
+// definition for the kernel that writes the operand and for the merge, which recomputes from it the logit the head
+// kernel saw for a column without a recorded value.
+__device__ __forceinline__ uint32_t operand_bf16_bits(float t) {
+    const uint32_t u = __float_as_uint(t * kLog2e);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ _Float16 operand_f16(float t) { return (_Float16)(t * kLog2e); }
+// ... and the value of t it stands for
+__device__ __forceinline__ float operand_value(float t, bool as_f16) {
+    return (as_f16 ? (float)operand_f16(t) : __uint_as_float(operand_bf16_bits(t) << 16)) * kLn2;
+}
+
 // Order of the outputs: larger logit first, equal logits: smaller id first.
 __device__ __forceinline__ bool ranks_before(float va, int ia, float vb, int ib) {
     return (va > vb) || (va == vb && ia < ib);

@@ -309,8 +309,7 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 // bf16 operand of the head kernel, in base-2 units: t log2(e)
-                const uint32_t u = __float_as_uint(v[e] * kLog2e);
-                hb[e] = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;            // round to nearest even
+                hb[e] = operand_bf16_bits(v[e]);                            // round to nearest even
                 const float dlt = v[e] - __uint_as_float(hb[e] << 16) * kLn2;
                 a += dlt * dlt;
                 b += v[e] * v[e];
@@ -320,7 +319,7 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
             f16x8 hv;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                hv[e] = (_Float16)(v[e] * kLog2e);
+                hv[e] = operand_f16(v[e]);
                 const float dlt = v[e] - (float)hv[e] * kLn2;
                 a += dlt * dlt;
                 b += v[e] * v[e];

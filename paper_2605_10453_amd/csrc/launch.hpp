@@ -97,10 +97,13 @@ hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pa
 // stream partials -> final ids / log-probabilities, with exact fp32 re-evaluation of uncertain ranks
 // nsr records per row (= gw, the number of vocabulary-tile columns of the head kernel's grid); unit: factor from the
 // records' values to natural-log logits; tiny_w: magnitude below which the kernel flushed weights to zero;
+// operand16: 0 the head kernel's row operand was exact, 1 it was t log2(e) rounded to bf16, 2 to f16 (the merge then
+// recomputes, from the same rounding, the logit the head kernel saw for a column that has no recorded value);
 // defer_buf: merge_defer_bytes(rows) of scratch, or null: with it, rows that need exact re-evaluations are finished by
 // two more launches that spread the column gathers over many CUs (worth it for long contractions only)
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
-                                const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
+                                const void *xexact, bool x_is_bf16, int ldx, int operand16,
+                                const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
                                 void *defer_buf, const SampleOut &so, int row_base, hipStream_t st);

@@ -37,12 +37,14 @@ constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes 
 // re-evaluates, so what remains of its error is the probability-weighted mean error of all the others.  With a wide
 // bound (eps above kWideEps) the row's probable tokens are therefore collected and re-evaluated as well, winners or
 // not: every listed maximum of probability >= kMassCut / eps.  If the tokens left over still hold so much mass that
-// errors of one sign at the bound would move the log-sum-exp by more than kLseGuard, the row is done exhaustively.
+// errors of one sign at the bound would move the log-sum-exp by more than kLseGuard, the row is done exhaustively
+// (a guard for bounds close to kExhaustiveEps: the exhaustive pass costs milliseconds per row, and at 2.5e-2 the
+// peaked rows of a 512-row batch at r = 1024, whose real error is a tenth of that, already tripped it).
 constexpr float kWideEps = 1.2e-2f;
 constexpr float kMassCut = 5.0e-4f;
-constexpr float kLseGuard = 2.5e-2f;
-constexpr int kListedBit = 1 << 30;
-constexpr int kSampleBit = 1 << 29;     // ... an entry of the sampling contenders' list (smp_id / smp_z) instead     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
+constexpr float kLseGuard = 1.0e-1f;
+constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
+constexpr int kSampleBit = 1 << 29;     // ... an entry of the sampling contenders' list (smp_id / smp_z) instead
 constexpr float kEpsSigmas = 4.0f;      // eps_v = this many standard deviations of the rounding error of t in column v
                                         // (values are re-evaluated when within eps_a + eps_b = 5.6 sigma of their difference)
 constexpr float kTileMaxBias = 1.35f;   // expected largest / true of 256 column rms estimates from 32 samples each
@@ -159,6 +161,7 @@ __device__ __forceinline__ int head_rank_share(const uint64_t *group, int part, 
 __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const float *__restrict__ part, int rec_stride, int nsr, int gw, int n_vt,
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
+    int operand16,      // 0: the head kernel's row operand was exact; 1: it was t log2(e) rounded to bf16; 2: to f16
     const uint16_t *__restrict__ M, int K, int V,
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float2 *__restrict__ tilescale,
     int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
@@ -180,6 +183,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     float *ts = w_eps + kWorkCap;                                       // [min(n_vt, kTsCap)]  column scale of B per vocabulary tile
     const bool ts_cached = n_vt <= kTsCap;                              // a larger vocabulary uses the largest scale for every tile
     float *xrow = ts + ((min(n_vt, kTsCap) + 3) & ~3);                  // [K]            the row's exact contraction input
+    float *xrow16 = xrow + K;                                           // [K]            ... as the head kernel had it (operand16 != 0)
     __shared__ float red_m[NWAVES], red_s[NWAVES];
     __shared__ uint64_t tau_key;
     __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden, cnt_need;
@@ -251,11 +255,16 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     };
     // A listed maximum had its computed value in the streams' sum of exp: remember by how much its term changes.
     // ... and check it against the bound that decided what to re-evaluate.
-    const auto take_exact = [&](int entry, float z, float Mx) {
+    // A member of a group that is not the listed maximum has no recorded value; z16 is its logit recomputed from the
+    // 16-bit contraction input (what the head kernel added to the sum of exp, up to the order of the additions).
+    const auto take_exact = [&](int entry, float z, float z16, float Mx) {
         const int item = entry & (kListedBit - 1);
         if (entry & kListedBit) {
             if (fabsf(z - w_val[item]) > kEpsViolation * w_eps[item]) eps_violated = 1;
             w_apx[item] = __builtin_amdgcn_exp2f(z * kLog2e - Mx) - __builtin_amdgcn_exp2f(w_val[item] * kLog2e - Mx);
+        } else {
+            if (fabsf(z - z16) > kEpsViolation * w_eps[item]) eps_violated = 1;
+            w_apx[item] = __builtin_amdgcn_exp2f(z * kLog2e - Mx) - __builtin_amdgcn_exp2f(z16 * kLog2e - Mx);
         }
         w_val[item] = z;
     };
@@ -351,7 +360,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             float z = 0.f;
 #pragma unroll
             for (int ks = 0; ks < kDeferSlices; ++ks) z += park_part[ks * kDeferNeed + i];      // fixed order
-            take_exact(park_need[i], z, Mx);
+            take_exact(park_need[i], z, z, Mx);          // (rows with unlisted members on a rounded operand are not parked)
         }
         __syncthreads();
         if (eps_violated) { exhaustive_pass(); return; }
@@ -403,7 +412,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             m_t = m_new;
         }
     }
-    for (int j = tid; j < K; j += NT) { const float v = (j == tid) ? x_first : x_at(ctx, j); xrow[j] = v; x2 += v * v; x1 += fabsf(v); }
+    for (int j = tid; j < K; j += NT) {
+        const float v = (j == tid) ? x_first : x_at(ctx, j);
+        xrow[j] = v; x2 += v * v; x1 += fabsf(v);
+        if (operand16) xrow16[j] = operand_value(v, operand16 == 2);
+    }
     __shared__ float dt2_sh;
     // Column scale of B per vocabulary tile (asked for early: by the time eps needs it, it has arrived): the largest
     // column rms of the tile, and the rms of all of B from the tiles' mean squares (added in a fixed order).
@@ -712,7 +725,9 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             } else if (tid == 0) eps_violated = 1;          // no room (thousands of near-ties): exhaustive pass
             __syncthreads();
         }
-        if (park && cnt_need != 0u && cnt_need <= (uint32_t)kDeferNeed && n_work <= kDeferWork) {
+        // (a row with unlisted members on a bf16 operand stays here: their recomputed 16-bit logits come with the gathers)
+        const bool park_ok = !(operand16 == 1 && cnt_hidden != 0u);
+        if (park && park_ok && cnt_need != 0u && cnt_need <= (uint32_t)kDeferNeed && n_work <= kDeferWork) {
             // park the row: collected set, list of columns, the streams' log-sum-exp
             const int n_need = (int)cnt_need;
             for (int c = tid; c < n_work; c += NT) { park_id[c] = w_id[c]; park_val[c] = w_val[c]; park_eps[c] = w_eps[c]; }
@@ -727,13 +742,17 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         // four wavefronts interleave rows, so one load instruction touches 4 rows of M x 16 columns and the
         // whole block has 16 rows in flight per step; partial sums are combined in a fixed order
         const int n_need = (int)cnt_need;
-        __shared__ float red_ex[NWAVES][16];
+        __shared__ float red_ex[NWAVES][16], red_ex16[NWAVES][16];
+        const bool with16 = operand16 != 0;
         for (int g0 = 0; g0 < n_need; g0 += 16) {
             const int u = lane & 15, jsub = lane >> 4;
             const int entry = w_need[min(g0 + u, n_need - 1)];
             const int item = entry & (kSampleBit - 1);
             const int id = (entry & kSampleBit) ? smp_id[item] : w_id[item];
-            float acc = 0.f;
+            // (the second sum only in a batch that holds a column without a recorded value: every wavefront sees the same
+            // 16 entries, so all of them decide alike)
+            const bool batch16 = with16 && __ballot((entry & (kListedBit | kSampleBit)) == 0) != 0ull;
+            float acc = 0.f, acc16 = 0.f;
             // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 16 independent loads per lane (K = 512: one round trip)
             const uint16_t *mcol = M + id;
             constexpr int RSTEP = 4 * NWAVES, NLD = 16;
@@ -746,20 +765,33 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                     const int j = j0 + e * RSTEP;
                     acc = fmaf(j < K ? xrow[j] : 0.f, bf16_to_float(w[e]), acc);
                 }
+                if (batch16) {                              // (a pass of its own: the common path stays as it was)
+#pragma unroll
+                    for (int e = 0; e < NLD; ++e) {
+                        const int j = j0 + e * RSTEP;
+                        acc16 = fmaf(j < K ? xrow16[j] : 0.f, bf16_to_float(w[e]), acc16);
+                    }
+                }
             }
             uint32_t a, b;
             swap_pair<16>(__float_as_uint(acc), a, b);
             acc = __uint_as_float(a) + __uint_as_float(b);
             swap_pair<32>(__float_as_uint(acc), a, b);
             acc = __uint_as_float(a) + __uint_as_float(b);
-            if (lane < 16) red_ex[wave][lane] = acc;
+            if (batch16) {
+                swap_pair<16>(__float_as_uint(acc16), a, b);
+                acc16 = __uint_as_float(a) + __uint_as_float(b);
+                swap_pair<32>(__float_as_uint(acc16), a, b);
+                acc16 = __uint_as_float(a) + __uint_as_float(b);
+            }
+            if (lane < 16) { red_ex[wave][lane] = acc; red_ex16[wave][lane] = acc16; }
             __syncthreads();
             if (tid < 16 && g0 + tid < n_need) {
-                float z = red_ex[0][tid];
+                float z = red_ex[0][tid], z16 = red_ex16[0][tid];
 #pragma unroll
-                for (int w = 1; w < NWAVES; ++w) z += red_ex[w][tid];
+                for (int w = 1; w < NWAVES; ++w) { z += red_ex[w][tid]; z16 += red_ex16[w][tid]; }
                 if (entry & kSampleBit) smp_z[item] = z;
-                else take_exact(entry, z, Mx);            // tid < 16: u == tid, so `entry` is this column's
+                else take_exact(entry, z, batch16 ? z16 : z, Mx);     // tid < 16: u == tid, so `entry` is this column's
             }
             __syncthreads();
         }
@@ -847,26 +879,27 @@ size_t merge_streams_lds_bytes(int nsr, int k, int n_vt) {
 }
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
-                                const void *xexact, bool x_is_bf16, int ldx, const uint16_t *M, int K, int V,
+                                const void *xexact, bool x_is_bf16, int ldx, int operand16,
+                                const uint16_t *M, int K, int V,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
                                 void *defer_buf, const SampleOut &so, int row_base, hipStream_t st)
 {
-    const size_t lds = merge_streams_lds_bytes(nsr, k, n_vt) + sizeof(float) * (size_t)K;      // + the row's contraction input
+    const size_t lds = merge_streams_lds_bytes(nsr, k, n_vt) + 2 * sizeof(float) * (size_t)K;   // + the row's contraction input, exact and as rounded
     static LdsLimit lds_limit;
     hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(merge_streams_kernel), (int)lds);
     if (e != hipSuccess) return e;
     int *defer = so.on ? nullptr : static_cast<int *>(defer_buf);      // sampling calls evaluate in place
     const int rec_stride = so.on ? kStreamRecSample : kStreamRec;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, rec_stride, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
+                                                           operand16, M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
                                                            defer, 0, so, row_base);
     if ((e = hipGetLastError()) != hipSuccess || !defer) return e;
     // parked rows: their exact columns on many CUs, then the rest of their merge
     exact_cols_kernel<<<dim3(kDeferSlices, rows), 256, 0, st>>>(defer, xexact, x_is_bf16 ? 1 : 0, ldx, M, K, V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, rec_stride, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
+                                                           operand16, M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
                                                            defer, 1, so, row_base);
     return hipGetLastError();
 }

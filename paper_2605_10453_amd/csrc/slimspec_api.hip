@@ -142,7 +142,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;      // diagnostic build, timing-only kernel: no result
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, tilescale, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, tile_f16 ? 2 : 1, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, tilescale, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
                                      (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);
@@ -155,7 +155,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, Mb, d, V, nullptr, 0, 0, nullptr, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, 0, Mb, d, V, nullptr, 0, 0, nullptr, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
                                      (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);

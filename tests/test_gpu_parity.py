@@ -408,6 +408,29 @@ def test_wide_rounding_bound_with_few_winners(gpu, oracle_mod):
     check_low_rank(gpu, oracle_mod, x, cfg.k)
 
 
+def test_two_probable_tokens_in_one_group_of_sixteen(gpu, oracle_mod):
+    """The row's two most probable tokens sit in the same group of 16 logits of one lane (columns b + 1 and b + 18 of a
+    32-column tile), so only the larger one is listed with its computed value; the other one carries 40 % of the
+    probability and, by construction, a large rounding error (a component orthogonal to t).  The merge has to replace
+    its term of the sum of exponentials too, for which it recomputes the logit the head kernel saw."""
+    cfg = synth.small_config(rows=24, d=256, r=96, V=2048, k=4, peaked_every=0)
+    x = synth.make_inputs(cfg, seed=91)
+    x.h = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(x.h) * np.float32(16.0))
+    t = synth.bf16_bits_to_f64(x.h) @ synth.bf16_bits_to_f64(x.A)
+    B = synth.bf16_bits_to_f32(x.B)
+    rng = np.random.default_rng(5)
+    for i in range(cfg.rows):
+        ti = t[i]
+        base = 64 * i
+        u = rng.standard_normal(cfg.r)
+        u -= (u @ ti) / (ti @ ti) * ti
+        u *= 2.0 / np.linalg.norm(u)
+        B[:, base + 1] = (90.0 * ti / (ti @ ti)).astype(np.float32)
+        B[:, base + 18] = (89.6 * ti / (ti @ ti) + u).astype(np.float32)
+    x.B = synth.f32_to_bf16_bits(B)
+    check_low_rank(gpu, oracle_mod, x, cfg.k)
+
+
 def test_logit_far_above_the_running_maximum(gpu, oracle_mod):
     """One column per row, late in the vocabulary (in a tile that is not the first one its block works on), whose logit is 126 to 130 binary orders above everything the row has
     seen until then (natural logits 88 ... 92 over a background of 2 ... 5): the running sum of exponentials has to be
