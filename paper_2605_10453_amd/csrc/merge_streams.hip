@@ -40,14 +40,13 @@ constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes 
 // errors of one sign at the bound would move the log-sum-exp by more than kLseGuard, the row is done exhaustively
 // (a guard for bounds close to kExhaustiveEps: the exhaustive pass costs milliseconds per row, and at 2.5e-2 the
 // peaked rows of a 512-row batch at r = 1024, whose real error is a tenth of that, already tripped it).
-constexpr float kWideEps = 1.2e-2f;
+constexpr float kWideEps = 8.0e-3f;      // (= kExactWinnersEps: from here on every winner is re-evaluated anyway)
 constexpr float kMassCut = 5.0e-4f;
 constexpr float kLseGuard = 1.0e-1f;
 constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
 constexpr int kSampleBit = 1 << 29;     // ... an entry of the sampling contenders' list (smp_id / smp_z) instead
 constexpr float kEpsSigmas = 4.0f;      // eps_v = this many standard deviations of the rounding error of t in column v
                                         // (values are re-evaluated when within eps_a + eps_b = 5.6 sigma of their difference)
-constexpr float kTileMaxBias = 1.35f;   // expected largest / true of 256 column rms estimates from 32 samples each
 constexpr int kSampleCap = 32;          // streams whose best z + g may be the row's Gumbel-max draw, at most
 constexpr int kTsCap = 4096;            // vocabulary tiles whose column scale is kept in shared memory (1 M columns)
 constexpr float kEpsViolation = 1.5f;   // a re-evaluated value further than this many eps_v from its computed value
@@ -538,10 +537,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     }
     else eps_abs = fabsf(tau) * 1.6e-5f + 1e-6f;
     // Scale of a tile's columns: the rms of all of B (tens of thousands of sampled entries: no noise to speak of), or
-    // the tile's own largest column rms (32 samples per column: the largest of 256 estimates overshoots by about a
-    // third, which kTileMaxBias takes off again) where that is larger, i.e. where the tile holds columns well above
-    // the average.
-    const auto tile_scale = [&](float tile_max) { return fmaxf(b_rms, tile_max * (1.f / kTileMaxBias)); };
+    // the tile's own column scale where that is larger, i.e. where the tile holds columns well above the average (the
+    // kernel that samples B has already taken the overshoot of "the largest of 256 estimates" off, or, where one column
+    // stands out of its tile, left that column's estimate as it is).
+    const auto tile_scale = [&](float tile_max) { return fmaxf(b_rms, tile_max); };
     const auto eps_of_tile = [&](int vt) {
         return (stat != nullptr) ? dt_scale * tile_scale(ts_cached ? ts[min(vt, n_vt - 1)] : ts_max) + eps_abs : eps_abs;
     };
