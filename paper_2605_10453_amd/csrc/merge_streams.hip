@@ -620,14 +620,15 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 if ((unsigned)id_max >= (unsigned)V) continue;      // cannot come from the head kernel: keeps the gathers in bounds whatever the records hold
                 // its own tile's bound decides (theta was the bound of the widest tile)
                 const float e_item = eps_of_tile(tag >> 3);
-                if (!(mask4(x) * unit >= tau - eps - e_item)) {
-                    // not a candidate for the top-k; collected all the same where the log-sum-exp needs its exact value
-                    if (mask4(x) * unit >= v_mass && e_item > kExactWinnersEps) push(id_max, mask4(x) * unit, 0, e_item);
-                    continue;
-                }
-                const uint32_t slot = push(id_max, mask4(x) * unit, 0, e_item);
-                if (keys[sidx * L + l] == tau_key) tau_slot = (int)slot;      // one writer: keys are unique
-                if (y > kNoValue && mask4(y) * unit >= tau - eps - e_item) {
+                // a candidate for the top-k, or at least a probable token whose exact value the log-sum-exp needs
+                const float xv = mask4(x) * unit, yv = mask4(y) * unit;
+                const bool cand = xv >= tau - eps - e_item;
+                const bool mass_on = e_item > kExactWinnersEps;      // (such a token is re-evaluated: see the need pass)
+                if (!cand && !(mass_on && xv >= v_mass)) continue;
+                const uint32_t slot = push(id_max, xv, 0, e_item);
+                if (cand && keys[sidx * L + l] == tau_key) tau_slot = (int)slot;      // one writer: keys are unique
+                // the group's other members, when its second largest value is a candidate or a probable token itself
+                if (y > kNoValue && ((cand && yv >= tau - eps - e_item) || (mass_on && yv >= v_mass))) {
                     for (int i = 0; i < 16; ++i) {
                         const int id = id_of(tag, i, half);
                         if (i != imax && (unsigned)id < (unsigned)V) push(id, 0.f, 1, e_item);
@@ -635,7 +636,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 }
             }
             const float U = r[2];
-            if (U > kNoValue && mask4(U) * unit >= theta) {
+            if (U > kNoValue && mask4(U) * unit >= fminf(theta, v_mass)) {
                 // every unlisted group of the stream: record sidx covers vocabulary tiles sidx, sidx + gw, ...
                 for (int vt = sidx; vt < n_vt; vt += gw)
                     for (int j = 0; j < 8; ++j)
