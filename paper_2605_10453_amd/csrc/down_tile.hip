@@ -321,7 +321,7 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
                 hb[e] = operand_bf16_bits(v[e]);                            // round to nearest even
                 const float dlt = v[e] - __uint_as_float(hb[e] << 16) * kLn2;
                 a += dlt * dlt;
-                b += v[e] * v[e];
+                b += v[e] * dlt;
             }
             packed = make_uint4(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16), hb[4] | (hb[5] << 16), hb[6] | (hb[7] << 16));
         } else {
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(256) void down_finish_kernel(
                 hv[e] = operand_f16(v[e]);
                 const float dlt = v[e] - (float)hv[e] * kLn2;
                 a += dlt * dlt;
-                b += v[e] * v[e];
+                b += v[e] * dlt;
             }
             packed = __builtin_bit_cast(uint4, hv);
         }

@@ -43,6 +43,7 @@ constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes 
 constexpr float kWideEps = 8.0e-3f;      // (= kExactWinnersEps: from here on every winner is re-evaluated anyway)
 constexpr float kMassCut = 5.0e-4f;
 constexpr float kLseGuard = 1.0e-1f;
+constexpr float kCommonModeTol = 1.0e-2f;
 constexpr int kListedBit = 1 << 30;     // marks, in the list of items to evaluate, a listed maximum (it has a computed value)
 constexpr int kSampleBit = 1 << 29;     // ... an entry of the sampling contenders' list (smp_id / smp_z) instead
 constexpr float kEpsSigmas = 4.0f;      // eps_v = this many standard deviations of the rounding error of t in column v
@@ -384,9 +385,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         if (tid + NT < n_vt) ts_first1 = tilescale[tid + NT];
     }
     // squared norm of t - rounded t: lane q of the first wavefront adds the row's entries q, q + 64, ... in order
-    float dt2_mine = 0.f;
+    float dt2_mine = 0.f, tdt_mine = 0.f;               // ... and of t . (t - rounded t)
     if (stat != nullptr && tid < 64)
-        for (int q = tid; q < n_stat; q += 64) dt2_mine += stat[(size_t)q * rows_pad + row].x;
+        for (int q = tid; q < n_stat; q += 64) {
+            const float2 sq = stat[(size_t)q * rows_pad + row];
+            dt2_mine += sq.x;
+            tdt_mine += sq.y;
+        }
     const f32x4 *mine_src = reinterpret_cast<const f32x4 *>(rec + (size_t)min(tid, nsr - 1) * rec_stride);
     const f32x4 mine0 = mine_src[0], mine1 = mine_src[1], mine2 = mine_src[2];
     auto load_rec = [&](int sidx, float (&f)[REC]) {
@@ -416,7 +421,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         xrow[j] = v; x2 += v * v; x1 += fabsf(v);
         if (operand16) xrow16[j] = operand_value(v, operand16 == 2);
     }
-    __shared__ float dt2_sh;
+    __shared__ float dt2_sh, tdt_sh;
     // Column scale of B per vocabulary tile (asked for early: by the time eps needs it, it has arrived): the largest
     // column rms of the tile, and the rms of all of B from the tiles' mean squares (added in a fixed order).
     float ts_max = 0.f, ts_msq = 0.f;
@@ -429,8 +434,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         }
     __shared__ float red_ts[NWAVES], red_tq[NWAVES];
     if (wave == 0) {                                          // (fixed order: the lanes' sums, then the DPP tree)
-        const float dt2_w = wave_sum(dt2_mine);
-        if (lane == 0) dt2_sh = dt2_w;
+        const float dt2_w = wave_sum(dt2_mine), tdt_w = wave_sum(tdt_mine);
+        if (lane == 0) { dt2_sh = dt2_w; tdt_sh = tdt_w; }
     }
     const float m_w = wave_max(m_t);
     float s_w = (m_t == kNegInf) ? 0.f : s_t * __builtin_amdgcn_exp2f(m_t - m_w);
@@ -692,7 +697,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                 if (lane == 0) mass_eval_sh = pm;
             }
             __syncthreads();
-            if ((1.f - fminf(mass_eval_sh, 1.f)) * eps > kLseGuard) exhaustive = true;
+            const float rest = 1.f - fminf(mass_eval_sh, 1.f);
+            if (rest * eps > kLseGuard) exhaustive = true;
+            // The part of the rounding error that lies along t itself, (t - rounded t) . t / |t|^2 =: rho, scales every
+            // logit by 1 - rho: errors of one sign, proportional to the logit, which do not average out of the sum of
+            // exponentials.  rho is known exactly; with a long contraction it is a few 1e-5, with a rank of a few dozen
+            // it reaches 1e-3 and more.  Where it could move the log-sum-exp of the tokens left over, the row is redone.
+            if (stat != nullptr && rest * fabsf(tdt_sh / X2) * fabsf(Mx * kLn2) > kCommonModeTol) exhaustive = true;
         }
     }
     if (!exhaustive) {
