@@ -166,7 +166,7 @@ struct MfmaPlan {
     size_t off_down_part = 0;            // fp32 [slices][n_rt][n_ct][4][16][64]: partial tiles of t (sized for any grouping of the rows)
     size_t off_t32 = 0;                  // fp32 [rows_pad, r]
     size_t off_t16 = 0;                  // 16-byte vectors [8 ceil(K / 64), rows_pad]: the head kernel's row operand
-    size_t off_stat = 0;                 // float2 [2 ceil(r / 64), rows_pad]
+    size_t off_stat = 0;                 // float2 [2 ceil(r / 64), rows_pad]: per row and 32 columns of t, (sum of dt^2, sum of t dt), dt = t - rounded t
     size_t off_tilescale = 0;            // float2 [n_vt]: (column scale, mean square) of B per vocabulary tile
     size_t off_streams = 0;              // fp32 [rows, nsr, kStreamRec]
     size_t off_defer = 0;                // parked rows of the merge (long contractions only; bytes 0 otherwise)
