@@ -24,7 +24,9 @@
  *                                    largest logit of the row, p = 0..k-1
  *     out_logprobs [rows, k] float   its log-probability
  * Order: descending logit; equal logits: smaller id first.  Logits are accumulated in
- * fp32 from exact bf16 products.  With few rows t = h A stays in fp32 throughout.  With
+ * fp32 from exact bf16 products, and the log-probabilities are fp32 values: their
+ * absolute accuracy is that of fp32 at the magnitude of the logits (about 1e-3 at logits
+ * of a few thousand, 1e-1 at 1e5), whatever the path.  With few rows t = h A stays in fp32 throughout.  With
  * many rows the matrix cores take a 16-bit t (bf16, or f16 for k > 12) for the sum of
  * exponentials and for finding the candidates; every candidate whose rank or reported
  * value could depend on that rounding is then evaluated again from the fp32 t.
