@@ -67,6 +67,7 @@ hipError_t launch_merge(const float2 *part_ms, const float *part_val, const int 
 constexpr int kStreamList = 3;          // groups kept per lane stream
 constexpr int kStreamRec = 3 + 3 * kStreamList;   // floats per stream partial
 constexpr int kStreamRecSample = kStreamRec + 8;  // ... of a sampling call
+static_assert(kStreamList == kStreamListPlan && kStreamRecSample == kStreamRecPlan, "the workspace plan is sized for these records");
 
 // t = h A for up to 512 rows: 64 x 64 tiles over slices of the contraction (partial tiles in `part`), then the
 // fixed-order sum of the slices: fp32 t, the 16-bit operand t log2(e) (bf16, or f16 when as_f16) in the k-grouped
