@@ -17,7 +17,11 @@
 // If the collected set outgrows its buffer (possible only with thousands of near-ties at the
 // k-th place) the block falls back to an exhaustive exact pass over the row's whole vocabulary.
 //
-// log-sum-exp: streams carry (max * log2 e, sum of 2^(z log2 e - max)); combined in a fixed order.
+// log-sum-exp: streams carry (max * log2 e, sum of 2^(z log2 e - max)); combined in a fixed order.  The sum is
+// made of computed logits: the term of every re-evaluated logit is replaced by its exact one (a listed maximum has
+// its recorded value; for any other column the computed logit is recomputed from the same 16-bit rounding of the
+// contraction input).  With a wide bound the row's probable tokens are re-evaluated for that purpose alone, and two
+// guards send a row whose remaining error could still be seen to the exhaustive pass (see kWideEps below).
 #include "device_utils.hpp"
 #include "launch.hpp"
 
