@@ -474,6 +474,17 @@ def main():
                                            20, 3, with_events=False)
                         extra[name]["with_sampling_outputs_us_per_call"] = sdt / 20 * 1e6
                         del ws_s
+                        # the same rows as six drafted positions (section 5.1 drafts six tokens) with a down-projection each
+                        n_pos = 6
+                        stack = torch.stack([As[0]] + [(torch.randn((d, r), device=dev) * d ** -0.5).to(torch.bfloat16)
+                                                       for _ in range(n_pos - 1)]).contiguous()
+                        off = [rows * p_ // n_pos for p_ in range(n_pos + 1)]
+                        ids_p, lp_p, ws_p = out_buffers(rows, d, r, V, k)
+                        pdt, _, _ = _timed(lambda i: binding.slimspec_head_topk_positions(h, stack, off, Bs[i % ncopies], k, out_ids=ids_p,
+                                                                                         out_logprobs=lp_p, workspace=ws_p),
+                                           20, 3, with_events=False)
+                        extra[name]["six_positions_us_per_call"] = pdt / 20 * 1e6
+                        del stack, ids_p, lp_p, ws_p
                     del h, As, Bs
                     torch.cuda.empty_cache()
                 except Exception as exc:
