@@ -150,7 +150,8 @@ inline DownGrid make_down_grid(int rows, int rows_pad, int d, int r, int n_group
     g.n_ct = (r + 63) / 64;
     const int tiles = g.n_rt * g.n_ct, n_full = d / 32;
     // (two blocks per CU, i.e. twice the slices, measured slower: 10.7 + 4.6 against 8.9 + 4.5 us at 512 rows)
-    while (g.slices < 64 && tiles * g.slices < 256 && n_full / (2 * g.slices) >= 2) g.slices *= 2;
+    // (at most 16 slices: with 32, at 16 and 64 rows, the tile kernel measures the same and the sum of the slices 1.1 us more)
+    while (g.slices < 16 && tiles * g.slices < 256 && n_full / (2 * g.slices) >= 2) g.slices *= 2;
     return g;
 }
 // Partial tiles of t, in 64 x 64 tiles of floats, for any grouping of `rows` rows into at most kMaxPositions groups:
