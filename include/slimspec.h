@@ -100,6 +100,25 @@ int slimspec_head_topk(const void *h, const void *A, const void *B,
                        void *workspace, size_t workspace_bytes,
                        void *stream);
 
+/* Column-major copy of a bf16 weight matrix: Mt[V, K] = transpose of M[K, V] (both device,
+ * 16-byte aligned, K and V multiples of 8; Mt holds K * V elements and belongs to the
+ * caller).  Made once per weight matrix, not per call.  Enqueued on `stream`. */
+int slimspec_transpose_weights(const void *M, int32_t K, int32_t V, void *Mt, void *stream);
+
+/* slimspec_head_topk (second display of section 4.1) for weights that do not change
+ * between calls, as in serving: the caller also passes Bt[V, r], the column-major copy of B
+ * made by slimspec_transpose_weights(B, r, V, Bt).  Same operation and outputs.  With five rows
+ * or more and k <= 16 the projection runs on 16-bit operands and uncertain ranks are settled
+ * by exact fp32 logits of single columns: a column is r adjacent elements of Bt but one
+ * element per 128-byte line of B, so these reads shrink by the line length.  Log-probabilities
+ * may differ from slimspec_head_topk's in the last bits (another summation order of the exact
+ * logits).  With fewer rows Bt is not read.  Bt must match B: nothing checks it. */
+int slimspec_head_topk_prepared(const void *h, const void *A, const void *B, const void *Bt,
+                                const slimspec_shape *shape, int32_t k,
+                                int32_t *out_ids, float *out_logprobs,
+                                void *workspace, size_t workspace_bytes,
+                                void *stream);
+
 /* The low-rank head for callers that cannot allocate device memory or hand over a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same operation, kernels and results as slimspec_head_topk, but the scratch

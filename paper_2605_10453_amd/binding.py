@@ -29,7 +29,7 @@ STATUS_SCRATCH_LIMIT = -5
 STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = (
-    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_sample", "full_head_sample", "routed_workspace_bytes", "routed_head_topk",
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_transpose_weights", "slimspec_head_topk_prepared", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_sample", "full_head_sample", "routed_workspace_bytes", "routed_head_topk",
     "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
@@ -65,6 +65,10 @@ def load_library() -> ctypes.CDLL:
     lib.slimspec_workspace_bytes.argtypes = [shp, i32]
     lib.slimspec_head_topk.restype = ctypes.c_int
     lib.slimspec_head_topk.argtypes = [vp, vp, vp, shp, i32, vp, vp, vp, sz, vp]
+    lib.slimspec_transpose_weights.restype = ctypes.c_int
+    lib.slimspec_transpose_weights.argtypes = [vp, i32, i32, vp, vp]
+    lib.slimspec_head_topk_prepared.restype = ctypes.c_int
+    lib.slimspec_head_topk_prepared.argtypes = [vp, vp, vp, vp, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_head_topk_static.restype = ctypes.c_int
     lib.slimspec_head_topk_static.argtypes = [vp, vp, vp, shp, i32, vp, vp, vp]
     lib.full_head_topk.restype = ctypes.c_int
@@ -182,6 +186,51 @@ def slimspec_head_topk(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, k: int
                                 _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
                                 _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                 _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs
+
+
+def slimspec_transpose_weights(M: torch.Tensor, out: Optional[torch.Tensor] = None,
+                               stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Column-major copy Mt [V, K] of a bf16 weight matrix M [K, V] (made once per matrix)."""
+    K, V = M.shape
+    if M.element_size() != 2:
+        raise ValueError("M must hold bf16 (2-byte) elements")
+    if out is None:
+        out = torch.empty((V, K), dtype=M.dtype, device=M.device)
+    if tuple(out.shape) != (V, K) or out.element_size() != 2:
+        raise ValueError("out must be a [V, K] tensor of 2-byte elements")
+    lib = load_library()
+    st = lib.slimspec_transpose_weights(_dev_ptr(M, "M"), K, V, _dev_ptr(out, "out"), _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out
+
+
+def slimspec_head_topk_prepared(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, Bt: torch.Tensor, k: int,
+                                out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                                workspace: Optional[torch.Tensor] = None,
+                                stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """slimspec_head_topk with the column-major copy Bt [V, r] of B (see slimspec_transpose_weights) as well."""
+    rows, d = h.shape
+    d2, r = A.shape
+    r2, V = B.shape
+    if d != d2 or r != r2 or tuple(Bt.shape) != (V, r):
+        raise ValueError("shape mismatch between h, A, B and Bt")
+    for t, n in ((h, "h"), (A, "A"), (B, "B"), (Bt, "Bt")):
+        if t.element_size() != 2:
+            raise ValueError(f"{n} must hold bf16 (2-byte) elements")
+    out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, r, V)
+    need = int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k))
+    workspace = _workspace(need, h.device, workspace)
+    st = lib.slimspec_head_topk_prepared(_dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"), _dev_ptr(Bt, "Bt"),
+                                         ctypes.byref(shape), k,
+                                         _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+                                         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                         _stream_handle(stream))
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs

@@ -104,10 +104,13 @@ hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pa
 // two more launches that spread the column gathers over many CUs (worth it for long contractions only)
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, int operand16,
-                                const uint16_t *M, int K, int V,
+                                const uint16_t *M, int K, int V, const uint16_t *Mt,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
                                 void *defer_buf, const SampleOut &so, int row_base, hipStream_t st);
+
+// Mt[V, K] = the transpose of M[K, V] (bf16): the column-major copy launch_merge_streams can take
+hipError_t launch_transpose_weights(const uint16_t *M, int K, int V, uint16_t *Mt, hipStream_t st);
 
 // ---- router-then-exact head: exact full-head logits on each row's k_route routed ids, softmax and top-k over them
 // part: rows * routed_slices(d) * k_route floats of scratch

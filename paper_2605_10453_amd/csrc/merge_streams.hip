@@ -167,6 +167,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     const void *__restrict__ xexact, int x_is_bf16, int ldx,
     int operand16,      // 0: the head kernel's row operand was exact; 1: it was t log2(e) rounded to bf16; 2: to f16
     const uint16_t *__restrict__ M, int K, int V,
+    const uint16_t *__restrict__ Mt,      // null, or the caller's column-major copy of M, [V, K]: a column is K adjacent elements
     const float2 *__restrict__ stat, int n_stat, int rows_pad, const float2 *__restrict__ tilescale,
     int k, float unit, float tiny_w, int32_t *__restrict__ out_ids, float *__restrict__ out_logprobs,
     const int32_t *__restrict__ id_map, int *__restrict__ defer, int resume, SampleOut so, int row_base)
@@ -767,6 +768,57 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             // (the second sum only in a batch that holds a column without a recorded value: every wavefront sees the same
             // 16 entries, so all of them decide alike)
             const bool batch16 = with16 && __ballot((entry & (kListedBit | kSampleBit)) == 0) != 0ull;
+            if (Mt != nullptr) {
+                // Column-major copy: wavefront w takes columns w, w + NWAVES, ... of the batch, a lane 8 adjacent
+                // elements of the column per step (K = 512: one 16-byte load per lane and column, all of a
+                // wavefront's columns in flight together); lanes in order inside the DPP tree.
+                constexpr int CPW = 16 / NWAVES;
+                float zc[CPW], zc16[CPW];
+#pragma unroll
+                for (int q = 0; q < CPW; ++q) { zc[q] = 0.f; zc16[q] = 0.f; }
+                const uint16_t *col[CPW];
+#pragma unroll
+                for (int q = 0; q < CPW; ++q) {
+                    const int ent = w_need[min(g0 + wave + q * NWAVES, n_need - 1)];
+                    const int it = ent & (kSampleBit - 1);
+                    col[q] = Mt + (size_t)((ent & kSampleBit) ? smp_id[it] : w_id[it]) * K;
+                }
+                for (int j = lane * 8; j < K; j += 512) {        // K is a multiple of 8
+                    uint4 wq[CPW];
+#pragma unroll
+                    for (int q = 0; q < CPW; ++q) wq[q] = *reinterpret_cast<const uint4 *>(col[q] + j);
+                    float xv[8];                                   // (xrow is 8-byte aligned)
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2) {
+                        const float2 x2 = *reinterpret_cast<const float2 *>(xrow + j + e);
+                        xv[e] = x2.x; xv[e + 1] = x2.y;
+                    }
+#pragma unroll
+                    for (int q = 0; q < CPW; ++q) {
+                        const float f[8] = {bf16_lo(wq[q].x), bf16_hi(wq[q].x), bf16_lo(wq[q].y), bf16_hi(wq[q].y),
+                                            bf16_lo(wq[q].z), bf16_hi(wq[q].z), bf16_lo(wq[q].w), bf16_hi(wq[q].w)};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) zc[q] = fmaf(xv[e], f[e], zc[q]);
+                        if (batch16) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) zc16[q] = fmaf(xrow16[j + e], f[e], zc16[q]);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < CPW; ++q) {
+                    const float z = wave_sum(zc[q]), z16 = batch16 ? wave_sum(zc16[q]) : 0.f;
+                    if (lane == 0) { red_ex[0][wave + q * NWAVES] = z; red_ex16[0][wave + q * NWAVES] = z16; }
+                }
+                __syncthreads();
+                if (tid < 16 && g0 + tid < n_need) {
+                    const float z = red_ex[0][tid];
+                    if (entry & kSampleBit) smp_z[item] = z;
+                    else take_exact(entry, z, batch16 ? red_ex16[0][tid] : z, Mx);
+                }
+                __syncthreads();
+                continue;
+            }
             float acc = 0.f, acc16 = 0.f;
             // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 16 independent loads per lane (K = 512: one round trip)
             const uint16_t *mcol = M + id;
@@ -895,7 +947,7 @@ size_t merge_streams_lds_bytes(int nsr, int k, int n_vt) {
 
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,
                                 const void *xexact, bool x_is_bf16, int ldx, int operand16,
-                                const uint16_t *M, int K, int V,
+                                const uint16_t *M, int K, int V, const uint16_t *Mt,
                                 const float2 *stat, int n_stat, int rows_pad, const float2 *tilescale, int k,
                                 float unit, float tiny_w, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
                                 void *defer_buf, const SampleOut &so, int row_base, hipStream_t st)
@@ -904,17 +956,18 @@ hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, in
     static LdsLimit lds_limit;
     hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(merge_streams_kernel), (int)lds);
     if (e != hipSuccess) return e;
-    int *defer = so.on ? nullptr : static_cast<int *>(defer_buf);      // sampling calls evaluate in place
+    // sampling calls evaluate in place; with a column-major copy an exact logit is one short read: nothing to park
+    int *defer = (so.on || Mt != nullptr) ? nullptr : static_cast<int *>(defer_buf);
     const int rec_stride = so.on ? kStreamRecSample : kStreamRec;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, rec_stride, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           operand16, M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
+                                                           operand16, M, K, V, Mt, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
                                                            defer, 0, so, row_base);
     if ((e = hipGetLastError()) != hipSuccess || !defer) return e;
     // parked rows: their exact columns on many CUs, then the rest of their merge
     exact_cols_kernel<<<dim3(kDeferSlices, rows), 256, 0, st>>>(defer, xexact, x_is_bf16 ? 1 : 0, ldx, M, K, V);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     merge_streams_kernel<<<rows, kMergeThreads, lds, st>>>(part, rec_stride, nsr, gw, n_vt, xexact, x_is_bf16 ? 1 : 0, ldx,
-                                                           operand16, M, K, V, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
+                                                           operand16, M, K, V, Mt, stat, n_stat, rows_pad, tilescale, k, unit, tiny_w, out_ids, out_logprobs, id_map,
                                                            defer, 1, so, row_base);
     return hipGetLastError();
 }

@@ -97,7 +97,7 @@ int position_of_row(const Positions &pos, int row)
     return p;
 }
 
-int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
+int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M, const void *Mt,
                   const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs, const int32_t *id_map,
                   const Positions &pos, const SampleOut &so, void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -108,6 +108,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
     const int per = mfma_max_rows_per_launch(shape->rows);
     const uint16_t *hb = static_cast<const uint16_t *>(h);
     const uint16_t *Mb = static_cast<const uint16_t *>(M);
+    const uint16_t *Mtb = static_cast<const uint16_t *>(Mt);      // column-major copy of M, or null
     for (int row0 = 0; row0 < shape->rows; row0 += per) {
         const int rows = (shape->rows - row0 < per) ? shape->rows - row0 : per;
         // a last, smaller batch may fall below the matrix-core threshold; it still runs here
@@ -132,7 +133,8 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             void *t16 = ws + p.off_t16;
             float2 *stat = reinterpret_cast<float2 *>(ws + p.off_stat);
             float2 *tilescale = reinterpret_cast<float2 *>(ws + p.off_tilescale);
-            const bool tile_f16 = head_tile_f16(k);
+            // (with a column-major copy the re-evaluations the finer operand saves cost little: bf16 as it is)
+            const bool tile_f16 = head_tile_f16(k) && Mtb == nullptr;
             e = launch_down_projection_tiles(hrow, static_cast<const uint16_t *>(A), reinterpret_cast<float *>(ws + p.off_down_part), p.down,
                                              p.rows_pad, d, r, t32, t16, stat, Mb, V, tilescale, tile_f16, s);
             if (e != hipSuccess) return fail_hip(e);
@@ -142,7 +144,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;      // diagnostic build, timing-only kernel: no result
             // the records are in base-2 units (t was scaled by log2 e); f16 mode flushes weights below 2^-25 to zero
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, tile_f16 ? 2 : 1, Mb, r, V, stat, 2 * ((r + 63) / 64), p.rows_pad, tilescale, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, t32, false, r, tile_f16 ? 2 : 1, Mb, r, V, Mtb, stat, 2 * ((r + 63) / 64), p.rows_pad, tilescale, k,
                                      0.6931471805599453f, tile_f16 ? 2.9802322e-8f : 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
                                      (p.defer && merge_parks_rows(r, tile_f16)) ? ws + p.off_defer : nullptr, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);
@@ -155,7 +157,7 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
             if (e != hipSuccess) return fail_hip(e);
             if (timed && (e = hipEventRecord(g_ev_stop, s)) != hipSuccess) return fail_hip(e);
             if (head_tile_timing_only()) return SLIMSPEC_UNSUPPORTED;
-            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, 0, Mb, d, V, nullptr, 0, 0, nullptr, k,
+            e = launch_merge_streams(streams, rows, p.nsr, p.gw, p.n_vt, hrow, true, d, 0, Mb, d, V, Mtb, nullptr, 0, 0, nullptr, k,
                                      1.0f, 0.f, out_ids + (size_t)row0 * k, out_logprobs + (size_t)row0 * k, id_map,
                                      (p.defer && merge_parks_rows(d, true)) ? ws + p.off_defer : nullptr, so, row0, s);
             if (e != hipSuccess) return fail_hip(e);
@@ -167,20 +169,20 @@ int run_head_mfma(HeadKind kind, const void *h, const void *A, const void *M,
 int run_head(HeadKind kind, const void *h, const void *A, const void *M, bool m_is_f32,
              const slimspec_shape *shape, int32_t k, int32_t *out_ids, float *out_logprobs,
              void *workspace, size_t workspace_bytes, void *stream, const int32_t *id_map = nullptr,
-             const Positions &pos = Positions(), const SampleOut &so = SampleOut())
+             const Positions &pos = Positions(), const SampleOut &so = SampleOut(), const void *Mt = nullptr)
 {
     int st = check_shape(kind, shape, k);
     if (st != SLIMSPEC_OK) return st;
     if (!h || !M || !out_ids || !out_logprobs || !workspace) return SLIMSPEC_INVALID_ARGUMENT;
     if (kind == HeadKind::LowRank && !A) return SLIMSPEC_INVALID_ARGUMENT;
-    if (!aligned16(h) || !aligned16(M) || (A && !aligned16(A)) || !aligned16(workspace))
+    if (!aligned16(h) || !aligned16(M) || (A && !aligned16(A)) || !aligned16(workspace) || !aligned16(Mt))
         return SLIMSPEC_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(out_ids) & 3u) || (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
         return SLIMSPEC_UNSUPPORTED;
     if (so.on && (!so.lse || !so.sample_ids || !so.sample_logprobs)) return SLIMSPEC_INVALID_ARGUMENT;
     const bool use_mfma = shape->rows >= kMfmaMinRows && !m_is_f32 && k <= kMfmaMaxK;
     if (use_mfma)
-        return run_head_mfma(kind, h, A, M, shape, k, out_ids, out_logprobs, id_map, pos, so, workspace, workspace_bytes, stream);
+        return run_head_mfma(kind, h, A, M, Mt, shape, k, out_ids, out_logprobs, id_map, pos, so, workspace, workspace_bytes, stream);
     const Plan p = make_plan(kind, shape->rows, shape->d, shape->r, shape->V, k);
     if (workspace_bytes < p.bytes) return SLIMSPEC_WORKSPACE_TOO_SMALL;
 
@@ -279,6 +281,26 @@ int slimspec_head_topk(const void *h, const void *A, const void *B,
 {
     return run_head(HeadKind::LowRank, h, A, B, false, shape, k, out_ids, out_logprobs,
                     workspace, workspace_bytes, stream);
+}
+
+int slimspec_transpose_weights(const void *M, int32_t K, int32_t V, void *Mt, void *stream)
+{
+    if (!M || !Mt || K <= 0 || V <= 0) return SLIMSPEC_INVALID_ARGUMENT;
+    if ((K & 7) || (V & 7) || (int64_t)V > (int64_t)1 << 28) return SLIMSPEC_UNSUPPORTED;
+    if (!aligned16(M) || !aligned16(Mt)) return SLIMSPEC_UNSUPPORTED;
+    const hipError_t e = launch_transpose_weights(static_cast<const uint16_t *>(M), K, V, static_cast<uint16_t *>(Mt),
+                                                  static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? SLIMSPEC_OK : fail_hip(e);
+}
+
+int slimspec_head_topk_prepared(const void *h, const void *A, const void *B, const void *Bt,
+                                const slimspec_shape *shape, int32_t k,
+                                int32_t *out_ids, float *out_logprobs,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Bt) return SLIMSPEC_INVALID_ARGUMENT;
+    return run_head(HeadKind::LowRank, h, A, B, false, shape, k, out_ids, out_logprobs,
+                    workspace, workspace_bytes, stream, nullptr, Positions(), SampleOut(), Bt);
 }
 
 int slimspec_head_topk_static(const void *h, const void *A, const void *B,

@@ -204,3 +204,29 @@ def test_routed_head_argument_validation(lib):
     assert call(good, 64, 10, W=null) == b.STATUS_INVALID_ARGUMENT
     assert call(good, 64, 10, dtype=3) == b.STATUS_INVALID_ARGUMENT
     assert call(good, 64, 10, wsb=need - 1) == b.STATUS_WORKSPACE_TOO_SMALL
+
+
+def test_prepared_weights_argument_validation(lib):
+    l, b = lib
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    good = b.SlimspecShape(512, 4096, 512, 128256)
+
+    def call(shape=good, k=10, Bt=fake, wsb=1 << 40):
+        return l.slimspec_head_topk_prepared(fake, fake, fake, Bt, ctypes.byref(shape), k, fake, fake, fake, wsb, None)
+
+    assert call(Bt=null) == b.STATUS_INVALID_ARGUMENT
+    assert call(Bt=ctypes.c_void_p(0x1008)) == b.STATUS_UNSUPPORTED                      # misaligned
+    assert call(k=0) == b.STATUS_INVALID_ARGUMENT
+    assert call(shape=b.SlimspecShape(512, 4096, 516, 128256)) == b.STATUS_UNSUPPORTED
+    assert call(wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
+
+    def transpose(M=fake, K=512, V=128256, Mt=fake):
+        return l.slimspec_transpose_weights(M, K, V, Mt, None)
+
+    assert transpose(M=null) == b.STATUS_INVALID_ARGUMENT
+    assert transpose(Mt=null) == b.STATUS_INVALID_ARGUMENT
+    assert transpose(K=0) == b.STATUS_INVALID_ARGUMENT
+    assert transpose(V=-8) == b.STATUS_INVALID_ARGUMENT
+    assert transpose(K=12) == b.STATUS_UNSUPPORTED
+    assert transpose(V=128257) == b.STATUS_UNSUPPORTED
+    assert transpose(Mt=ctypes.c_void_p(0x1004)) == b.STATUS_UNSUPPORTED
