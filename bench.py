@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--head", default="low_rank", choices=("low_rank", "full"),
                     help="full: time full_head_topk on the workload's shape instead (a profiling aid: the comparator "
                          "alone in the run; implies --quick)")
+    ap.add_argument("--prepared", action="store_true",
+                    help="time slimspec_head_topk_prepared (the caller also passes a column-major copy of B, made once "
+                         "before the timed region) instead of slimspec_head_topk; the JSON line says so in config")
     ap.add_argument("--quick", action="store_true", help="skip the extra workloads and the CPU baseline")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra workloads only")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -171,14 +174,20 @@ def main():
         ws = torch.empty(binding.slimspec_workspace_bytes(rows, d, r, V, k), dtype=torch.uint8, device=dev)
         return ids, lp, ws
 
-    def time_low_rank_tensors(h, As, Bs, k, steps, warmup, with_events=True):
+    def time_low_rank_tensors(h, As, Bs, k, steps, warmup, with_events=True, prepared=False):
         rows, d = h.shape
         r, V = Bs[0].shape
         ids, lp, ws = out_buffers(rows, d, r, V, k)
         n = len(Bs)
+        if prepared:          # weights are prepared once, outside the timed region
+            Bts = [binding.slimspec_transpose_weights(b) for b in Bs]
+            torch.cuda.synchronize()
 
-        def step(i):
-            binding.slimspec_head_topk(h, As[i % n], Bs[i % n], k, out_ids=ids, out_logprobs=lp, workspace=ws)
+            def step(i):
+                binding.slimspec_head_topk_prepared(h, As[i % n], Bs[i % n], Bts[i % n], k, out_ids=ids, out_logprobs=lp, workspace=ws)
+        else:
+            def step(i):
+                binding.slimspec_head_topk(h, As[i % n], Bs[i % n], k, out_ids=ids, out_logprobs=lp, workspace=ws)
 
         return _timed(step, steps, warmup, with_events)
 
@@ -189,7 +198,7 @@ def main():
         for _ in range(copies - 1):
             As.append(As[0].clone())
             Bs.append(Bs[0].clone())
-        return time_low_rank_tensors(h, As, Bs, cfg.k, steps, warmup, with_events)
+        return time_low_rank_tensors(h, As, Bs, cfg.k, steps, warmup, with_events, prepared=args.prepared)
 
     def time_full_tensors(h, Ws, k, steps, warmup, with_events=True):
         rows, d = h.shape
@@ -279,6 +288,8 @@ def main():
     log(f"[bench] {ms_per_step * 1e3:.2f} us/call, {rows_per_s:.1f} rows/s, projection kernel {kern_ms * 1e3:.2f} us "
         f"(empty event pair {null_ms * 1e3:.2f} us)")
 
+    head_name = ("FULL head (comparator, not the headline metric)" if full_only else
+                 "low-rank head with the caller's column-major copy of B" if args.prepared else "low-rank head")
     out = {
         "metric": "LM-head rows/s (and us/call) at d=4096,r=512,V=128256; % HBM/MFMA peak",
         "value": rows_per_s, "unit": "rows/s",
@@ -289,7 +300,7 @@ def main():
         "dtype": "bf16 weights and hidden states, fp32 accumulate",
         "data": "synthetic (seeded host generator for the headline workload; the extra workloads draw the same "
                 "distributions on the device)",
-        "config": {"workload": f"{cfg.name}: {'FULL head (comparator, not the headline metric)' if full_only else 'low-rank head'} "
+        "config": {"workload": f"{cfg.name}: {head_name} "
                                f"rows={cfg.rows} d={cfg.d} r={cfg.r} V={cfg.V} k={cfg.k}, "
                                f"{copies} rotating weight copies (cold last-level cache)",
                    "rows": cfg.rows, "d": cfg.d, "r": cfg.r, "V": cfg.V, "k": cfg.k},
@@ -468,6 +479,9 @@ def main():
                     edt, ek, ecall = time_low_rank_tensors(h, As, Bs, k, nsteps, 8)
                     extra[name] = low_rank_entry(name, rows, d, r, V, k, edt, nsteps, ek, ecall, null_ms)
                     extra[name]["weight_copies"] = ncopies
+                    if rows >= 5:       # the matrix-core path with the caller's column-major copy of B as well
+                        qdt, _, _ = time_low_rank_tensors(h, As, Bs, k, nsteps, 8, with_events=False, prepared=True)
+                        extra[name]["prepared_weights_us_per_call"] = qdt / nsteps * 1e6
                     if name == "C4_512_rows":
                         ws_s = torch.empty(binding.slimspec_workspace_bytes(rows, d, r, V, k), dtype=torch.uint8, device=dev)
                         sdt, _, _ = _timed(lambda i: binding.slimspec_head_sample(h, As[i % ncopies], Bs[i % ncopies], k, i, workspace=ws_s),

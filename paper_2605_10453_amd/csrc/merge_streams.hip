@@ -36,6 +36,7 @@ constexpr int kExhaustCap = kMergeThreads * 4 + SLIMSPEC_KMAX_INTERNAL;
 static_assert(kMergeThreads * 4 <= kWorkCap, "a step of the exhaustive pass appends at most kWorkCap keys");
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
 constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
+constexpr int kGatherRound = 64;          // columns of a column-major copy evaluated per round of loads
 constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes the exhaustive exact pass
 // The streams' sum of exponentials is made of computed logits; the merge replaces the terms of the logits it
 // re-evaluates, so what remains of its error is the probability-weighted mean error of all the others.  With a wide
@@ -760,7 +761,65 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         const int n_need = (int)cnt_need;
         __shared__ float red_ex[NWAVES][16], red_ex16[NWAVES][16];
         const bool with16 = operand16 != 0;
-        for (int g0 = 0; g0 < n_need; g0 += 16) {
+        // Column-major copy: a column is K adjacent elements.  64 columns per round; wavefront w takes columns w,
+        // w + NWAVES, ... of the round, a lane 8 adjacent elements of the column per step (K = 512: one 16-byte load
+        // per lane and column, all of a wavefront's columns in flight together); lanes in order inside the DPP tree.
+        for (int g0 = 0; Mt != nullptr && g0 < n_need; g0 += kGatherRound) {
+            constexpr int CPW = kGatherRound / NWAVES;
+            __shared__ float z_col[kGatherRound], z16_col[kGatherRound];
+            const int n_here = min(kGatherRound, n_need - g0);
+            const int entry = w_need[g0 + min(lane, n_here - 1)];
+            // (the second sum only in a round that holds a column without a recorded value: every wavefront sees the same
+            // entries, so all of them decide alike)
+            const bool round16 = with16 && __ballot(lane < n_here && (entry & (kListedBit | kSampleBit)) == 0) != 0ull;
+            float zc[CPW], zc16[CPW];
+            const uint16_t *col[CPW];
+#pragma unroll
+            for (int q = 0; q < CPW; ++q) {
+                zc[q] = 0.f; zc16[q] = 0.f;
+                const int ent = w_need[g0 + min(wave + q * NWAVES, n_here - 1)];
+                const int it = ent & (kSampleBit - 1);
+                col[q] = Mt + (size_t)((ent & kSampleBit) ? smp_id[it] : w_id[it]) * K;
+            }
+            for (int j = lane * 8; j < K; j += 512) {        // K is a multiple of 8
+                uint4 wq[CPW];
+#pragma unroll
+                for (int q = 0; q < CPW; ++q)
+                    if (wave + q * NWAVES < n_here) wq[q] = *reinterpret_cast<const uint4 *>(col[q] + j);
+                float xv[8];                                   // (xrow is 8-byte aligned)
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const float2 x2 = *reinterpret_cast<const float2 *>(xrow + j + e);
+                    xv[e] = x2.x; xv[e + 1] = x2.y;
+                }
+#pragma unroll
+                for (int q = 0; q < CPW; ++q) {
+                    if (wave + q * NWAVES >= n_here) continue;
+                    const float f[8] = {bf16_lo(wq[q].x), bf16_hi(wq[q].x), bf16_lo(wq[q].y), bf16_hi(wq[q].y),
+                                        bf16_lo(wq[q].z), bf16_hi(wq[q].z), bf16_lo(wq[q].w), bf16_hi(wq[q].w)};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) zc[q] = fmaf(xv[e], f[e], zc[q]);
+                    if (round16) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) zc16[q] = fmaf(xrow16[j + e], f[e], zc16[q]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < CPW; ++q) {
+                if (wave + q * NWAVES >= n_here) continue;     // (the same for the whole wavefront)
+                const float z = wave_sum(zc[q]), z16 = round16 ? wave_sum(zc16[q]) : 0.f;
+                if (lane == 0) { z_col[wave + q * NWAVES] = z; z16_col[wave + q * NWAVES] = z16; }
+            }
+            __syncthreads();
+            if (tid < n_here) {                                 // tid < 64: `entry` is this column's
+                const float z = z_col[tid];
+                if (entry & kSampleBit) smp_z[entry & (kSampleBit - 1)] = z;
+                else take_exact(entry, z, round16 ? z16_col[tid] : z, Mx);
+            }
+            __syncthreads();
+        }
+        for (int g0 = 0; Mt == nullptr && g0 < n_need; g0 += 16) {
             const int u = lane & 15, jsub = lane >> 4;
             const int entry = w_need[min(g0 + u, n_need - 1)];
             const int item = entry & (kSampleBit - 1);
@@ -768,57 +827,6 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             // (the second sum only in a batch that holds a column without a recorded value: every wavefront sees the same
             // 16 entries, so all of them decide alike)
             const bool batch16 = with16 && __ballot((entry & (kListedBit | kSampleBit)) == 0) != 0ull;
-            if (Mt != nullptr) {
-                // Column-major copy: wavefront w takes columns w, w + NWAVES, ... of the batch, a lane 8 adjacent
-                // elements of the column per step (K = 512: one 16-byte load per lane and column, all of a
-                // wavefront's columns in flight together); lanes in order inside the DPP tree.
-                constexpr int CPW = 16 / NWAVES;
-                float zc[CPW], zc16[CPW];
-#pragma unroll
-                for (int q = 0; q < CPW; ++q) { zc[q] = 0.f; zc16[q] = 0.f; }
-                const uint16_t *col[CPW];
-#pragma unroll
-                for (int q = 0; q < CPW; ++q) {
-                    const int ent = w_need[min(g0 + wave + q * NWAVES, n_need - 1)];
-                    const int it = ent & (kSampleBit - 1);
-                    col[q] = Mt + (size_t)((ent & kSampleBit) ? smp_id[it] : w_id[it]) * K;
-                }
-                for (int j = lane * 8; j < K; j += 512) {        // K is a multiple of 8
-                    uint4 wq[CPW];
-#pragma unroll
-                    for (int q = 0; q < CPW; ++q) wq[q] = *reinterpret_cast<const uint4 *>(col[q] + j);
-                    float xv[8];                                   // (xrow is 8-byte aligned)
-#pragma unroll
-                    for (int e = 0; e < 8; e += 2) {
-                        const float2 x2 = *reinterpret_cast<const float2 *>(xrow + j + e);
-                        xv[e] = x2.x; xv[e + 1] = x2.y;
-                    }
-#pragma unroll
-                    for (int q = 0; q < CPW; ++q) {
-                        const float f[8] = {bf16_lo(wq[q].x), bf16_hi(wq[q].x), bf16_lo(wq[q].y), bf16_hi(wq[q].y),
-                                            bf16_lo(wq[q].z), bf16_hi(wq[q].z), bf16_lo(wq[q].w), bf16_hi(wq[q].w)};
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) zc[q] = fmaf(xv[e], f[e], zc[q]);
-                        if (batch16) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) zc16[q] = fmaf(xrow16[j + e], f[e], zc16[q]);
-                        }
-                    }
-                }
-#pragma unroll
-                for (int q = 0; q < CPW; ++q) {
-                    const float z = wave_sum(zc[q]), z16 = batch16 ? wave_sum(zc16[q]) : 0.f;
-                    if (lane == 0) { red_ex[0][wave + q * NWAVES] = z; red_ex16[0][wave + q * NWAVES] = z16; }
-                }
-                __syncthreads();
-                if (tid < 16 && g0 + tid < n_need) {
-                    const float z = red_ex[0][tid];
-                    if (entry & kSampleBit) smp_z[item] = z;
-                    else take_exact(entry, z, batch16 ? red_ex16[0][tid] : z, Mx);
-                }
-                __syncthreads();
-                continue;
-            }
             float acc = 0.f, acc16 = 0.f;
             // rows wave * 4 + jsub + 4 NWAVES e, e = 0, 1, ...: batches of 16 independent loads per lane (K = 512: one round trip)
             const uint16_t *mcol = M + id;
