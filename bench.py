@@ -418,7 +418,14 @@ def main():
                                     "paper_relative_head_time_r_d8": 0.46,
                                     "note": "routed_head_topk: low-rank router (k_route ids per row), exact logits on those, softmax "
                                             "over them; the paper's ratio is SpecVocab at r = d/8 on H200 in vLLM (context only)"}
-            del hr_, Ar_, Br_, wsr
+            # the same head from the token-major full head Wt [V, d] (the layout frameworks store it in)
+            Wts = [w.t().contiguous() for w in Ws]
+            step_t = lambda i: binding.routed_head_topk_prepared(hr_, Ar_[i % 2], Br_[i % 2], Wts[i % 2], k_route, cfg.k,
+                                                                 out_ids=idr, out_logprobs=lpr, workspace=wsr)
+            tdt, _, _ = _timed(step_t, nf, 5, with_events=False)
+            extra["routed_head"]["token_major_W_us_per_call"] = tdt / nf * 1e6
+            extra["routed_head"]["token_major_W_relative_to_full_head"] = tdt / fdt
+            del hr_, Ar_, Br_, wsr, Wts
         except Exception as exc:
             extra["routed_head"] = {"error": repr(exc)[:200]}
         # six head calls (the paper's six draft steps, section 5.1) captured in one HIP graph: no host launch jitter
@@ -499,6 +506,22 @@ def main():
                                            20, 3, with_events=False)
                         extra[name]["six_positions_us_per_call"] = pdt / 20 * 1e6
                         del stack, ids_p, lp_p, ws_p
+                        # the router-then-exact head on the same rows, 16 routed ids per row (the router on the matrix cores)
+                        k_rt = 16
+                        Wr = (torch.randn((d, V), device=dev) * d ** -0.5).to(torch.bfloat16)
+                        Wrt = Wr.t().contiguous()
+                        Bt0 = binding.slimspec_transpose_weights(Bs[0])
+                        import ctypes as _ct2
+                        shape_q = binding.SlimspecShape(rows, d, r, V)
+                        ws_q = torch.empty(int(binding.load_library().routed_workspace_bytes(_ct2.byref(shape_q), k_rt)), dtype=torch.uint8, device=dev)
+                        ids_q, lp_q, _ = out_buffers(rows, d, r, V, k)
+                        q1, _, _ = _timed(lambda i: binding.routed_head_topk(h, As[0], Bs[0], Wr, k_rt, k, out_ids=ids_q, out_logprobs=lp_q,
+                                                                             workspace=ws_q), 10, 2, with_events=False)
+                        q2, _, _ = _timed(lambda i: binding.routed_head_topk_prepared(h, As[0], Bs[0], Wrt, k_rt, k, Bt=Bt0, out_ids=ids_q,
+                                                                                      out_logprobs=lp_q, workspace=ws_q), 20, 3, with_events=False)
+                        extra[name]["routed_head_k_route_16"] = {"us_per_call": q1 / 10 * 1e6, "token_major_W_and_Bt_us_per_call": q2 / 20 * 1e6,
+                                                                 "note": "one copy of the weights (warm last-level cache for B, W read sparsely)"}
+                        del Wr, Wrt, Bt0, ws_q, ids_q, lp_q
                     del h, As, Bs
                     torch.cuda.empty_cache()
                 except Exception as exc:

@@ -215,6 +215,20 @@ int routed_head_topk(const void *h, const void *A, const void *B, const void *W,
                      void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* routed_head_topk for weights in the layouts a serving stack keeps anyway: Wt [V, d] is the
+ * token-major full head (the transpose of W [d, V]: the row of a token is d adjacent elements,
+ * bf16 or fp32 by w_dtype, 16-byte aligned), so the exact logits of the routed ids read
+ * k_route * d adjacent-element rows instead of one element per 128-byte line; Bt is null or
+ * the column-major copy of B for the router (see slimspec_head_topk_prepared).  Same operation
+ * and outputs (the exact logits are summed in another order: last bits).  Nothing checks that
+ * Wt and Bt match W and B. */
+int routed_head_topk_prepared(const void *h, const void *A, const void *B, const void *Bt,
+                              const void *Wt, slimspec_dtype w_dtype,
+                              const slimspec_shape *shape, int32_t k_route, int32_t k,
+                              int32_t *out_ids, float *out_logprobs,
+                              void *workspace, size_t workspace_bytes,
+                              void *stream);
+
 /* Human-readable name of a status code (static storage). */
 const char *slimspec_status_string(int status);
 

@@ -29,7 +29,7 @@ STATUS_SCRATCH_LIMIT = -5
 STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = (
-    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_transpose_weights", "slimspec_head_topk_prepared", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_sample", "full_head_sample", "routed_workspace_bytes", "routed_head_topk",
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_transpose_weights", "slimspec_head_topk_prepared", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_sample", "full_head_sample", "routed_workspace_bytes", "routed_head_topk", "routed_head_topk_prepared",
     "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
@@ -83,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.routed_workspace_bytes.argtypes = [shp, i32]
     lib.routed_head_topk.restype = ctypes.c_int
     lib.routed_head_topk.argtypes = [vp, vp, vp, vp, ctypes.c_int, shp, i32, i32, vp, vp, vp, sz, vp]
+    lib.routed_head_topk_prepared.restype = ctypes.c_int
+    lib.routed_head_topk_prepared.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, shp, i32, i32, vp, vp, vp, sz, vp]
     lib.truncated_head_topk.restype = ctypes.c_int
     lib.truncated_head_topk.argtypes = [vp, vp, ctypes.c_int, vp, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_status_string.restype = ctypes.c_char_p
@@ -427,6 +429,32 @@ def routed_head_topk(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, W: torch
                               ctypes.byref(shape), k_route, k, _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
                               _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                               _stream_handle(stream))
+    if st != STATUS_OK:
+        _raise(st)
+    return out_ids, out_logprobs
+
+
+def routed_head_topk_prepared(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, Wt: torch.Tensor, k_route: int, k: int,
+                              Bt: Optional[torch.Tensor] = None,
+                              out_ids: Optional[torch.Tensor] = None, out_logprobs: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None,
+                              stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """routed_head_topk with the token-major full head Wt [V, d] (and, optionally, the column-major copy Bt [V, r] of B)."""
+    rows, d = h.shape
+    d2, r = A.shape
+    r2, V = B.shape
+    if d != d2 or r != r2 or tuple(Wt.shape) != (V, d) or (Bt is not None and tuple(Bt.shape) != (V, r)):
+        raise ValueError("shape mismatch between h, A, B, Wt and Bt")
+    w_dtype = SLIMSPEC_F32 if Wt.dtype == torch.float32 else SLIMSPEC_BF16
+    out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
+    lib = load_library()
+    shape = SlimspecShape(rows, d, r, V)
+    workspace = _workspace(int(lib.routed_workspace_bytes(ctypes.byref(shape), k_route)), h.device, workspace)
+    st = lib.routed_head_topk_prepared(_dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"),
+                                       _dev_ptr(Bt, "Bt") if Bt is not None else None, _dev_ptr(Wt, "Wt"), w_dtype,
+                                       ctypes.byref(shape), k_route, k, _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+                                       _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                       _stream_handle(stream))
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs

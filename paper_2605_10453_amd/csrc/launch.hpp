@@ -117,5 +117,8 @@ hipError_t launch_transpose_weights(const uint16_t *M, int K, int V, uint16_t *M
 int routed_slices(int d);
 hipError_t launch_routed_exact(const uint16_t *h, const void *W, bool w_is_f32, const int32_t *route_ids, float *part,
                                int rows, int d, int V, int k_route, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st);
+// ... from a token-major copy of W, Wt [V, d]; y: rows * k_route floats of scratch
+hipError_t launch_routed_exact_token_major(const uint16_t *h, const void *Wt, bool w_is_f32, const int32_t *route_ids, float *y,
+                                           int rows, int d, int V, int k_route, int k, int32_t *out_ids, float *out_logprobs, hipStream_t st);
 
 }  // namespace slimspec

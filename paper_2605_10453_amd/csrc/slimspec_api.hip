@@ -360,10 +360,12 @@ size_t routed_workspace_bytes(const slimspec_shape *shape, int32_t k_route)
     return align_up(router) + align_up(4 * n) + align_up(4 * n) + align_up(4 * n * routed_slices(shape->d));
 }
 
-int routed_head_topk(const void *h, const void *A, const void *B, const void *W, slimspec_dtype w_dtype,
-                     const slimspec_shape *shape, int32_t k_route, int32_t k,
-                     int32_t *out_ids, float *out_logprobs,
-                     void *workspace, size_t workspace_bytes, void *stream)
+namespace {
+// W: [d, V], or (token_major) its copy [V, d]; Bt: null, or the column-major copy of B for the router
+int run_routed(const void *h, const void *A, const void *B, const void *Bt, const void *W, bool token_major, slimspec_dtype w_dtype,
+               const slimspec_shape *shape, int32_t k_route, int32_t k,
+               int32_t *out_ids, float *out_logprobs,
+               void *workspace, size_t workspace_bytes, void *stream)
 {
     if (w_dtype != SLIMSPEC_BF16 && w_dtype != SLIMSPEC_F32) return SLIMSPEC_INVALID_ARGUMENT;
     const int st = check_shape(HeadKind::LowRank, shape, k_route);
@@ -379,12 +381,34 @@ int routed_head_topk(const void *h, const void *A, const void *B, const void *W,
     float *route_lp = reinterpret_cast<float *>(ws + router + align_up(4 * n));
     float *part = reinterpret_cast<float *>(ws + router + 2 * align_up(4 * n));
     // the router: the low-rank head's k_route best ids of every row
-    const int rs = run_head(HeadKind::LowRank, h, A, B, false, shape, k_route, route_ids, route_lp, workspace, router, stream);
+    const int rs = run_head(HeadKind::LowRank, h, A, B, false, shape, k_route, route_ids, route_lp, workspace, router, stream,
+                            nullptr, Positions(), SampleOut(), Bt);
     if (rs != SLIMSPEC_OK) return rs;
-    const hipError_t e = launch_routed_exact(static_cast<const uint16_t *>(h), W, w_dtype == SLIMSPEC_F32, route_ids, part,
-                                             shape->rows, shape->d, shape->V, k_route, k, out_ids, out_logprobs,
-                                             static_cast<hipStream_t>(stream));
+    const hipError_t e = token_major
+        ? launch_routed_exact_token_major(static_cast<const uint16_t *>(h), W, w_dtype == SLIMSPEC_F32, route_ids, part,
+                                          shape->rows, shape->d, shape->V, k_route, k, out_ids, out_logprobs,
+                                          static_cast<hipStream_t>(stream))
+        : launch_routed_exact(static_cast<const uint16_t *>(h), W, w_dtype == SLIMSPEC_F32, route_ids, part,
+                              shape->rows, shape->d, shape->V, k_route, k, out_ids, out_logprobs,
+                              static_cast<hipStream_t>(stream));
     return e == hipSuccess ? SLIMSPEC_OK : fail_hip(e);
+}
+}  // namespace
+
+int routed_head_topk(const void *h, const void *A, const void *B, const void *W, slimspec_dtype w_dtype,
+                     const slimspec_shape *shape, int32_t k_route, int32_t k,
+                     int32_t *out_ids, float *out_logprobs,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_routed(h, A, B, nullptr, W, false, w_dtype, shape, k_route, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
+}
+
+int routed_head_topk_prepared(const void *h, const void *A, const void *B, const void *Bt, const void *Wt, slimspec_dtype w_dtype,
+                              const slimspec_shape *shape, int32_t k_route, int32_t k,
+                              int32_t *out_ids, float *out_logprobs,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_routed(h, A, B, Bt, Wt, true, w_dtype, shape, k_route, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
 }
 
 int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,

@@ -230,3 +230,19 @@ def test_prepared_weights_argument_validation(lib):
     assert transpose(K=12) == b.STATUS_UNSUPPORTED
     assert transpose(V=128257) == b.STATUS_UNSUPPORTED
     assert transpose(Mt=ctypes.c_void_p(0x1004)) == b.STATUS_UNSUPPORTED
+
+
+def test_routed_head_prepared_argument_validation(lib):
+    l, b = lib
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    good = b.SlimspecShape(1, 4096, 512, 128256)
+
+    def call(shape=good, k_route=64, k=10, Bt=null, Wt=fake, dtype=0, wsb=1 << 40):
+        return l.routed_head_topk_prepared(fake, fake, fake, Bt, Wt, dtype, ctypes.byref(shape), k_route, k, fake, fake, fake, wsb, None)
+
+    assert call(Wt=null) == b.STATUS_INVALID_ARGUMENT
+    assert call(Wt=ctypes.c_void_p(0x1008)) == b.STATUS_UNSUPPORTED
+    assert call(Bt=ctypes.c_void_p(0x1008)) == b.STATUS_UNSUPPORTED
+    assert call(k=65) == b.STATUS_INVALID_ARGUMENT
+    assert call(dtype=7) == b.STATUS_INVALID_ARGUMENT
+    assert call(wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL

@@ -205,17 +205,26 @@ def test_config4_sample(gpu, oracle_mod):
 @pytest.mark.parametrize("rows,d,r,V,k_route,k,w_f32", [
     (1, 256, 32, 8200, 32, 8, False), (1, 4096, 512, 20000, 64, 10, False), (3, 128, 16, 5000, 16, 16, True),
     (9, 96, 24, 2056, 12, 5, False), (20, 136, 32, 3080, 40, 7, False),
+    (70, 264, 64, 8200, 16, 8, False), (130, 1032, 520, 4104, 13, 13, True),        # the router on the matrix-core path
 ])
-def test_routed_head(gpu, oracle_mod, rows, d, r, V, k_route, k, w_f32):
+@pytest.mark.parametrize("layout", ["W_d_by_V", "token_major_Wt", "token_major_Wt_and_Bt"])
+def test_routed_head(gpu, oracle_mod, rows, d, r, V, k_route, k, w_f32, layout):
     torch, b = gpu
-    print(f"routed head rows={rows} d={d} r={r} V={V} k_route={k_route} k={k} f32={w_f32}", flush=True)
+    print(f"routed head rows={rows} d={d} r={r} V={V} k_route={k_route} k={k} f32={w_f32} {layout}", flush=True)
     x = synth.make_inputs(synth.small_config(rows, d, r, V, k, peaked_every=4), seed=400 + rows, with_full_head=True)
     # a full head that agrees with the router on the whole but not in detail (as a trained router would)
     zr = synth.bf16_bits_to_f64(x.A) @ synth.bf16_bits_to_f64(x.B)
     W = synth.f32_to_bf16_bits((zr + 0.3 * synth.bf16_bits_to_f64(x.W)).astype(np.float32))
     Wh = synth.bf16_bits_to_f32(W) if w_f32 else W
-    ids, lp = b.routed_head_topk(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B),
-                                 to_dev_f32(Wh) if w_f32 else to_dev_bf16(Wh), k_route, k)
+    if layout == "W_d_by_V":
+        ids, lp = b.routed_head_topk(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B),
+                                     to_dev_f32(Wh) if w_f32 else to_dev_bf16(Wh), k_route, k)
+    else:
+        Wt = np.ascontiguousarray(Wh.T)                     # transposed on the host: the layout a framework stores
+        B = to_dev_bf16(x.B)
+        Bt = b.slimspec_transpose_weights(B) if layout.endswith("Bt") else None
+        ids, lp = b.routed_head_topk_prepared(to_dev_bf16(x.h), to_dev_bf16(x.A), B,
+                                              to_dev_f32(Wt) if w_f32 else to_dev_bf16(Wt), k_route, k, Bt=Bt)
     torch.cuda.synchronize()
     ids, lp = ids.cpu().numpy(), lp.cpu().numpy()
     o_ids, o_lp, o_lse, o_route = oracle_mod.routed_head_topk(x.h, x.A, x.B, Wh, k_route, k)
@@ -263,6 +272,11 @@ def test_truncated_and_routed_heads_at_the_single_row_workload(gpu, oracle_mod):
     assert np.all(router.z[0, ids[0]] >= kth - 1e-3), "an id the router would not have kept"
     y_at = lambda ri, ci: oracle_mod.full_logits_at(x.h, x.W, ri, ci)
     compare_with_oracle(ids, lp, o_ids, o_lse, y_at, cfg.V)
+    print("... and from the token-major full head", flush=True)
+    ids_t, lp_t = b.routed_head_topk_prepared(h, to_dev_bf16(x.A), to_dev_bf16(x.B), to_dev_bf16(np.ascontiguousarray(x.W.T)), k_route, cfg.k)
+    torch.cuda.synchronize()
+    compare_with_oracle(ids_t.cpu().numpy(), lp_t.cpu().numpy(), o_ids, o_lse, y_at, cfg.V)
+    assert np.array_equal(ids_t.cpu().numpy(), ids)
 
 
 def test_positions_at_the_512_row_workload(gpu, oracle_mod):
