@@ -494,6 +494,10 @@ def main():
                         sdt, _, _ = _timed(lambda i: binding.slimspec_head_sample(h, As[i % ncopies], Bs[i % ncopies], k, i, workspace=ws_s),
                                            20, 3, with_events=False)
                         extra[name]["with_sampling_outputs_us_per_call"] = sdt / 20 * 1e6
+                        Bts_s = [binding.slimspec_transpose_weights(b_) for b_ in Bs]
+                        sdt, _, _ = _timed(lambda i: binding.slimspec_head_sample_prepared(h, As[i % ncopies], Bs[i % ncopies], Bts_s[i % ncopies],
+                                                                                           k, i, workspace=ws_s), 20, 3, with_events=False)
+                        extra[name]["with_sampling_outputs_prepared_weights_us_per_call"] = sdt / 20 * 1e6
                         del ws_s
                         # the same rows as six drafted positions (section 5.1 drafts six tokens) with a down-projection each
                         n_pos = 6
@@ -505,6 +509,11 @@ def main():
                                                                                          out_logprobs=lp_p, workspace=ws_p),
                                            20, 3, with_events=False)
                         extra[name]["six_positions_us_per_call"] = pdt / 20 * 1e6
+                        pdt, _, _ = _timed(lambda i: binding.slimspec_head_topk_positions_prepared(h, stack, off, Bs[i % ncopies], Bts_s[i % ncopies], k,
+                                                                                                  out_ids=ids_p, out_logprobs=lp_p, workspace=ws_p),
+                                           20, 3, with_events=False)
+                        extra[name]["six_positions_prepared_weights_us_per_call"] = pdt / 20 * 1e6
+                        del Bts_s
                         del stack, ids_p, lp_p, ws_p
                         # the router-then-exact head on the same rows, 16 routed ids per row (the router on the matrix cores)
                         k_rt = 16

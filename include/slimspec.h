@@ -215,6 +215,22 @@ int routed_head_topk(const void *h, const void *A, const void *B, const void *W,
                      void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* slimspec_head_sample and slimspec_head_topk_positions with the column-major copy Bt [V, r]
+ * of B as well (see slimspec_head_topk_prepared): same operations and outputs; ids, draws and
+ * log-probabilities as from the plain calls up to the summation order of the exact logits. */
+int slimspec_head_sample_prepared(const void *h, const void *A, const void *B, const void *Bt,
+                                  const slimspec_shape *shape, int32_t k, uint64_t seed,
+                                  int32_t *out_ids, float *out_logprobs,
+                                  float *out_lse, int32_t *out_sample_ids, float *out_sample_logprobs,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *stream);
+int slimspec_head_topk_positions_prepared(const void *h, const void *A_stack, int32_t n_pos,
+                                          const int32_t *pos_offsets, const void *B, const void *Bt,
+                                          const slimspec_shape *shape, int32_t k,
+                                          int32_t *out_ids, float *out_logprobs,
+                                          void *workspace, size_t workspace_bytes,
+                                          void *stream);
+
 /* routed_head_topk for weights in the layouts a serving stack keeps anyway: Wt [V, d] is the
  * token-major full head (the transpose of W [d, V]: the row of a token is d adjacent elements,
  * bf16 or fp32 by w_dtype, 16-byte aligned), so the exact logits of the routed ids read

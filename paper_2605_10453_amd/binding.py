@@ -29,7 +29,7 @@ STATUS_SCRATCH_LIMIT = -5
 STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTED_SYMBOLS = (
-    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_transpose_weights", "slimspec_head_topk_prepared", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_sample", "full_head_sample", "routed_workspace_bytes", "routed_head_topk", "routed_head_topk_prepared",
+    "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_transpose_weights", "slimspec_head_topk_prepared", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_topk_positions_prepared", "slimspec_head_sample", "slimspec_head_sample_prepared", "full_head_sample", "routed_workspace_bytes", "routed_head_topk", "routed_head_topk_prepared",
     "slimspec_status_string", "slimspec_last_hip_error", "slimspec_set_timing_events",
 )
 
@@ -77,6 +77,10 @@ def load_library() -> ctypes.CDLL:
     lib.slimspec_head_topk_positions.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int32), vp, shp, i32, vp, vp, vp, sz, vp]
     lib.slimspec_head_sample.restype = ctypes.c_int
     lib.slimspec_head_sample.argtypes = [vp, vp, vp, shp, i32, ctypes.c_uint64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.slimspec_head_sample_prepared.restype = ctypes.c_int
+    lib.slimspec_head_sample_prepared.argtypes = [vp, vp, vp, vp, shp, i32, ctypes.c_uint64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.slimspec_head_topk_positions_prepared.restype = ctypes.c_int
+    lib.slimspec_head_topk_positions_prepared.argtypes = [vp, vp, i32, ctypes.POINTER(ctypes.c_int32), vp, vp, shp, i32, vp, vp, vp, sz, vp]
     lib.full_head_sample.restype = ctypes.c_int
     lib.full_head_sample.argtypes = [vp, vp, ctypes.c_int, shp, i32, ctypes.c_uint64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.routed_workspace_bytes.restype = sz
@@ -333,6 +337,18 @@ def slimspec_head_topk_positions(h: torch.Tensor, A_stack: torch.Tensor, pos_off
                                  stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """Low-rank head with one down-projection per drafted position: A_stack [n_pos, d, r]; rows
     [pos_offsets[p], pos_offsets[p + 1]) use matrix p (pos_offsets: a host sequence of n_pos + 1 ints)."""
+    return _positions(h, A_stack, pos_offsets, B, None, k, out_ids, out_logprobs, workspace, stream)
+
+
+def slimspec_head_topk_positions_prepared(h: torch.Tensor, A_stack: torch.Tensor, pos_offsets, B: torch.Tensor, Bt: torch.Tensor,
+                                          k: int, out_ids: Optional[torch.Tensor] = None,
+                                          out_logprobs: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                                          stream: Optional[torch.cuda.Stream] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """slimspec_head_topk_positions with the column-major copy Bt [V, r] of B as well."""
+    return _positions(h, A_stack, pos_offsets, B, Bt, k, out_ids, out_logprobs, workspace, stream)
+
+
+def _positions(h, A_stack, pos_offsets, B, Bt, k, out_ids, out_logprobs, workspace, stream):
     rows, d = h.shape
     n_pos, d2, r = A_stack.shape
     r2, V = B.shape
@@ -341,7 +357,9 @@ def slimspec_head_topk_positions(h: torch.Tensor, A_stack: torch.Tensor, pos_off
     off = [int(v) for v in pos_offsets]
     if len(off) != n_pos + 1:
         raise ValueError("pos_offsets must have n_pos + 1 entries")
-    for t, n in ((h, "h"), (A_stack, "A_stack"), (B, "B")):
+    if Bt is not None and tuple(Bt.shape) != (V, r):
+        raise ValueError("Bt must be [V, r]")
+    for t, n in ((h, "h"), (A_stack, "A_stack"), (B, "B")) + (((Bt, "Bt"),) if Bt is not None else ()):
         if t.element_size() != 2:
             raise ValueError(f"{n} must hold bf16 (2-byte) elements")
     out_ids, out_logprobs = _outputs(rows, k, h.device, out_ids, out_logprobs)
@@ -350,10 +368,13 @@ def slimspec_head_topk_positions(h: torch.Tensor, A_stack: torch.Tensor, pos_off
     need = int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k))
     workspace = _workspace(need, h.device, workspace)
     off_arr = (ctypes.c_int32 * (n_pos + 1))(*off)
-    st = lib.slimspec_head_topk_positions(_dev_ptr(h, "h"), _dev_ptr(A_stack, "A_stack"), n_pos, off_arr, _dev_ptr(B, "B"),
-                                          ctypes.byref(shape), k, _dev_ptr(out_ids, "out_ids"),
-                                          _dev_ptr(out_logprobs, "out_logprobs"), _dev_ptr(workspace, "workspace"),
-                                          workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    tail = (ctypes.byref(shape), k, _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if Bt is None:
+        st = lib.slimspec_head_topk_positions(_dev_ptr(h, "h"), _dev_ptr(A_stack, "A_stack"), n_pos, off_arr, _dev_ptr(B, "B"), *tail)
+    else:
+        st = lib.slimspec_head_topk_positions_prepared(_dev_ptr(h, "h"), _dev_ptr(A_stack, "A_stack"), n_pos, off_arr,
+                                                       _dev_ptr(B, "B"), _dev_ptr(Bt, "Bt"), *tail)
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs
@@ -367,6 +388,16 @@ def _sample_outputs(rows, device):
 def slimspec_head_sample(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, k: int, seed: int,
                          workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
     """Low-rank head with the outputs of stochastic decoding: (ids, logprobs, lse, sample_ids, sample_logprobs)."""
+    return _sample(h, A, B, None, k, seed, workspace, stream)
+
+
+def slimspec_head_sample_prepared(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, Bt: torch.Tensor, k: int, seed: int,
+                                  workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """slimspec_head_sample with the column-major copy Bt [V, r] of B as well."""
+    return _sample(h, A, B, Bt, k, seed, workspace, stream)
+
+
+def _sample(h, A, B, Bt, k, seed, workspace, stream):
     rows, d = h.shape
     d2, r = A.shape
     r2, V = B.shape
@@ -377,11 +408,15 @@ def slimspec_head_sample(h: torch.Tensor, A: torch.Tensor, B: torch.Tensor, k: i
     lib = load_library()
     shape = SlimspecShape(rows, d, r, V)
     workspace = _workspace(int(lib.slimspec_workspace_bytes(ctypes.byref(shape), k)), h.device, workspace)
-    st = lib.slimspec_head_sample(_dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"), ctypes.byref(shape), k, seed,
-                                  _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
-                                  _dev_ptr(lse, "lse"), _dev_ptr(sid, "sample_ids"), _dev_ptr(slp, "sample_logprobs"),
-                                  _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(),
-                                  _stream_handle(stream))
+    tail = (ctypes.byref(shape), k, seed, _dev_ptr(out_ids, "out_ids"), _dev_ptr(out_logprobs, "out_logprobs"),
+            _dev_ptr(lse, "lse"), _dev_ptr(sid, "sample_ids"), _dev_ptr(slp, "sample_logprobs"),
+            _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if Bt is None:
+        st = lib.slimspec_head_sample(_dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"), *tail)
+    else:
+        if tuple(Bt.shape) != (V, r) or Bt.element_size() != 2:
+            raise ValueError("Bt must be a [V, r] tensor of bf16 (2-byte) elements")
+        st = lib.slimspec_head_sample_prepared(_dev_ptr(h, "h"), _dev_ptr(A, "A"), _dev_ptr(B, "B"), _dev_ptr(Bt, "Bt"), *tail)
     if st != STATUS_OK:
         _raise(st)
     return out_ids, out_logprobs, lse, sid, slp

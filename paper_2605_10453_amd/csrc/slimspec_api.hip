@@ -339,6 +339,17 @@ int slimspec_head_sample(const void *h, const void *A, const void *B,
                     nullptr, Positions(), sample_out(seed, out_lse, out_sample_ids, out_sample_logprobs));
 }
 
+int slimspec_head_sample_prepared(const void *h, const void *A, const void *B, const void *Bt,
+                                  const slimspec_shape *shape, int32_t k, uint64_t seed,
+                                  int32_t *out_ids, float *out_logprobs,
+                                  float *out_lse, int32_t *out_sample_ids, float *out_sample_logprobs,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Bt) return SLIMSPEC_INVALID_ARGUMENT;
+    return run_head(HeadKind::LowRank, h, A, B, false, shape, k, out_ids, out_logprobs, workspace, workspace_bytes, stream,
+                    nullptr, Positions(), sample_out(seed, out_lse, out_sample_ids, out_sample_logprobs), Bt);
+}
+
 int full_head_sample(const void *h, const void *W, slimspec_dtype w_dtype,
                      const slimspec_shape *shape, int32_t k, uint64_t seed,
                      int32_t *out_ids, float *out_logprobs,
@@ -411,10 +422,11 @@ int routed_head_topk_prepared(const void *h, const void *A, const void *B, const
     return run_routed(h, A, B, Bt, Wt, true, w_dtype, shape, k_route, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
 }
 
-int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,
-                                 const void *B, const slimspec_shape *shape, int32_t k,
-                                 int32_t *out_ids, float *out_logprobs,
-                                 void *workspace, size_t workspace_bytes, void *stream)
+namespace {
+int run_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,
+                  const void *B, const void *Bt, const slimspec_shape *shape, int32_t k,
+                  int32_t *out_ids, float *out_logprobs,
+                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!shape || !pos_offsets) return SLIMSPEC_INVALID_ARGUMENT;
     if (n_pos < 1) return SLIMSPEC_INVALID_ARGUMENT;
@@ -427,7 +439,25 @@ int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_p
     Positions pos;
     pos.n = n_pos; pos.off = pos_offsets;
     return run_head(HeadKind::LowRank, h, A_stack, B, false, shape, k, out_ids, out_logprobs,
-                    workspace, workspace_bytes, stream, nullptr, pos);
+                    workspace, workspace_bytes, stream, nullptr, pos, SampleOut(), Bt);
+}
+}  // namespace
+
+int slimspec_head_topk_positions(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,
+                                 const void *B, const slimspec_shape *shape, int32_t k,
+                                 int32_t *out_ids, float *out_logprobs,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    return run_positions(h, A_stack, n_pos, pos_offsets, B, nullptr, shape, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
+}
+
+int slimspec_head_topk_positions_prepared(const void *h, const void *A_stack, int32_t n_pos, const int32_t *pos_offsets,
+                                          const void *B, const void *Bt, const slimspec_shape *shape, int32_t k,
+                                          int32_t *out_ids, float *out_logprobs,
+                                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Bt) return SLIMSPEC_INVALID_ARGUMENT;
+    return run_positions(h, A_stack, n_pos, pos_offsets, B, Bt, shape, k, out_ids, out_logprobs, workspace, workspace_bytes, stream);
 }
 
 int truncated_head_topk(const void *h, const void *W_tr, slimspec_dtype w_dtype, const int32_t *id_map,

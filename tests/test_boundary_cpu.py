@@ -246,3 +246,26 @@ def test_routed_head_prepared_argument_validation(lib):
     assert call(k=65) == b.STATUS_INVALID_ARGUMENT
     assert call(dtype=7) == b.STATUS_INVALID_ARGUMENT
     assert call(wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
+
+
+def test_prepared_sampling_and_positions_argument_validation(lib):
+    l, b = lib
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    good = b.SlimspecShape(8, 4096, 512, 128256)
+
+    def sample(Bt=fake, k=10, lse=fake, wsb=1 << 40):
+        return l.slimspec_head_sample_prepared(fake, fake, fake, Bt, ctypes.byref(good), k, 7, fake, fake, lse, fake, fake, fake, wsb, None)
+
+    assert sample(Bt=null) == b.STATUS_INVALID_ARGUMENT
+    assert sample(lse=null) == b.STATUS_INVALID_ARGUMENT
+    assert sample(k=0) == b.STATUS_INVALID_ARGUMENT
+    assert sample(wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
+
+    def positions(off, Bt=fake, n_pos=2, wsb=1 << 40):
+        arr = (ctypes.c_int32 * len(off))(*off)
+        return l.slimspec_head_topk_positions_prepared(fake, fake, n_pos, arr, fake, Bt, ctypes.byref(good), 10, fake, fake, fake, wsb, None)
+
+    assert positions([0, 4, 8], Bt=null) == b.STATUS_INVALID_ARGUMENT
+    assert positions([0, 4, 7]) == b.STATUS_INVALID_ARGUMENT
+    assert positions([0, 4, 8], Bt=ctypes.c_void_p(0x1002)) == b.STATUS_UNSUPPORTED
+    assert positions([0, 4, 8], wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL

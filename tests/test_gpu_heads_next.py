@@ -77,7 +77,8 @@ def test_truncated_head_tied_columns_break_by_column(gpu, oracle_mod):
     ((300, 250, 50), 64, 32, 1032, 5),              # two launches: a group crosses the 512-row boundary
     ((9, 11), 128, 32, 3080, 20),                   # k beyond the matrix-core path: streaming in row groups of 8
 ])
-def test_position_specific_down_projections(gpu, oracle_mod, sizes, d, r, V, k):
+@pytest.mark.parametrize("prepared", [False, True])
+def test_position_specific_down_projections(gpu, oracle_mod, sizes, d, r, V, k, prepared):
     torch, b = gpu
     rows, n_pos = sum(sizes), len(sizes)
     print(f"positions case sizes={sizes} d={d} r={r} V={V} k={k}", flush=True)
@@ -86,8 +87,11 @@ def test_position_specific_down_projections(gpu, oracle_mod, sizes, d, r, V, k):
     stack = np.stack([x.A] + [synth.f32_to_bf16_bits((rng.standard_normal((d, r)) * d ** -0.5).astype(np.float32))
                               for _ in range(n_pos - 1)])
     off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
-    ids, lp = b.slimspec_head_topk_positions(to_dev_bf16(x.h), to_dev_bf16(stack.reshape(n_pos * d, r)).view(n_pos, d, r),
-                                             off.tolist(), to_dev_bf16(x.B), k)
+    stack_dev, B = to_dev_bf16(stack.reshape(n_pos * d, r)).view(n_pos, d, r), to_dev_bf16(x.B)
+    if prepared:      # with the column-major copy of B as well
+        ids, lp = b.slimspec_head_topk_positions_prepared(to_dev_bf16(x.h), stack_dev, off.tolist(), B, b.slimspec_transpose_weights(B), k)
+    else:
+        ids, lp = b.slimspec_head_topk_positions(to_dev_bf16(x.h), stack_dev, off.tolist(), B, k)
     torch.cuda.synchronize()
     ora = oracle_mod.slimspec_head_topk_positions(x.h, stack, off, x.B, k, return_logits=True)
     z_at = lambda ri, ci: ora.z[ri, ci]
@@ -132,11 +136,16 @@ def check_sample_outputs(torch, out, ora, seed, V, z_rows, oracle_mod):
     (9, 96, 24, 2056, 7, 5), (40, 256, 32, 4104, 12, 6), (130, 64, 40, 2056, 5, 7), (20, 128, 32, 3080, 20, 8),
     (12, 64, 24, 2056, 16, 9),
 ])
-def test_low_rank_head_sample(gpu, oracle_mod, rows, d, r, V, k, seed):
+@pytest.mark.parametrize("prepared", [False, True])
+def test_low_rank_head_sample(gpu, oracle_mod, rows, d, r, V, k, seed, prepared):
     torch, b = gpu
-    print(f"sample case rows={rows} d={d} r={r} V={V} k={k} seed={seed}", flush=True)
+    print(f"sample case rows={rows} d={d} r={r} V={V} k={k} seed={seed} prepared={prepared}", flush=True)
     x = synth.make_inputs(synth.small_config(rows, d, r, V, k, peaked_every=4), seed=200 + rows)
-    out = b.slimspec_head_sample(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), k, seed)
+    if prepared:      # with the column-major copy of B as well
+        B = to_dev_bf16(x.B)
+        out = b.slimspec_head_sample_prepared(to_dev_bf16(x.h), to_dev_bf16(x.A), B, b.slimspec_transpose_weights(B), k, seed)
+    else:
+        out = b.slimspec_head_sample(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), k, seed)
     torch.cuda.synchronize()
     ora = oracle_mod.head_sample(x.h, x.A, x.B, k, seed, return_logits=True)
     check_sample_outputs(torch, out, ora, seed, V, ora.z, oracle_mod)
@@ -187,12 +196,17 @@ def test_config2_sample(gpu, oracle_mod):
         check_sample_outputs(torch, out, ora, seed, cfg.V, ora.z, oracle_mod)
 
 
-def test_config4_sample(gpu, oracle_mod):
+@pytest.mark.parametrize("prepared", [False, True])
+def test_config4_sample(gpu, oracle_mod, prepared):
     """The 512-row throughput workload (matrix-core path, peaked rows) with the outputs of stochastic decoding."""
     torch, b = gpu
     cfg = synth.CONFIGS["C4"]
     x = synth.make_inputs(cfg, 0)
-    out = b.slimspec_head_sample(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), cfg.k, 12345)
+    if prepared:
+        B = to_dev_bf16(x.B)
+        out = b.slimspec_head_sample_prepared(to_dev_bf16(x.h), to_dev_bf16(x.A), B, b.slimspec_transpose_weights(B), cfg.k, 12345)
+    else:
+        out = b.slimspec_head_sample(to_dev_bf16(x.h), to_dev_bf16(x.A), to_dev_bf16(x.B), cfg.k, 12345)
     torch.cuda.synchronize()
     ora = oracle_mod.head_sample(x.h, x.A, x.B, cfg.k, 12345, return_logits=True)
     n_other = check_sample_outputs(torch, out, ora, 12345, cfg.V, ora.z, oracle_mod)
