@@ -82,7 +82,7 @@ typedef enum slimspec_status {
 #define SLIMSPEC_KMAX 64
 #define SLIMSPEC_VERSION 1
 #define SLIMSPEC_MAX_POSITIONS 16
-#define SLIMSPEC_STATIC_SCRATCH_BYTES (32u << 20)   /* device scratch built into the library, per GPU */
+#define SLIMSPEC_STATIC_SCRATCH_BYTES (64u << 20)   /* device scratch built into the library, per GPU */
 
 /* Library version (SLIMSPEC_VERSION it was built with).  Host only, no HIP call. */
 int slimspec_version(void);

@@ -150,6 +150,6 @@ __device__ __forceinline__ void sample_combine(SampleTrack &a, const SampleTrack
 // Work of block g: row block rb and the vocabulary tiles col, col + gw, col + 2 gw, ...
 // Blocks are dealt round-robin to the 8 XCDs, so blocks g and g + 8 share an L2: they get the same
 // vocabulary tiles and different row blocks, and so read each tile of M from HBM once.
-struct HeadGrid { int n_rb, gw, n_vt; };
+struct HeadGrid { int n_rb, gw, n_vt, spb; };      // spb: records a block leaves per row (4, 2 or 1)
 
 }  // namespace slimspec

@@ -399,9 +399,32 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
         return;
     }
 
-    // ---- one record per (row, block): the four streams of a row (two half-wavefronts x two column halves)
-    // are folded into one, in a fixed order.  From here on a tag also names the half: tag * 2 + half.
+    // ---- the records of (row, block).  A row has four lane streams in a block (two half-wavefronts x two column
+    // halves), 16 groups each.  hg.spb = 4: every lane stream is written as it is; 2: the half-wavefronts are folded,
+    // one record per column half; 1: all four folded into one record.  Folding keeps three groups of the folded
+    // streams' 32 or 64 per row, and a row whose best groups crowd into one record pays an exact rescan of all the
+    // record's columns in the merge: the fewer records a row has in all (large row counts: few column blocks), the
+    // less is folded.  From here on a tag also names the half: tag * 2 + half.
     constexpr int REC = 3 + 3 * L + (SAMPLE ? 8 : 0);
+    if (hg.spb == kStreamsPerBlock) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            const Stream<L> &a = st[rt];
+            const int row = row0 + (wr * 2 + rt) * 32 + l32;
+            if (row >= rows) continue;
+            float *w = part + (((size_t)row * hg.gw + col) * kStreamsPerBlock + (wv * 2 + half)) * REC;
+            w[0] = NAT ? a.mc * kLog2e : a.mc;                          // records carry the running maximum in base-2 units
+            w[1] = a.s; w[2] = a.U;
+#pragma unroll
+            for (int l = 0; l < L; ++l) { w[3 + 3 * l] = a.x[l]; w[4 + 3 * l] = a.y[l]; w[5 + 3 * l] = __int_as_float(a.tag[l] * 2 + half); }
+            if constexpr (SAMPLE) {
+                w[3 + 3 * L] = smp[rt].w1; w[4 + 3 * L] = __int_as_float(smp[rt].id1); w[5 + 3 * L] = smp[rt].w2;
+                w[6 + 3 * L] = __int_as_float(smp[rt].id2); w[7 + 3 * L] = smp[rt].w3;
+            }
+        }
+        return;
+    }
+    // fold the half-wavefronts (fixed order)
     float *xchg = reinterpret_cast<float *>(lds_raw);                      // [RT][REC + 1], free after the last barrier
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
@@ -421,6 +444,25 @@ __global__ __launch_bounds__(128 * WR, 2) void head_tile_kernel(
             if (half == 0) sample_combine(smp[rt], so);
         }
     }
+    if (hg.spb == 2) {
+        if (half == 0) {
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) {
+                const int row = row0 + (wr * 2 + rt) * 32 + l32;
+                if (row >= rows) continue;
+                float *w = part + (((size_t)row * hg.gw + col) * 2 + wv) * REC;
+                w[0] = st[rt].mc; w[1] = st[rt].s; w[2] = st[rt].U;
+#pragma unroll
+                for (int l = 0; l < L; ++l) { w[3 + 3 * l] = st[rt].x[l]; w[4 + 3 * l] = st[rt].y[l]; w[5 + 3 * l] = __int_as_float(st[rt].tag[l]); }
+                if constexpr (SAMPLE) {
+                    w[3 + 3 * L] = smp[rt].w1; w[4 + 3 * L] = __int_as_float(smp[rt].id1); w[5 + 3 * L] = smp[rt].w2;
+                    w[6 + 3 * L] = __int_as_float(smp[rt].id2); w[7 + 3 * L] = smp[rt].w3;
+                }
+            }
+        }
+        return;
+    }
+    // ... and the two column halves, through shared memory
     __syncthreads();                                                        // every wavefront is past its last operand read
     if (wv == 1 && half == 0) {
 #pragma unroll
@@ -499,7 +541,7 @@ static hipError_t launch_tile_cfg(const void *X, const uint16_t *M, float *part,
     static LdsLimit lds_limit;
     hipError_t e = lds_limit.raise(reinterpret_cast<const void *>(fn), S::LDS);
     if (e != hipSuccess) return e;
-    HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT};
+    HeadGrid hg{n_rb, gw, (V + kTNT - 1) / kTNT, streams_per_block(gw)};
     fn<<<n_rb * gw, 64 * S::NW, S::LDS, st>>>(static_cast<const uint4 *>(X), M, part, rows, rows_pad, K, V, hg, sd);
     return hipGetLastError();
 }

@@ -36,7 +36,9 @@ constexpr int kExhaustCap = kMergeThreads * 4 + SLIMSPEC_KMAX_INTERNAL;
 static_assert(kMergeThreads * 4 <= kWorkCap, "a step of the exhaustive pass appends at most kWorkCap keys");
 constexpr float kNoValue = -1.0e38f;    // stream fields at or below this are empty
 constexpr float kExactWinnersEps = 8.0e-3f;   // largest eps at which a computed winner's log-probability is reported as is
-constexpr int kGatherRound = 64;          // columns of a column-major copy evaluated per round of loads
+static_assert(kStreamsPerBlock == 4, "a record's place in its block names (column half, half-wavefront)");
+constexpr int kCrowdCap = 8;              // streams of a row whose unlisted groups are all listed member by member (more: exhaustive pass)
+constexpr int kGatherRound = 32;          // columns of a column-major copy evaluated per round of loads
 constexpr float kExhaustiveEps = 0.25f;       // from this eps on the row takes the exhaustive exact pass
 // The streams' sum of exponentials is made of computed logits; the merge replaces the terms of the logits it
 // re-evaluates, so what remains of its error is the probability-weighted mean error of all the others.  With a wide
@@ -128,6 +130,20 @@ __device__ __forceinline__ int lanes_per_item_log2(int n, int nthreads) {
     while (p < 6 && (2 * n << p) <= nthreads) ++p;
     return p;
 }
+// Slots of a shared list for the lanes of a wavefront that have `take` set: one atomic per wavefront instead of one per
+// lane (a thousand atomics on one shared-memory counter take tens of microseconds).  Every lane of the wavefront calls.
+__device__ __forceinline__ uint32_t wave_slots(uint32_t *counter, bool take, int &n_taken) {
+    const uint64_t mask = __ballot(take);
+    n_taken = __popcll(mask);
+    uint32_t base = 0u;
+    if (n_taken != 0) {
+        const int before = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+        if (take && before == 0) base = atomicAdd(counter, (uint32_t)n_taken);
+        base = (uint32_t)__shfl((int)base, __ffsll((unsigned long long)mask) - 1) + (uint32_t)before;
+    }
+    return base;
+}
+
 // rank_all_pairs with the scan for every key shared by P adjacent lanes (few keys, many threads: the ranking is a
 // chain of shared-memory reads, and P lanes make it P times shorter).  Every thread of the block must call it.
 template <class F>
@@ -180,8 +196,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     uint64_t *keys = reinterpret_cast<uint64_t *>(lds_raw);            // [n]            every listed maximum
     uint64_t *hkeys = keys + n;                                         // [ngroups * 64] the streams' largest maxima, padded with kNoKey
     uint64_t *surv = hkeys + (size_t)ngroups * 64;                      // [max(ngroups, 3) * k]  best k of every 64 heads; then the candidates for tau
-    uint64_t *work = surv + (size_t)(ngroups > 3 ? ngroups : 3) * k;    // [kExhaustCap]  final keys / fallback buffer
-    int *w_id = reinterpret_cast<int *>(work + kExhaustCap);            // [kWorkCap]
+    // (the final keys and the fallback's buffer lie over the three arrays above, which are dead by then)
+    uint64_t *work = keys;                                              // [kExhaustCap]  final keys / fallback buffer
+    const size_t n_front = (size_t)n + (size_t)ngroups * 64 + (size_t)(ngroups > 3 ? ngroups : 3) * k;
+    int *w_id = reinterpret_cast<int *>(keys + (n_front > (size_t)kExhaustCap ? n_front : (size_t)kExhaustCap));   // [kWorkCap]
     float *w_val = reinterpret_cast<float *>(w_id + kWorkCap);          // [kWorkCap]
     int *w_need = reinterpret_cast<int *>(w_val + kWorkCap);            // [kWorkCap]     0 no, 1 / 2 yes; later: list of items to evaluate
     float *w_apx = reinterpret_cast<float *>(w_need + kWorkCap);        // [kWorkCap]     change of the item's term of the sum of exp; later by rank
@@ -194,6 +212,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
     __shared__ uint64_t tau_key;
     __shared__ uint32_t cnt_surv, cnt_work, cnt_hidden, cnt_need;
     __shared__ int tau_slot, eps_violated;
+    __shared__ uint32_t cnt_crowd;                                      // streams whose best unlisted group is a candidate
+    __shared__ int crowd[kCrowdCap];
     __shared__ float mass_eval_sh;
     __shared__ uint64_t smp_wkey[NWAVES];                               // sampling: per-wavefront reductions
     __shared__ float smp_wz[NWAVES], smp_w2[NWAVES], lse_out_sh;
@@ -374,7 +394,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         return;
     }
     if (tid == 0) {
-        tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; cnt_need = 0u; tau_slot = -1; eps_violated = 0;
+        tau_key = kNoKey; cnt_surv = 0u; cnt_work = 0u; cnt_hidden = 0u; cnt_need = 0u; cnt_crowd = 0u; tau_slot = -1; eps_violated = 0;
         if (park) park[0] = 0;                              // not parked, unless decided otherwise below
     }
 
@@ -648,21 +668,43 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
             }
             const float U = r[2];
             if (U > kNoValue && mask4(U) * unit >= fminf(theta, v_mass)) {
-                // every unlisted group of the stream: record sidx covers vocabulary tiles sidx, sidx + gw, ...
-                for (int vt = sidx; vt < n_vt; vt += gw)
-                    for (int j = 0; j < 8; ++j)
-                        for (int half = 0; half < 2; ++half) {
-                            const int tag = vt * 8 + j;
-                            const int rawtag = tag * 2 + half;
-                            bool is_listed = false;
+                // every unlisted group of the stream is a candidate: the whole block lists their members below
+                const uint32_t c = atomicAdd(&cnt_crowd, 1u);
+                if (c < (uint32_t)kCrowdCap) crowd[c] = sidx;
+            }
+        }
+        __syncthreads();
+        // Column block col covers vocabulary tiles col, col + gw, ...; of a tile's 8 MFMA tiles a column half has four,
+        // of an MFMA tile's 32 columns a half-wavefront 16.  A record stands for one lane stream (column half,
+        // half-wavefront), for a column half, or for the whole block (see the head kernel): 256, 512 or 1024 columns
+        // at four tiles per block, listed by the whole merge block (one thread alone took 0.3 ms for 1000 columns).
+        const int n_crowd = (int)cnt_crowd;
+        if (n_crowd > kCrowdCap) exhaustive = true;           // (the same for every thread)
+        for (int c = 0; c < n_crowd && !exhaustive; ++c) {
+            const int sidx = crowd[c];
+            float r[REC];
+            load_rec(sidx, r);
+            int listed[L];
 #pragma unroll
-                            for (int l = 0; l < L; ++l) is_listed |= (listed[l] == rawtag);
-                            if (is_listed) continue;
-                            for (int i = 0; i < 16; ++i) {
-                                const int id = id_of(tag, i, half);
-                                if (id < V) push(id, 0.f, 1, eps_of_tile(vt));
-                            }
-                        }
+            for (int l = 0; l < L; ++l) listed[l] = (r[3 + 3 * l] > kNoValue) ? __float_as_int(r[5 + 3 * l]) : -1;
+            const int spb = nsr / gw, col = sidx / spb, sub = sidx % spb;       // 4, 2 or 1 records per column block
+            const int n_tiles = (n_vt - col + gw - 1) / gw;
+            const int per_tile = 256 / spb, sh = (spb == 4) ? 6 : (spb == 2) ? 7 : 8;
+            for (int e = tid; e < n_tiles * per_tile; e += NT) {
+                const int vt = col + (e >> sh) * gw, m = e & (per_tile - 1);
+                // spb 4: (column half, half-wavefront) = sub; 2: column half = sub, both half-wavefronts; 1: everything
+                const int half = (spb == 4) ? (sub & 1) : ((m >> 4) & 1);
+                const int j = (spb == 4) ? 4 * (sub >> 1) + ((m >> 4) & 3) : (spb == 2) ? 4 * sub + ((m >> 5) & 3) : ((m >> 5) & 7);
+                const int rawtag = (vt * 8 + j) * 2 + half;
+                bool is_listed = false;
+#pragma unroll
+                for (int l = 0; l < L; ++l) is_listed |= (listed[l] == rawtag);
+                const int id = id_of(rawtag >> 1, e & 15, rawtag & 1);
+                const bool take = !is_listed && id < V;           // (a wavefront's 64 values of e are all inside the range or all outside)
+                int n_taken;
+                const uint32_t slot = wave_slots(&cnt_work, take, n_taken);
+                if (take && slot < (uint32_t)kWorkCap) { w_id[slot] = id; w_val[slot] = 0.f; w_need[slot] = 1; w_apx[slot] = 0.f; w_eps[slot] = eps_of_tile(vt); }
+                if (lane == 0 && n_taken != 0) atomicAdd(&cnt_hidden, (uint32_t)n_taken);
             }
         }
     }
@@ -723,8 +765,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         }
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < PER; ++i)
-            if (my_need[i] >= 0) w_need[atomicAdd(&cnt_need, 1u)] = my_need[i];
+        for (int i = 0; i < PER; ++i) {
+            int n_taken;
+            const uint32_t slot = wave_slots(&cnt_need, my_need[i] >= 0, n_taken);
+            if (my_need[i] >= 0) w_need[slot] = my_need[i];
+        }
         __syncthreads();
         // No item to evaluate: the k-th listed maximum is evaluated all the same, so that every row checks the bound
         // it relied on against one exact value at least (take_exact).
@@ -761,9 +806,24 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
         const int n_need = (int)cnt_need;
         __shared__ float red_ex[NWAVES][16], red_ex16[NWAVES][16];
         const bool with16 = operand16 != 0;
-        // Column-major copy: a column is K adjacent elements.  64 columns per round; wavefront w takes columns w,
+        // Column-major copy: a column is K adjacent elements.  kGatherRound columns per round; wavefront w takes columns w,
         // w + NWAVES, ... of the round, a lane 8 adjacent elements of the column per step (K = 512: one 16-byte load
         // per lane and column, all of a wavefront's columns in flight together); lanes in order inside the DPP tree.
+        // (a lane's 8 adjacent elements of the contraction input are 32 bytes from its neighbour's: reads with shared-memory
+        // bank conflicts, so they are done once per step, not once per column, and once for all rounds when the
+        // contraction fits one step)
+        float xv[8], xv16[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { xv[e] = 0.f; xv16[e] = 0.f; }
+        const bool one_step = K <= 512;
+        if (Mt != nullptr && one_step && lane * 8 < K) {
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {                   // (xrow is 8-byte aligned)
+                const float2 x2 = *reinterpret_cast<const float2 *>(xrow + lane * 8 + e);
+                const float2 y2 = *reinterpret_cast<const float2 *>(xrow16 + lane * 8 + e);
+                xv[e] = x2.x; xv[e + 1] = x2.y; xv16[e] = y2.x; xv16[e + 1] = y2.y;
+            }
+        }
         for (int g0 = 0; Mt != nullptr && g0 < n_need; g0 += kGatherRound) {
             constexpr int CPW = kGatherRound / NWAVES;
             __shared__ float z_col[kGatherRound], z16_col[kGatherRound];
@@ -786,11 +846,13 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
 #pragma unroll
                 for (int q = 0; q < CPW; ++q)
                     if (wave + q * NWAVES < n_here) wq[q] = *reinterpret_cast<const uint4 *>(col[q] + j);
-                float xv[8];                                   // (xrow is 8-byte aligned)
+                if (!one_step) {
 #pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const float2 x2 = *reinterpret_cast<const float2 *>(xrow + j + e);
-                    xv[e] = x2.x; xv[e + 1] = x2.y;
+                    for (int e = 0; e < 8; e += 2) {
+                        const float2 x2 = *reinterpret_cast<const float2 *>(xrow + j + e);
+                        const float2 y2 = *reinterpret_cast<const float2 *>(xrow16 + j + e);
+                        xv[e] = x2.x; xv[e + 1] = x2.y; xv16[e] = y2.x; xv16[e + 1] = y2.y;
+                    }
                 }
 #pragma unroll
                 for (int q = 0; q < CPW; ++q) {
@@ -801,7 +863,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_streams_kernel(
                     for (int e = 0; e < 8; ++e) zc[q] = fmaf(xv[e], f[e], zc[q]);
                     if (round16) {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) zc16[q] = fmaf(xrow16[j + e], f[e], zc16[q]);
+                        for (int e = 0; e < 8; ++e) zc16[q] = fmaf(xv16[e], f[e], zc16[q]);
                     }
                 }
             }
@@ -949,7 +1011,8 @@ size_t merge_defer_bytes(int rows) { return sizeof(int) * kDeferRowInts * (size_
 size_t merge_streams_lds_bytes(int nsr, int k, int n_vt) {
     const size_t n = (size_t)nsr * kStreamList;
     const size_t ngroups = ((size_t)nsr + 63) / 64;
-    return sizeof(uint64_t) * (n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k + kExhaustCap) + 20u * kWorkCap
+    const size_t n_front = n + ngroups * 64 + (ngroups > 3 ? ngroups : 3) * k;
+    return sizeof(uint64_t) * (n_front > (size_t)kExhaustCap ? n_front : (size_t)kExhaustCap) + 20u * kWorkCap
            + sizeof(float) * (((size_t)(n_vt < kTsCap ? n_vt : kTsCap) + 3) & ~(size_t)3);
 }
 

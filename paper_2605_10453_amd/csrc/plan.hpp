@@ -104,6 +104,11 @@ constexpr size_t kMergeLdsLimit = 160 * 1024 - 1024;
 
 // ---- matrix-core path -------------------------------------------------------------------
 constexpr int kPlanSlotsPerXcd = 32;     // blocks per XCD of the persistent kernel (256 CUs / 8 XCDs)
+constexpr int kStreamsPerBlock = 4;      // lane streams of a row in one block of the head kernel: two half-wavefronts x two column halves
+// Records a block of the head kernel leaves per row: all four lane streams while a row then has at most 512 records
+// (many rows: few column blocks, where three listed groups per folded record would often be too few), two or one
+// where there are more column blocks (the merge's time grows with the number of records).
+inline int streams_per_block(int gw) { return gw <= 128 ? kStreamsPerBlock : gw <= 256 ? 2 : 1; }
 constexpr int kStreamListPlan = 3;       // must equal kStreamList (launch.hpp)
 constexpr int kStreamRecPlan = 3 + 3 * kStreamListPlan + 8;      // sized for sampling calls (kStreamRecSample, launch.hpp)
 
@@ -188,7 +193,7 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
     const int need = (p.n_vt + 7) / 8;
     if (colgroups > need) colgroups = need;
     p.gw = 8 * colgroups;
-    p.nsr = p.gw;          // the head kernel folds a block's streams of a row into one record
+    p.nsr = streams_per_block(p.gw) * p.gw;
     size_t off = 0;
     if (kind == HeadKind::LowRank) {
         p.off_t32 = off;       off = align_up(off + sizeof(float) * (size_t)p.rows_pad * r);
