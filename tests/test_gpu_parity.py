@@ -451,6 +451,30 @@ def test_logit_far_above_the_running_maximum(gpu, oracle_mod):
     check_low_rank(gpu, oracle_mod, x, cfg.k)
 
 
+@pytest.mark.parametrize("rows,V", [(300, 40960), (200, 70000), (20, 70000)])
+def test_four_best_logits_in_one_lane_stream(gpu, oracle_mod, rows, V):
+    """The matrix-core kernel lists three groups of 16 logits per lane stream (a row's share of four of a vocabulary
+    tile's eight 32-column MFMA tiles in one half-wavefront, over the tiles of a column block).  Here a row's four
+    largest logits sit in four different groups of one lane stream (columns 256 vt + 32 j + 4, j = 4 ... 7), so one of
+    them is dropped from the list and the merge has to rescan every column of the record that stream went into.  The
+    three shapes leave four, two and one record per row and column block (few, more, many column blocks)."""
+    cfg = synth.small_config(rows=rows, d=64, r=64, V=V, k=5, peaked_every=0)
+    x = synth.make_inputs(cfg, seed=rows + V)
+    t = synth.bf16_bits_to_f64(x.h) @ synth.bf16_bits_to_f64(x.A)
+    B = synth.bf16_bits_to_f32(x.B)
+    planted = {}
+    for n, i in enumerate((0, 7, rows - 1)):
+        vt = 1 + 2 * n
+        cols = [256 * vt + 32 * j + 4 for j in (4, 5, 6, 7)]
+        for c, alpha in zip(cols, (12.0, 11.5, 11.0, 10.5)):
+            B[:, c] = (alpha * t[i] / (t[i] @ t[i])).astype(np.float32)
+        planted[i] = cols
+    x.B = synth.f32_to_bf16_bits(B)
+    g_ids, _, ora, _ = check_low_rank(gpu, oracle_mod, x, cfg.k, exact_rows=list(planted))
+    for i, cols in planted.items():
+        assert g_ids[i, :4].tolist() == cols, (i, g_ids[i], cols)
+
+
 # ------------------------------------------------------------------ the five workloads at full size
 
 @pytest.mark.parametrize("seed", list(range(10)))

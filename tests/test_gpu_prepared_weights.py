@@ -55,6 +55,9 @@ SPECIAL = {
     "more_rows_than_one_launch": (base.test_more_rows_than_one_launch, {}),
     "few_rows_do_not_read_the_copy": (base.test_low_rank_small, dict(zip(("rows", "d", "r", "V", "k"), base.SMALL[6]))),
     "large_k_does_not_read_the_copy": (base.test_many_rows_large_k, dict(rows=20, k=17)),
+    "four_best_in_one_lane_stream_4_records": (base.test_four_best_logits_in_one_lane_stream, dict(rows=300, V=40960)),
+    "four_best_in_one_lane_stream_2_records": (base.test_four_best_logits_in_one_lane_stream, dict(rows=200, V=70000)),
+    "four_best_in_one_lane_stream_1_record": (base.test_four_best_logits_in_one_lane_stream, dict(rows=20, V=70000)),
     "C4": (base.test_config4_low_rank, dict(name="C4")),
     "C4_r256": (base.test_config4_low_rank, dict(name="C4_r256")),
     "C4_r1024": (base.test_config4_low_rank, dict(name="C4_r1024")),
