@@ -26,7 +26,7 @@ STATUS_UNSUPPORTED = -2
 STATUS_WORKSPACE_TOO_SMALL = -3
 STATUS_HIP_ERROR = -4
 STATUS_SCRATCH_LIMIT = -5
-STATIC_SCRATCH_BYTES = 32 << 20
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTED_SYMBOLS = (
     "slimspec_version", "slimspec_workspace_bytes", "slimspec_head_topk", "slimspec_transpose_weights", "slimspec_head_topk_prepared", "slimspec_head_topk_static", "full_head_topk", "truncated_head_topk", "slimspec_head_topk_positions", "slimspec_head_topk_positions_prepared", "slimspec_head_sample", "slimspec_head_sample_prepared", "full_head_sample", "routed_workspace_bytes", "routed_head_topk", "routed_head_topk_prepared",

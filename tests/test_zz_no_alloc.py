@@ -38,7 +38,7 @@ def test_static_scratch_entry_matches_workspace_entry(oracle_mod, first, second)
 def test_static_scratch_entry_refuses_what_does_not_fit():
     import torch
     from paper_2605_10453_amd import binding as b
-    rows, d, r, V, k = 4096, 8192, 2048, 8192, 10
+    rows, d, r, V, k = 4096, 8192, 4096, 65536, 10
     assert b.slimspec_workspace_bytes(rows, d, r, V, k) > b.STATIC_SCRATCH_BYTES
     dummy = torch.zeros(16, dtype=torch.bfloat16, device="cuda")
     shape = b.SlimspecShape(rows, d, r, V)
