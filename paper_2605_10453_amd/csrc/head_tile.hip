@@ -85,7 +85,7 @@ __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)
 //    beyond the last row; rows_pad a multiple of 64 WR.  NAT = false: the contraction input times log2(e), bf16
 //    (F16: f16): logits come out in base-2 units.  NAT = true: the bf16 input itself (full head): natural units.
 // M: [K][V] bf16 row-major, V and K multiples of 8
-// part: [rows][gw][3 + 3 L] stream records (values in base-2 units): one per row and block
+// part: [rows][gw * hg.spb][3 + 3 L] stream records (values in base-2 units): hg.spb = 4, 2 or 1 per row and block
 // DBG != 0 (experiment builds only, -DSLIMSPEC_DIAG_DBG=n): timing experiments (1 no epilogue, 2 loads only, 3 no loads);
 // their results are meaningless
 // SAMPLE: every lane also keeps, per row, the largest logit + Gumbel noise it has seen (Gumbel-max sampling with the

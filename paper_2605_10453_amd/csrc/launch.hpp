@@ -96,10 +96,11 @@ bool head_tile_timing_only();
 hipError_t launch_regroup_rows(const uint16_t *h, void *X, int rows, int rows_pad, int K, hipStream_t st);
 
 // stream partials -> final ids / log-probabilities, with exact fp32 re-evaluation of uncertain ranks
-// nsr records per row (= gw, the number of vocabulary-tile columns of the head kernel's grid); unit: factor from the
+// nsr records per row (4, 2 or 1 for each of the gw column blocks of the head kernel's grid); unit: factor from the
 // records' values to natural-log logits; tiny_w: magnitude below which the kernel flushed weights to zero;
 // operand16: 0 the head kernel's row operand was exact, 1 it was t log2(e) rounded to bf16, 2 to f16 (the merge then
 // recomputes, from the same rounding, the logit the head kernel saw for a column that has no recorded value);
+// Mt: null, or the column-major copy of M, [V, K] (an exact logit then reads K adjacent elements; rows are not parked);
 // defer_buf: merge_defer_bytes(rows) of scratch, or null: with it, rows that need exact re-evaluations are finished by
 // two more launches that spread the column gathers over many CUs (worth it for long contractions only)
 hipError_t launch_merge_streams(const float *part, int rows, int nsr, int gw, int n_vt,

@@ -211,9 +211,9 @@ inline MfmaPlan make_mfma_plan(HeadKind kind, int rows, int d, int r, int V) {
     p.bytes = off;
     return p;
 }
-// Rows of one launch of the matrix-core kernels.  More rows per launch would leave fewer column groups, hence fewer
-// stream records per row (gw of them), and a row whose top-k crowd into one stream pays an exact rescan of that
-// stream: at 512 rows a row still has 128 records or more.
+// Rows of one launch of the matrix-core kernels.  More rows per launch would leave fewer column blocks (gw), hence
+// fewer stream records per row, and a row whose top-k crowd into one record pays an exact rescan of that record's
+// columns: at 512 rows a row still has 128 column blocks, with four records each.
 inline int mfma_max_rows_per_launch(int rows) { return rows > 512 ? 512 : rows; }
 size_t merge_streams_lds_bytes(int nsr, int k, int n_vt);
 
