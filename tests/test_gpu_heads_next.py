@@ -76,6 +76,8 @@ def test_truncated_head_tied_columns_break_by_column(gpu, oracle_mod):
     ((64, 64, 64), 256, 64, 4104, 16),              # groups that fill their tiles; f16 operands
     ((300, 250, 50), 64, 32, 1032, 5),              # two launches: a group crosses the 512-row boundary
     ((9, 11), 128, 32, 3080, 20),                   # k beyond the matrix-core path: streaming in row groups of 8
+    ((100, 60, 40), 64, 64, 70000, 5),              # many column blocks: two records per block and row
+    ((7, 13), 64, 64, 70000, 5),                    # ... one record
 ])
 @pytest.mark.parametrize("prepared", [False, True])
 def test_position_specific_down_projections(gpu, oracle_mod, sizes, d, r, V, k, prepared):
@@ -135,6 +137,7 @@ def check_sample_outputs(torch, out, ora, seed, V, z_rows, oracle_mod):
     (1, 256, 32, 8200, 8, 1), (1, 64, 16, 140000, 5, 2 ** 40 + 17), (3, 128, 16, 5000, 6, 3), (4, 512, 64, 10248, 10, 4),
     (9, 96, 24, 2056, 7, 5), (40, 256, 32, 4104, 12, 6), (130, 64, 40, 2056, 5, 7), (20, 128, 32, 3080, 20, 8),
     (12, 64, 24, 2056, 16, 9),
+    (200, 64, 64, 70000, 5, 10), (20, 64, 64, 70000, 5, 11),       # many column blocks: two records, one record per block and row
 ])
 @pytest.mark.parametrize("prepared", [False, True])
 def test_low_rank_head_sample(gpu, oracle_mod, rows, d, r, V, k, seed, prepared):
