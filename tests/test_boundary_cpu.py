@@ -269,3 +269,29 @@ def test_prepared_sampling_and_positions_argument_validation(lib):
     assert positions([0, 4, 7]) == b.STATUS_INVALID_ARGUMENT
     assert positions([0, 4, 8], Bt=ctypes.c_void_p(0x1002)) == b.STATUS_UNSUPPORTED
     assert positions([0, 4, 8], wsb=1024) == b.STATUS_WORKSPACE_TOO_SMALL
+
+
+def test_binding_rejects_mismatched_shapes_before_any_device_call(lib):
+    """The Python binding only marshals arguments; what it checks itself (shapes, element sizes) it checks before
+    the first device call, so CPU tensors are enough here."""
+    import torch
+    _, b = lib
+    bf = torch.bfloat16
+    h, A, B = torch.zeros(5, 64, dtype=bf), torch.zeros(64, 16, dtype=bf), torch.zeros(16, 800, dtype=bf)
+    Bt_bad, W = torch.zeros(16, 800, dtype=bf), torch.zeros(64, 800, dtype=bf)
+    with pytest.raises(ValueError):
+        b.slimspec_head_topk(h, A, torch.zeros(24, 800, dtype=bf), 4)
+    with pytest.raises(ValueError):
+        b.slimspec_head_topk_prepared(h, A, B, Bt_bad, 4)                     # Bt must be [V, r]
+    with pytest.raises(ValueError):
+        b.slimspec_head_topk_prepared(h, A, B, torch.zeros(800, 16, dtype=torch.float32), 4)
+    with pytest.raises(ValueError):
+        b.slimspec_head_sample_prepared(h, A, B, Bt_bad, 4, 1)
+    with pytest.raises(ValueError):
+        b.slimspec_head_topk_positions_prepared(h, A.view(1, 64, 16), [0, 5], B, Bt_bad, 4)
+    with pytest.raises(ValueError):
+        b.routed_head_topk_prepared(h, A, B, W, 8, 4)                         # Wt must be [V, d]
+    with pytest.raises(ValueError):
+        b.slimspec_transpose_weights(torch.zeros(16, 800, dtype=torch.float32))
+    with pytest.raises(ValueError):
+        b.slimspec_transpose_weights(B, out=torch.zeros(16, 800, dtype=bf))
